@@ -1,0 +1,284 @@
+// TACO reference ("oracle"): a plain, slow CPU statement of what the fused FP8
+// compression operator computes.  TEST INFRASTRUCTURE ONLY: nothing on the product
+// path may include, link or call this file; it shares no code with the HIP kernels.
+//
+// Every function follows one passage of the TACO paper (Section 4.2 "Adaptive
+// Scale-Hadamard Transform", Section 4.3 "Dual-Scale FP8 Quantization", Algorithm 1):
+//
+//   partition      X = [G_1 .. G_M], contiguous blocks of B elements   (Eq. ash_partition)
+//   sigma_k        sqrt( (1/B) sum_j G_kj^2 + eps )                     (Eq. ash_sigma)
+//   alpha_k        tau / sigma_k                                        (Eq. ash_alpha)
+//   Z_k            (1/sqrt(B)) H_B (alpha_k G_k)                        (Eq. ash_rotation)
+//   s_k            max|Z_k| / Q_max                                     (Eq. post_scale)
+//   q_k            Cvt_FP8( Z_k / s_k )                                 (Eq. quantization)
+//   Zhat_k         Cvt_FP32(q_k) * s_k                                  (Eq. recon_dequant)
+//   Ghat_k         (1/sqrt(B)) H_B Zhat_k                               (Eq. recon_ifwht)
+//   G'_k           Ghat_k / alpha_k                                     (Eq. recon_rescale)
+//
+// Arithmetic is IEEE double.  A value is rounded to binary32 only where the method
+// stores it (alpha_k and s_k travel as fp32 scalars beside the payload, Section 4.3
+// "Dual-Scale Reconstruction"), and the stored value is what every later step reads.
+// The rotation is the explicit B x B matrix product with
+// H[i][j] = (-1)^popcount(i & j) (natural / Sylvester order); no fast transform, no
+// blocking, no reordering.  OpenMP, when enabled, splits the loop over blocks only.
+//
+// Readings taken where the paper is silent (all listed in the design notes):
+//   * FP8 is E4M3 in the OCP 8-bit floating point layout: 1 sign, 4 exponent (bias 7),
+//     3 mantissa bits, subnormals, no infinities, S.1111.111 = NaN, Q_max = 448
+//     (Section 5.3 format ablation selects E4M3; Section 2.3 gives the generic form).
+//   * Cvt_FP8 rounds to nearest, ties to even, and saturates to +-448.
+//   * A block whose rotated maximum is zero stores s_k = 0 and all-zero codes.
+//   * The last block is zero padded when N is not a multiple of B; sigma still divides by B.
+//   * The reduction of k decoded payloads accumulates in double, payload index ascending,
+//     and rounds once to bf16 (via binary32), Section 4.4.2 "single local reduction".
+//
+// Pins: see tests/test_oracle_*.py (exhaustive E4M3 table against an independent
+// library decode, H H^T = B I and a library Hadamard matrix, closed forms for the
+// all-zero, single-outlier and constant blocks, brute-force scales, error bound).
+// Parity unpinned: the paper prints no worked numeric example, so the choice of tau,
+// eps, Hadamard ordering and payload layout is pinned only against this file.
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+namespace {
+
+constexpr double kQmax = 448.0;  // largest finite E4M3 magnitude (S.1111.110)
+
+// ---- bf16 <-> double -------------------------------------------------------------------
+
+double bf16_to_double(uint16_t h) {
+    uint32_t u = static_cast<uint32_t>(h) << 16;
+    float f;
+    std::memcpy(&f, &u, sizeof f);
+    return static_cast<double>(f);
+}
+
+// binary32 -> bf16, round to nearest, ties to even.  NaN keeps a quiet payload.
+uint16_t float_to_bf16(float f) {
+    uint32_t u;
+    std::memcpy(&u, &f, sizeof u);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x0040u);
+    uint32_t keep = u >> 16;
+    uint32_t rest = u & 0xffffu;
+    if (rest > 0x8000u || (rest == 0x8000u && (keep & 1u))) keep += 1;
+    return static_cast<uint16_t>(keep);
+}
+
+// ---- FP8 E4M3 ----------------------------------------------------------------------------
+
+// Value of an 8-bit code  s eeee mmm :
+//   e == 0          (m/8)      * 2^-6      (zero and subnormals, step 2^-9)
+//   e == 15, m == 7 NaN
+//   otherwise       (1 + m/8)  * 2^(e-7)
+double e4m3_decode(uint8_t code) {
+    int sign = code >> 7;
+    int e = (code >> 3) & 0xf;
+    int m = code & 0x7;
+    double mag;
+    if (e == 0xf && m == 0x7) return std::nan("");
+    if (e == 0)
+        mag = std::ldexp(static_cast<double>(m), -9);
+    else
+        mag = std::ldexp(8.0 + static_cast<double>(m), e - 10);
+    return sign ? -mag : mag;
+}
+
+// Round an exact non-negative double to an integer, ties to the even integer.
+double round_half_even(double v) {
+    double fl = std::floor(v);
+    double diff = v - fl;  // exact for the magnitudes used here (v < 2^10)
+    if (diff > 0.5) return fl + 1.0;
+    if (diff < 0.5) return fl;
+    return (std::fmod(fl, 2.0) == 0.0) ? fl : fl + 1.0;
+}
+
+// Nearest E4M3 code, ties to even mantissa, saturating at +-448, sign kept on underflow.
+uint8_t e4m3_encode(double v) {
+    if (std::isnan(v)) return 0x7f;
+    uint8_t sign = std::signbit(v) ? 0x80 : 0x00;
+    double a = std::fabs(v);
+    if (a >= kQmax) return sign | 0x7e;  // covers +-inf and every overshoot
+    // Spacing of the grid around a: 2^-9 below 2^-6, else 2^(floor(log2 a) - 3).
+    int ex;
+    std::frexp(a, &ex);        // a = f * 2^ex, f in [0.5, 1)  =>  floor(log2 a) = ex - 1
+    int p = (a < std::ldexp(1.0, -6)) ? -6 : ex - 1;
+    double steps = round_half_even(std::ldexp(a, 3 - p));  // a in units of the local step
+    // steps is in [0, 8] for subnormals, [8, 16] for normals; 16 carries into the next binade.
+    int code;
+    if (p == -6 && steps < 8.0) {
+        code = static_cast<int>(steps);  // exponent field 0
+    } else {
+        if (steps == 16.0) { steps = 8.0; p += 1; }
+        code = ((p + 7) << 3) | (static_cast<int>(steps) - 8);
+    }
+    if (code > 0x7e) code = 0x7e;
+    return sign | static_cast<uint8_t>(code);
+}
+
+// ---- Hadamard matrix -----------------------------------------------------------------------
+
+bool is_pow2(int64_t b) { return b >= 1 && (b & (b - 1)) == 0; }
+
+int parity_of(unsigned v) {
+    int p = 0;
+    while (v) { p ^= 1; v &= v - 1; }
+    return p;
+}
+
+// Row-major B x B matrix of +-1: H[i][j] = (-1)^popcount(i & j).
+void fill_hadamard(int B, std::vector<double>& H) {
+    H.resize(static_cast<size_t>(B) * B);
+    for (int i = 0; i < B; ++i)
+        for (int j = 0; j < B; ++j)
+            H[static_cast<size_t>(i) * B + j] = parity_of(static_cast<unsigned>(i & j)) ? -1.0 : 1.0;
+}
+
+// y = H x (no normalisation), plain matrix-vector product.
+void matvec(const std::vector<double>& H, int B, const double* x, double* y) {
+    for (int i = 0; i < B; ++i) {
+        const double* row = &H[static_cast<size_t>(i) * B];
+        double acc = 0.0;
+        for (int j = 0; j < B; ++j) acc += row[j] * x[j];
+        y[i] = acc;
+    }
+}
+
+// Decode one block of one payload into g'[0..B): Eqs. recon_dequant, recon_ifwht, recon_rescale.
+void decode_block(const std::vector<double>& H, int B, const uint8_t* codes, float alpha_f,
+                  float s_f, double* zhat, double* gprime) {
+    const double alpha = static_cast<double>(alpha_f);
+    const double s = static_cast<double>(s_f);
+    const double root_b = std::sqrt(static_cast<double>(B));
+    for (int i = 0; i < B; ++i) zhat[i] = e4m3_decode(codes[i]) * s;
+    matvec(H, B, zhat, gprime);
+    for (int j = 0; j < B; ++j) gprime[j] = (gprime[j] / root_b) / alpha;
+}
+
+}  // namespace
+
+extern "C" {
+
+enum { TACO_REF_OK = 0, TACO_REF_ERR_ARG = -1 };
+
+double taco_ref_e4m3_decode(uint8_t code) { return e4m3_decode(code); }
+uint8_t taco_ref_e4m3_encode(double v) { return e4m3_encode(v); }
+uint16_t taco_ref_float_to_bf16(float f) { return float_to_bf16(f); }
+
+// H (row-major, B*B doubles).
+int taco_ref_hadamard_matrix(int32_t block, double* H_out) {
+    if (!H_out || !is_pow2(block)) return TACO_REF_ERR_ARG;
+    std::vector<double> H;
+    fill_hadamard(block, H);
+    std::memcpy(H_out, H.data(), H.size() * sizeof(double));
+    return TACO_REF_OK;
+}
+
+// y = (1/sqrt(B)) H_B x : the orthonormal rotation of Eq. ash_rotation on one block.
+int taco_ref_rotate(const double* x, int32_t block, double* y) {
+    if (!x || !y || !is_pow2(block)) return TACO_REF_ERR_ARG;
+    std::vector<double> H;
+    fill_hadamard(block, H);
+    matvec(H, block, x, y);
+    const double root_b = std::sqrt(static_cast<double>(block));
+    for (int i = 0; i < block; ++i) y[i] /= root_b;
+    return TACO_REF_OK;
+}
+
+// Sender side of Algorithm 1.  x: n bf16 values (host).  payload: ceil(n/B)*B codes.
+// scales: ceil(n/B) pairs {alpha_k, s_k} as fp32.  z_out (optional, may be null):
+// ceil(n/B)*B doubles receiving the rotated values Z_k before quantisation.
+int taco_ref_compress(const uint16_t* x, int64_t n, int32_t block, float tau_f, float eps_f,
+                      uint8_t* payload, float* scales, double* z_out) {
+    if (!x || !payload || !scales || n <= 0 || !is_pow2(block) || block < 2) return TACO_REF_ERR_ARG;
+    const int B = block;
+    const int64_t M = (n + B - 1) / B;
+    const double tau = static_cast<double>(tau_f);
+    const double eps = static_cast<double>(eps_f);
+    const double root_b = std::sqrt(static_cast<double>(B));
+    std::vector<double> H;
+    fill_hadamard(B, H);
+
+#pragma omp parallel
+    {
+        std::vector<double> g(B), w(B), z(B);
+#pragma omp for schedule(static)
+        for (int64_t k = 0; k < M; ++k) {
+            // Eq. ash_partition: block k holds elements [kB, (k+1)B); zeros past n.
+            for (int j = 0; j < B; ++j) {
+                int64_t idx = k * B + j;
+                g[j] = idx < n ? bf16_to_double(x[idx]) : 0.0;
+            }
+            // Eq. ash_sigma, Eq. ash_alpha.
+            double energy = 0.0;
+            for (int j = 0; j < B; ++j) energy += g[j] * g[j];
+            const double sigma = std::sqrt(energy / B + eps);
+            const float alpha_f = static_cast<float>(tau / sigma);
+            const double alpha = static_cast<double>(alpha_f);
+            // Rescale, then Eq. ash_rotation.
+            for (int j = 0; j < B; ++j) g[j] = alpha * g[j];
+            matvec(H, B, g.data(), w.data());
+            double amax = 0.0;
+            for (int i = 0; i < B; ++i) {
+                z[i] = w[i] / root_b;
+                amax = std::fmax(amax, std::fabs(z[i]));
+            }
+            // Eq. post_scale, Eq. quantization.
+            const float s_f = static_cast<float>(amax / kQmax);
+            const double s = static_cast<double>(s_f);
+            uint8_t* q = payload + k * B;
+            for (int i = 0; i < B; ++i) q[i] = (s_f == 0.0f) ? 0x00 : e4m3_encode(z[i] / s);
+            scales[2 * k + 0] = alpha_f;
+            scales[2 * k + 1] = s_f;
+            if (z_out) std::memcpy(z_out + k * B, z.data(), sizeof(double) * B);
+        }
+    }
+    return TACO_REF_OK;
+}
+
+// Receiver side of Algorithm 1 followed by the local reduction over k payloads:
+// out[j] = bf16( fp32( sum_i G'^(i)_j ) ).  k = 1 is plain decompression.
+// sum_out (optional): n doubles receiving the unrounded sum.
+int taco_ref_decompress_sum(const uint8_t* const* payloads, const float* const* scales, int32_t k,
+                            int64_t n, int32_t block, uint16_t* out, double* sum_out) {
+    if (!payloads || !scales || !out || k < 1 || n <= 0 || !is_pow2(block) || block < 2)
+        return TACO_REF_ERR_ARG;
+    for (int i = 0; i < k; ++i)
+        if (!payloads[i] || !scales[i]) return TACO_REF_ERR_ARG;
+    const int B = block;
+    const int64_t M = (n + B - 1) / B;
+    std::vector<double> H;
+    fill_hadamard(B, H);
+
+#pragma omp parallel
+    {
+        std::vector<double> zhat(B), gp(B), acc(B);
+#pragma omp for schedule(static)
+        for (int64_t b = 0; b < M; ++b) {
+            for (int j = 0; j < B; ++j) acc[j] = 0.0;
+            for (int i = 0; i < k; ++i) {
+                decode_block(H, B, payloads[i] + b * B, scales[i][2 * b], scales[i][2 * b + 1],
+                             zhat.data(), gp.data());
+                for (int j = 0; j < B; ++j) acc[j] += gp[j];
+            }
+            for (int j = 0; j < B; ++j) {
+                int64_t idx = b * B + j;
+                if (idx >= n) break;
+                if (sum_out) sum_out[idx] = acc[j];
+                out[idx] = float_to_bf16(static_cast<float>(acc[j]));
+            }
+        }
+    }
+    return TACO_REF_OK;
+}
+
+int taco_ref_decompress(const uint8_t* payload, const float* scales, int64_t n, int32_t block,
+                        uint16_t* out, double* sum_out) {
+    const uint8_t* p[1] = {payload};
+    const float* s[1] = {scales};
+    return taco_ref_decompress_sum(p, s, 1, n, block, out, sum_out);
+}
+
+}  // extern "C"

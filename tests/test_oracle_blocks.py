@@ -1,0 +1,200 @@
+"""Pins for the oracle's sender side (Algorithm 1, Eqs. ash_sigma .. quantization):
+closed forms for degenerate blocks, a block worked by hand, brute-force recomputation of
+both scale levels with library routines, and the invariants the paper states."""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.linalg
+import torch
+
+from paper_2604_24088_amd import workloads as W
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+QMAX = 448.0
+F32 = np.float32
+
+
+def bits(x):
+    return W.float32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+
+
+def vals(b):
+    return W.bf16_bits_to_float32(b).astype(np.float64)
+
+
+def parity(v):
+    return bin(v).count("1") & 1
+
+
+# ---- hand-worked block -------------------------------------------------------------------
+
+def test_worked_block_b4_golden(oracle):
+    rec = {}
+    for line in open(os.path.join(GOLD, "worked_block_b4.txt")):
+        if line.strip() and line[0] != "#":
+            key, *rest = line.split()
+            rec[key] = rest
+    x = bits([float(t) for t in rec["input"]])
+    payload, scales = oracle.compress(x, block=4, tau=1.0, eps=0.0)
+    assert list(payload) == [int(t, 16) for t in rec["codes"]]
+    assert scales[0, 0] == F32(float(rec["alpha"][0]))
+    assert abs(float(scales[0, 1]) / float(rec["s"][0]) - 1.0) < 2.0 ** -23
+    out = vals(oracle.decompress(payload, scales, 4, block=4))
+    assert list(out) == [float(t) for t in rec["output"]]
+
+
+# ---- closed forms ------------------------------------------------------------------------
+
+@pytest.mark.parametrize("B", [32, 128, 256])
+def test_all_zero_block(oracle, B):
+    tau, eps = 1.0, 1e-12
+    payload, scales = oracle.compress(bits(np.zeros(2 * B)), block=B, tau=tau, eps=eps)
+    assert np.all(payload == 0)
+    assert np.all(scales[:, 1] == 0.0)
+    expect_alpha = F32(tau / math.sqrt(float(F32(eps))))
+    assert np.all(scales[:, 0] == expect_alpha)
+    out = oracle.decompress(payload, scales, 2 * B, block=B)
+    assert np.all(out == 0)                      # +0 bit pattern
+
+
+@pytest.mark.parametrize("B,j,a", [(128, 0, 1.5), (128, 77, -0.0234375), (256, 201, 96.0), (32, 31, -2.0 ** -20)])
+def test_single_outlier_block(oracle, B, j, a):
+    """G = a e_j: every |Z_i| equals alpha |a| / sqrt(B), so s = alpha |a| / (Q_max sqrt(B)),
+    every code is +-Q_max with the sign of a (-1)^popcount(i & j), and the reconstruction is
+    a at j and exactly zero elsewhere."""
+    tau, eps = 1.0, 1e-12
+    g = np.zeros(B)
+    g[j] = a
+    payload, scales = oracle.compress(bits(g), block=B, tau=tau, eps=eps)
+    alpha, s = float(scales[0, 0]), float(scales[0, 1])
+    assert alpha == F32(tau / math.sqrt(a * a / B + float(F32(eps))))
+    assert s == F32(alpha * abs(a) / math.sqrt(B) / QMAX)
+    sigma2 = a * a / B + float(F32(eps))
+    lower = tau * math.sqrt(1.0 - float(F32(eps)) / sigma2) / QMAX       # lower end of the range of s
+    assert abs(s / lower - 1.0) < 1e-6
+    for i in range(B):
+        neg = (a < 0) ^ bool(parity(i & j))
+        assert payload[i] == (0xFE if neg else 0x7E), i
+    out = vals(oracle.decompress(payload, scales, B, block=B))
+    assert out[j] == a
+    assert np.all(np.delete(out, j) == 0.0)
+
+
+@pytest.mark.parametrize("B,c", [(128, 0.0078125), (256, -3.0), (64, 1e-3)])
+def test_constant_block(oracle, B, c):
+    """G = c 1: Z = alpha c sqrt(B) e_0, so s reaches its upper end tau sqrt(B) / Q_max."""
+    tau, eps = 1.0, 1e-12
+    cb = float(vals(bits([c]))[0])
+    payload, scales = oracle.compress(bits(np.full(B, c)), block=B, tau=tau, eps=eps)
+    alpha, s = float(scales[0, 0]), float(scales[0, 1])
+    assert alpha == F32(tau / math.sqrt(cb * cb + float(F32(eps))))
+    assert s == F32(alpha * abs(cb) * math.sqrt(B) / QMAX)
+    assert abs(s / (tau * math.sqrt(B) / QMAX) - 1.0) < 1e-5
+    assert payload[0] == (0xFE if c < 0 else 0x7E)
+    assert np.all(payload[1:] & 0x7F == 0)
+    out = vals(oracle.decompress(payload, scales, B, block=B))
+    assert np.all(out == cb)
+
+
+# ---- brute force with library routines ---------------------------------------------------
+
+@pytest.mark.parametrize("B", [8, 32, 128, 256, 512])
+def test_scales_and_codes_against_library_recomputation(oracle, B):
+    rng = np.random.default_rng(100 + B)
+    M = 24
+    x = rng.standard_t(3.0, size=M * B) * 0.01
+    x[rng.integers(0, M * B, 5)] *= 200.0
+    xb = bits(x)
+    tau, eps = 1.0, 1e-12
+    payload, scales, z = oracle.compress(xb, block=B, tau=tau, eps=eps, want_z=True)
+    g = vals(xb).astype(np.longdouble).reshape(M, B)
+    H = scipy.linalg.hadamard(B).astype(np.longdouble)
+    epsl = np.longdouble(float(F32(eps)))
+    for k in range(M):
+        sigma = np.sqrt(np.sum(g[k] * g[k]) / B + epsl)
+        alpha = F32(float(np.longdouble(tau) / sigma))
+        assert scales[k, 0] == alpha
+        zk = H @ (np.longdouble(float(alpha)) * g[k]) / np.sqrt(np.longdouble(B))
+        assert np.allclose(z[k * B:(k + 1) * B], zk.astype(np.float64), rtol=1e-13, atol=1e-15)
+        s = F32(float(np.max(np.abs(zk)) / QMAX))
+        assert abs(float(scales[k, 1]) / float(s) - 1.0) <= 2.0 ** -23
+        # Codes: library cast of Z/s (the oracle's own Z and s, so only the conversion is pinned here).
+        ratio = (z[k * B:(k + 1) * B] / float(scales[k, 1]))
+        lib = torch.from_numpy(np.clip(ratio, -QMAX, QMAX).astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        mine = payload[k * B:(k + 1) * B]
+        diff = mine != lib
+        # double -> fp32 -> fp8 may double-round; it cannot move a code by more than one step.
+        assert diff.mean() <= 0.01
+        assert np.all(np.abs(mine[diff].astype(int) - lib[diff].astype(int)) <= 1)
+
+
+# ---- invariants ----------------------------------------------------------------------------
+
+def test_tau_scaling_leaves_codes_alone(oracle):
+    w = W.WORKLOADS["tiny"]
+    x = W.generate_rows(w, 0, 0, 16)
+    p1, s1 = oracle.compress(x, block=128, tau=1.0, eps=0.0)
+    p2, s2 = oracle.compress(x, block=128, tau=2.0, eps=0.0)
+    assert np.array_equal(p1, p2)
+    assert np.array_equal(s2[:, 0], 2.0 * s1[:, 0])
+    assert np.allclose(s2[:, 1], 2.0 * s1[:, 1], rtol=2.0 ** -22, atol=0)
+
+
+@pytest.mark.parametrize("name", ["tiny", "qwen_act", "bwd_grad"])
+def test_range_energy_and_scale_bounds(oracle, name):
+    w = W.WORKLOADS[name]
+    B, tau, eps = 128, 1.0, 1e-12
+    x = W.generate_rows(w, 0, 0, 8)
+    payload, scales, z = oracle.compress(x, block=B, tau=tau, eps=eps, want_z=True)
+    g = vals(x).reshape(-1, B)
+    z = z.reshape(-1, B)
+    codes = payload.reshape(-1, B)
+    alpha, s = scales[:, 0].astype(np.float64), scales[:, 1].astype(np.float64)
+    energy = np.sum(g * g, axis=1)
+    sigma = np.sqrt(energy / B + float(F32(eps)))
+    assert np.allclose(alpha * sigma, tau, rtol=1e-7)                        # alpha sigma = tau
+    assert np.allclose(np.sum(z * z, axis=1), alpha ** 2 * energy, rtol=1e-12)  # rotation keeps energy
+    nz = energy > 0
+    lower = tau * np.sqrt(1.0 - float(F32(eps)) / sigma ** 2) / QMAX
+    upper = tau * math.sqrt(B) / QMAX
+    assert np.all(s[nz] >= lower[nz] * (1 - 1e-6)) and np.all(s[nz] <= upper * (1 + 1e-6))
+    assert not np.any((codes & 0x7F) == 0x7F)                                # never NaN
+    assert np.all(np.max(codes[nz] & 0x7F, axis=1) == 0x7E)                  # block max maps to Q_max
+    ratio = np.abs(z[nz]) / s[nz, None]
+    assert np.all(ratio <= QMAX * (1 + 2.0 ** -23))                          # strictly inside the range
+
+
+def test_blocks_are_independent_and_flat(oracle):
+    """The tensor is flattened row-major and cut into contiguous blocks (Eq. ash_partition):
+    compressing a concatenation equals concatenating compressions, whatever the row length."""
+    rng = np.random.default_rng(2)
+    B = 128
+    x = bits(rng.standard_normal(6 * B) * 0.02)
+    p_all, s_all = oracle.compress(x.reshape(4, 192), block=B)     # rows straddle blocks
+    for k in range(6):
+        p, s = oracle.compress(x[k * B:(k + 1) * B], block=B)
+        assert np.array_equal(p, p_all[k * B:(k + 1) * B])
+        assert np.array_equal(s[0], s_all[k])
+
+
+def test_ragged_tail_is_zero_padded(oracle):
+    rng = np.random.default_rng(8)
+    B, n = 128, 3 * 128 + 5
+    x = bits(rng.standard_normal(n) * 0.02)
+    padded = np.concatenate([x, np.zeros(4 * B - n, dtype=np.uint16)])
+    p1, s1 = oracle.compress(x, block=B)
+    p2, s2 = oracle.compress(padded, block=B)
+    assert p1.size == 4 * B and np.array_equal(p1, p2) and np.array_equal(s1, s2)
+    o1 = oracle.decompress(p1, s1, n, block=B)
+    o2 = oracle.decompress(p2, s2, 4 * B, block=B)
+    assert o1.size == n and np.array_equal(o1, o2[:n])
+
+
+def test_bad_arguments_are_rejected(oracle):
+    x = bits(np.ones(128))
+    with pytest.raises(ValueError):
+        oracle.compress(x, block=96)
+    with pytest.raises(ValueError):
+        oracle.compress(np.zeros(0, dtype=np.uint16), block=128)
