@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Throughput of the TACO fused FP8 compression operator on one MI355X.
+
+One STEP is one pass of the whole hot path over one batch of synthetic input:
+    k x taco_compress  ->  taco_decompress (payload 0)  ->  taco_decompress_sum (all k)
+on the `large_k8` workload (bf16 [16384, 12288], k = 8 payloads, block 128): the largest
+single-GPU configuration, and the one whose buffers (3 GiB of inputs) cannot sit in the
+256 MB last-level cache.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line (see the design doc for every field).  `value` counts bf16-equivalent
+bytes: 2N per compressed tensor, 2N per decompressed tensor, k*2N for decompress_sum
+(k tensors decoded); `value_out_basis` counts only bf16 bytes that really cross HBM.
+The roofline object prices the dominant kernel (compress) by its ALGORITHMIC bytes
+(3.0625 B per element at block 128) over its average launch duration, measured with
+HIP events on the launch stream inside the timed region.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
+
+# HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE runs, scaled by a copy kernel of known size); None until measured.  The summary
+# the number comes from is committed under profiles/.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="large_k8")
+    ap.add_argument("--block", type=int, default=128)
+    ap.add_argument("--impl", default="auto", choices=["auto", "butterfly", "mfma"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gen-threads", type=int, default=16)
+    return ap.parse_args()
+
+
+def cpu_baseline(w, block, rows):
+    """The oracle, as it stands, on the first `rows` tokens of every payload, same call mix as a step."""
+    import numpy as np
+    from oracle import taco_ref
+    from paper_2604_24088_amd import workloads as W
+    xs = [W.generate_rows(w, i, 0, rows) for i in range(w.payloads)]
+    n = rows * w.hidden
+    t0 = time.perf_counter()
+    enc = [taco_ref.compress(x, block=block) for x in xs]
+    taco_ref.decompress(enc[0][0], enc[0][1], n, block=block)
+    taco_ref.decompress_sum([e[0] for e in enc], [e[1] for e in enc], n, block=block)
+    dt = time.perf_counter() - t0
+    k = w.payloads
+    bf16_bytes = (k + 1 + k) * 2 * n
+    return {"value": bf16_bytes / dt / 1e9, "unit": "GB/s", "cores": taco_ref.threads(), "kind": "oracle",
+            "sample": f"first {rows} of {w.tokens} tokens of each of the {k} payloads, same call mix as one step "
+                      f"({dt:.1f} s)"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the operator is block-local; see DESIGN.md on sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2604_24088_amd import taco
+    from paper_2604_24088_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    taco.lib()   # fail loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    w = W.WORKLOADS[args.workload]
+    k, n, B = w.payloads, w.numel, args.block
+    impl = {"auto": taco.TACO_IMPL_AUTO, "butterfly": taco.TACO_IMPL_BUTTERFLY, "mfma": taco.TACO_IMPL_MFMA}[args.impl]
+    params = taco.taco_default_params(block=B, impl=impl)
+
+    # ---- synthetic inputs, resident in HBM
+    host = np.empty((w.tokens, w.hidden), dtype=np.uint16)
+    xs = []
+    for i in range(k):
+        W.generate(w, i, threads=args.gen_threads, out=host)
+        xs.append(torch.from_numpy(host.view(np.int16)).to(dev).view(torch.bfloat16))
+    del host
+    payloads = [torch.empty(taco.taco_payload_bytes(n, B), dtype=torch.uint8, device=dev) for _ in range(k)]
+    scales = [torch.empty((taco.taco_scales_bytes(n, B) // 8, 2), dtype=torch.float32, device=dev) for _ in range(k)]
+    out1 = torch.empty((w.tokens, w.hidden), dtype=torch.bfloat16, device=dev)
+    outk = torch.empty((w.tokens, w.hidden), dtype=torch.bfloat16, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(ev=None):
+        if ev:
+            ev[0].record(stream)
+        for i in range(k):
+            taco.taco_compress(xs[i], params, payloads[i], scales[i], stream)
+        if ev:
+            ev[1].record(stream)
+        taco.taco_decompress(payloads[0], scales[0], out1.shape, params, out1, stream)
+        if ev:
+            ev[2].record(stream)
+        taco.taco_decompress_sum(payloads, scales, outk.shape, params, outk, stream)
+        if ev:
+            ev[3].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(events[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_step = wall * 1e3 / args.steps
+    t_comp = sum(e[0].elapsed_time(e[1]) for e in events) / (args.steps * k)   # ms per compress launch
+    t_dec = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    t_sum = sum(e[2].elapsed_time(e[3]) for e in events) / args.steps
+
+    per_elem = 1.0 + 8.0 / B                         # payload bytes per element: code + two fp32 per block
+    bytes_comp = (2.0 + per_elem) * n                # algorithmic bytes of one compress launch
+    bytes_dec = (per_elem + 2.0) * n
+    bytes_sum = (k * per_elem + 2.0) * n
+    equiv = (k + 1 + k) * 2.0 * n                    # bf16-equivalent bytes per step
+    real_bf16 = (k + 1 + 1) * 2.0 * n                # bf16 bytes that cross HBM per step
+    moved = k * bytes_comp + bytes_dec + bytes_sum
+
+    def call(ms, alg_bytes, bf16_bytes):
+        return {"ms": round(ms, 4), "moved_GBps": round(alg_bytes / ms / 1e6, 1),
+                "bf16_GBps": round(bf16_bytes / ms / 1e6, 1), "hbm_frac": round(alg_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+
+    achieved = bytes_comp / t_comp / 1e6
+    result = {
+        "metric": "compress+decompress GB/s of bf16 input and % of HBM peak, 1xMI355X",
+        "value": round(equiv / (ms_step * 1e6), 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16->fp8_e4m3 (fp32 arithmetic)",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: bf16 [{w.tokens}, {w.hidden}] x {k} payloads, block {B}, "
+                               f"step = {k} compress + 1 decompress + 1 decompress_sum(k={k})",
+                   "impl": args.impl, "block": B},
+        "value_out_basis": round(real_bf16 / (ms_step * 1e6), 1),
+        "moved_GBps": round(moved / (ms_step * 1e6), 1),
+        "hbm_frac_step": round(moved / (ms_step * 1e6) / HBM_PEAK_GBPS, 4),
+        "calls": {"compress": call(t_comp, bytes_comp, 2.0 * n),
+                  "decompress": call(t_dec, bytes_dec, 2.0 * n),
+                  f"decompress_sum_k{k}": call(t_sum, bytes_sum, k * 2.0 * n)},
+        "roofline": {"kernel": "compress_b128_mfma_kernel" if (B == 128 and args.impl != "butterfly") else "compress_butterfly_kernel",
+                     "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, B, args.impl)),
+                     "alg_bytes_per_launch": bytes_comp, "avg_launch_ms": round(t_comp, 4)},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, B, rows=max(w.tokens // 8, 64))
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,125 @@
+/*
+ * taco.h - C ABI of the MI355X (gfx950) implementation of the TACO fused FP8
+ * compression operator for tensor-parallel intermediate tensors.
+ *
+ * The operator is the one the TACO paper defines in Section 4 ("Design of TACO"):
+ *   - the flattened bf16 tensor is cut into contiguous blocks of B elements
+ *     (Section 4.2.2, Eq. ash_partition);
+ *   - each block is rescaled by alpha_k = tau / sigma_k, sigma_k its RMS with eps inside
+ *     the root (Eq. ash_sigma, Eq. ash_alpha), and rotated by the orthonormal Hadamard
+ *     matrix (Eq. ash_rotation): together the Adaptive Scale-Hadamard transform;
+ *   - Dual-Scale quantisation (Section 4.3): s_k = max|Z_k| / Q_max (Eq. post_scale),
+ *     codes = Cvt_FP8(Z_k / s_k) (Eq. quantization);
+ *   - the receiver undoes the three steps in reverse order (Eqs. recon_dequant,
+ *     recon_ifwht, recon_rescale), in one fused kernel (Section 4.4.1);
+ *   - k decoded payloads are added in one local reduction (Section 4.4.2, the
+ *     ReduceScatter half of the two-shot AllReduce).
+ * Algorithm 1 of the paper lists the sender and receiver sides step by step.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller; the library allocates
+ *     nothing, keeps no state and never synchronises.  `stream` is a hipStream_t (NULL =
+ *     the default stream); each call enqueues its kernels on it and returns.
+ *   - Inputs and outputs must not overlap.  Data pointers must be 16-byte aligned.
+ *   - A tensor of `rows` x `cols` bf16 values is row-major and is treated as the flat
+ *     vector of n = rows*cols elements; blocks may straddle rows.  When n is not a
+ *     multiple of B the last block is zero padded (sigma still divides by B).
+ *   - FP8 is E4M3 in the OCP 8-bit layout (1 sign, 4 exponent bits with bias 7, 3
+ *     mantissa bits, subnormals, no infinities, Q_max = 448), round to nearest even.
+ *   - Hadamard matrix: natural (Sylvester) order, H[i][j] = (-1)^popcount(i & j).
+ *   - Payload layout: ceil(n/B)*B one-byte codes, code i of block k at byte k*B + i.
+ *     Scales layout: ceil(n/B) records { float alpha_k; float s_k; }.
+ *     The two regions may be adjacent parts of one allocation (the paper's contiguous
+ *     metadata placement, Section 4.4.2, in structure-of-arrays form).
+ *   - A block whose rotated maximum is zero stores s_k = 0 and zero codes (sign bits
+ *     of the codes are unspecified) and decodes to zeros.
+ *   - Non-finite inputs are outside the contract.
+ *   - Return value: TACO_OK (0) or a negative taco_status.  Argument errors are found on
+ *     the host before anything is launched.
+ */
+#ifndef TACO_H_
+#define TACO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TACO_MAX_K 16 /* most payloads one taco_decompress_sum call can add */
+
+typedef enum taco_status {
+    TACO_OK = 0,
+    TACO_ERR_NULL = -1,   /* a required pointer is NULL                               */
+    TACO_ERR_SHAPE = -2,  /* rows <= 0, cols <= 0 or rows*cols overflows 2^40        */
+    TACO_ERR_BLOCK = -3,  /* block is not one of 32, 64, 128, 256, 512                */
+    TACO_ERR_ALIGN = -4,  /* a data pointer is not 16-byte aligned                    */
+    TACO_ERR_K = -5,      /* k outside 1..TACO_MAX_K                                  */
+    TACO_ERR_FORMAT = -6, /* params->format is not TACO_FORMAT_E4M3                   */
+    TACO_ERR_LAUNCH = -7, /* the HIP runtime refused the launch (hipGetLastError)     */
+    TACO_ERR_IMPL = -8,   /* params->impl names a kernel that cannot run this shape   */
+    TACO_ERR_PARAM = -9   /* tau <= 0, eps < 0, or a non-finite parameter             */
+} taco_status;
+
+enum { TACO_FORMAT_E4M3 = 0 };
+
+/* Kernel selection.  AUTO picks the matrix-core kernel when the block size has one and
+ * the plain butterfly kernel otherwise; the other two values force one of them (used by
+ * tests and benchmarks to compare the two). */
+enum { TACO_IMPL_AUTO = 0, TACO_IMPL_BUTTERFLY = 1, TACO_IMPL_MFMA = 2 };
+
+/* Hyper-parameters of Algorithm 1 ("Require" line): block size B, target energy tau,
+ * stabiliser eps; Q_max follows from the format. */
+typedef struct taco_params {
+    int32_t block;  /* B: 32, 64, 128, 256 or 512                                  */
+    float tau;      /* tau of Eq. ash_alpha, > 0 (the paper gives no value; 1.0f)  */
+    float eps;      /* eps of Eq. ash_sigma, >= 0 (the paper gives no value; 1e-12f) */
+    int32_t format; /* TACO_FORMAT_E4M3                                            */
+    int32_t impl;   /* TACO_IMPL_*                                                 */
+} taco_params;
+
+/* Fills *p with B = 128, tau = 1, eps = 1e-12, E4M3, AUTO. */
+void taco_default_params(taco_params* p);
+
+/* Sizes of the two output regions of taco_compress for n elements: ceil(n/B)*B bytes of
+ * codes and ceil(n/B)*8 bytes of {alpha, s} records.  0 if n <= 0 or block is invalid. */
+size_t taco_payload_bytes(int64_t n, int32_t block);
+size_t taco_scales_bytes(int64_t n, int32_t block);
+
+/* Sender side of Algorithm 1 (fused compression kernel, Section 4.4.1).
+ *   x_bf16   in   device, rows*cols bf16 values
+ *   payload  out  device, taco_payload_bytes(rows*cols, B) bytes
+ *   scales   out  device, taco_scales_bytes(rows*cols, B) bytes */
+int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_params* p,
+                  void* payload, void* scales, void* stream);
+
+/* Receiver side of Algorithm 1 (fused decompression kernel, Section 4.1 / 4.4.1):
+ * out = bf16( H (codes * s) / sqrt(B) / alpha ).  tau and eps are ignored.
+ *   out_bf16 out  device, rows*cols bf16 values */
+int taco_decompress(const void* payload, const void* scales, int64_t rows, int64_t cols,
+                    const taco_params* p, void* out_bf16, void* stream);
+
+/* Receiver side followed by the single local reduction of Section 4.4.2:
+ * out = bf16( sum_{i<k} decode(payloads[i], scales[i]) ), accumulated in fp32 with one
+ * final rounding.  `payloads` and `scales` are HOST arrays of k device pointers, read
+ * during the call (they may be freed as soon as it returns).  k = 1 equals taco_decompress. */
+int taco_decompress_sum(const void* const* payloads, const void* const* scales, int32_t k,
+                        int64_t rows, int64_t cols, const taco_params* p, void* out_bf16,
+                        void* stream);
+
+/* Diagnostic: converts n device floats to E4M3 codes with the same hardware conversion
+ * the compression kernels use (Cvt_FP8 of Eq. quantization), so that it can be compared
+ * against a code table.  in_f32: device, n floats; out_codes: device, n bytes. */
+int taco_debug_cvt_e4m3(const void* in_f32, int64_t n, void* out_codes, void* stream);
+
+/* Text for a taco_status value (static storage, never NULL). */
+const char* taco_strerror(int status);
+
+/* Library version, "major.minor". */
+const char* taco_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TACO_H_ */

@@ -42,6 +42,9 @@
 #include <cstdint>
 #include <cstring>
 #include <vector>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 namespace {
 
@@ -162,6 +165,15 @@ void decode_block(const std::vector<double>& H, int B, const uint8_t* codes, flo
 extern "C" {
 
 enum { TACO_REF_OK = 0, TACO_REF_ERR_ARG = -1 };
+
+// Threads the block loops use (1 without OpenMP).
+int taco_ref_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 double taco_ref_e4m3_decode(uint8_t code) { return e4m3_decode(code); }
 uint8_t taco_ref_e4m3_encode(double v) { return e4m3_encode(v); }

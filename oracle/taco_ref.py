@@ -23,6 +23,8 @@ def lib():
             _build.build(force=True)
         L = ctypes.CDLL(path)
         c = ctypes
+        L.taco_ref_threads.restype = c.c_int
+        L.taco_ref_threads.argtypes = []
         L.taco_ref_e4m3_decode.restype = c.c_double
         L.taco_ref_e4m3_decode.argtypes = [c.c_uint8]
         L.taco_ref_e4m3_encode.restype = c.c_uint8
@@ -48,6 +50,10 @@ def lib():
 
 def _ptr(a):
     return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def threads() -> int:
+    return int(lib().taco_ref_threads())
 
 
 def e4m3_decode(code: int) -> float:

@@ -1,0 +1,151 @@
+// Plain butterfly kernels: one 64-lane wavefront per block of B elements, any supported B
+// (32 .. 512), any n (ragged tails are bounds-checked).  They serve block sizes without a
+// matrix-core kernel and the tail of a tensor that does not fill a whole tile.
+//
+// Element e of a block lives in lane (e & 63), register (e >> 6).  The fast Walsh-Hadamard
+// transform (Algorithm 1, sender and receiver sides) then splits into stages that
+// exchange values between lanes (strides 1 .. 32, a wave shuffle) and stages between
+// registers of one lane (strides 64 and up).  The in-place butterfly with stride h maps
+// (a, b) -> (a + b, a - b) for the pair whose indices differ in bit h; running all strides
+// gives y = H x with H[i][j] = (-1)^popcount(i & j), the natural ordering.
+//
+// The transform runs on the raw block (bf16 inputs, or decoded FP8 codes) so that most
+// partial sums are exact in fp32, and the block scalars are applied once afterwards
+// (the rotation is linear, so alpha_k and 1/sqrt(B) commute with it).
+#pragma once
+
+#include "device_util.h"
+
+namespace taco {
+
+template <int B>
+struct ButterflyShape {
+    static constexpr int kRegs = (B + 63) / 64;   // values per lane
+    static constexpr int kLanes = B < 64 ? B : 64;  // lanes that hold data
+};
+
+// y = H x over the wave; v[r] holds element lane + 64 r.  Lanes >= B (B = 32) carry zeros.
+template <int B>
+__device__ __forceinline__ void fwht_wave(float (&v)[ButterflyShape<B>::kRegs], int lane) {
+    constexpr int R = ButterflyShape<B>::kRegs;
+#pragma unroll
+    for (int h = 1; h < 64 && h < B; h <<= 1) {
+        const bool upper = (lane & h) != 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float other = __shfl_xor(v[r], h, 64);
+            v[r] = upper ? other - v[r] : v[r] + other;
+        }
+    }
+#pragma unroll
+    for (int hr = 1; hr < R; hr <<= 1) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if ((r & hr) == 0) {
+                float a = v[r], b = v[r | hr];
+                v[r] = a + b;
+                v[r | hr] = a - b;
+            }
+        }
+    }
+}
+
+// Sender side of Algorithm 1 for blocks [first_block, first_block + n_blocks).
+template <int B>
+__global__ __launch_bounds__(64) void compress_butterfly_kernel(
+    const uint16_t* __restrict__ x, int64_t n, int64_t first_block, int64_t n_blocks, float tau,
+    float eps, uint8_t* __restrict__ payload, float2* __restrict__ scales) {
+    constexpr int R = ButterflyShape<B>::kRegs;
+    const int lane = threadIdx.x;
+    const float inv_root_b = 1.0f / __builtin_sqrtf(static_cast<float>(B));
+    for (int64_t blk = first_block + blockIdx.x; blk < first_block + n_blocks; blk += gridDim.x) {
+        float v[R];
+        float energy = 0.0f;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int e = lane + 64 * r;
+            const int64_t idx = blk * B + e;
+            v[r] = (e < B && idx < n) ? bf16_bits_to_f32(x[idx]) : 0.0f;   // zero padding
+            energy = __builtin_fmaf(v[r], v[r], energy);
+        }
+        energy = wave_allreduce_sum(energy);                 // sum_j G_kj^2
+        fwht_wave<B>(v, lane);                               // W = H G_k (unnormalised)
+        float wmax = 0.0f;
+#pragma unroll
+        for (int r = 0; r < R; ++r) wmax = fmaxf(wmax, __builtin_fabsf(v[r]));
+        wmax = wave_allreduce_max(wmax);
+        // Eq. ash_sigma, Eq. ash_alpha; Z = alpha W / sqrt(B); Eq. post_scale.
+        const float alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / B) + eps);
+        const float zmax = wmax * alpha * inv_root_b;
+        const float s = zmax * (1.0f / kQmax);
+        // Z / s = Q_max W / max|W| in exact arithmetic; zero blocks map to zero codes.
+        const float to_code = wmax > 0.0f ? kQmax * __builtin_amdgcn_rcpf(wmax) : 0.0f;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int e = lane + 64 * r;
+            if (e < B) {
+                const float q = v[r] * to_code;
+                payload[blk * B + e] = static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_fp8_f32(q, q, 0, false) & 0xFF);
+            }
+        }
+        if (lane == 0) scales[blk] = make_float2(alpha, s);
+    }
+}
+
+struct PayloadTable {
+    const void* payload[16];
+    const void* scales[16];
+};
+
+// Receiver side of Algorithm 1 plus the local reduction over k payloads.  The rotation is
+// linear, so for k > 1 the codes are first combined with their block factors
+// s / (alpha sqrt(B)) and rotated once; for k = 1 the raw codes are rotated (exact partial
+// sums) and the factor is applied afterwards.
+template <int B>
+__global__ __launch_bounds__(64) void decompress_sum_butterfly_kernel(
+    PayloadTable tab, int k, int64_t n, int64_t first_block, int64_t n_blocks,
+    uint16_t* __restrict__ out) {
+    constexpr int R = ButterflyShape<B>::kRegs;
+    const int lane = threadIdx.x;
+    const float inv_root_b = 1.0f / __builtin_sqrtf(static_cast<float>(B));
+    for (int64_t blk = first_block + blockIdx.x; blk < first_block + n_blocks; blk += gridDim.x) {
+        float v[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) v[r] = 0.0f;
+        float single = 1.0f;
+        for (int i = 0; i < k; ++i) {
+            const uint8_t* codes = static_cast<const uint8_t*>(tab.payload[i]);
+            const float2 sc = static_cast<const float2*>(tab.scales[i])[blk];
+            const float factor = sc.y * __builtin_amdgcn_rcpf(sc.x) * inv_root_b;   // s / (alpha sqrt(B))
+            const float w = (k == 1) ? 1.0f : factor;
+            single = factor;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int e = lane + 64 * r;
+                if (e < B) {
+                    const float q = __builtin_amdgcn_cvt_f32_fp8(codes[blk * B + e], 0);
+                    v[r] = __builtin_fmaf(q, w, v[r]);
+                }
+            }
+        }
+        fwht_wave<B>(v, lane);
+        const float post = (k == 1) ? single : 1.0f;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int e = lane + 64 * r;
+            const int64_t idx = blk * B + e;
+            if (e < B && idx < n) out[idx] = static_cast<uint16_t>(pack_bf16x2(v[r] * post, 0.0f) & 0xFFFF);
+        }
+    }
+}
+
+// Hardware float -> E4M3 conversion, one value per thread (diagnostic entry point).
+__global__ void cvt_e4m3_kernel(const float* __restrict__ in, int64_t n, uint8_t* __restrict__ out) {
+    int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) {
+        const float v = in[i];
+        out[i] = static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_fp8_f32(v, v, 0, false) & 0xFF);
+    }
+}
+
+}  // namespace taco

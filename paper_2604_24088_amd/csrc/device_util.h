@@ -1,0 +1,75 @@
+// Device-side helpers shared by the gfx950 kernels: type punning, bf16 / FP8 conversion
+// instructions, DPP lane exchanges inside a 16-lane row and whole-wave reductions.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace taco {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte load / store / LDS slot
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kQmax = 448.0f;  // largest finite E4M3 value (Q_max of Eq. post_scale)
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) {
+    return __builtin_bit_cast(float, bits16 << 16);
+}
+
+// binary32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32 on gfx950).
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __bf16 v2 __attribute__((ext_vector_type(2)));
+    v2 p;
+    p[0] = static_cast<__bf16>(lo);
+    p[1] = static_cast<__bf16>(hi);
+    return __builtin_bit_cast(uint32_t, p);
+}
+
+// Four floats -> four E4M3 codes in one dword, byte i = code of v_i (round to nearest even).
+__device__ __forceinline__ uint32_t pack_e4m3x4(float v0, float v1, float v2, float v3) {
+    int w = __builtin_amdgcn_cvt_pk_fp8_f32(v0, v1, 0, false);
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(v2, v3, w, true);
+    return static_cast<uint32_t>(w);
+}
+
+__device__ __forceinline__ int parity32(uint32_t v) { return __builtin_popcount(v) & 1; }
+
+// ---- DPP: data movement inside a row of 16 lanes --------------------------------------
+
+template <int kCtrl>
+__device__ __forceinline__ float dpp_f32(float v) {
+    int r = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xF, 0xF, true);
+    return __builtin_bit_cast(float, r);
+}
+
+constexpr int kDppRowRor(int n) { return 0x120 + n; }                  // rotate right by n in the row
+constexpr int kDppQuadBcast(int q) { return q | (q << 2) | (q << 4) | (q << 6); }  // lane q of each quad
+
+// max over the 16 lanes of a row, result in every lane.
+__device__ __forceinline__ float row16_allreduce_max(float v) {
+    v = fmaxf(v, dpp_f32<kDppRowRor(8)>(v));
+    v = fmaxf(v, dpp_f32<kDppRowRor(4)>(v));
+    v = fmaxf(v, dpp_f32<kDppRowRor(2)>(v));
+    v = fmaxf(v, dpp_f32<kDppRowRor(1)>(v));
+    return v;
+}
+
+// ---- whole-wave (64 lanes) reductions, result in every lane ---------------------------
+
+__device__ __forceinline__ float wave_allreduce_sum(float v) {
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+__device__ __forceinline__ float wave_allreduce_max(float v) {
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+    return v;
+}
+
+}  // namespace taco

@@ -1,0 +1,179 @@
+"""Thin ctypes binding of the C ABI in include/taco.h (libtaco_hip.so).
+
+Argument marshalling only: every step of the operator runs in the HIP kernels.  PyTorch
+supplies device memory and the stream.  There is no CPU fallback: if the library is not
+built or cannot be loaded, the first call raises.
+
+Function names follow the C entry points (taco_compress, taco_decompress,
+taco_decompress_sum, ...).  Tensors: bf16 input/output as torch.bfloat16, payload as
+torch.uint8 (E4M3 codes), scales as torch.float32 of shape [n_blocks, 2] = {alpha, s}.
+"""
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+from . import build as _build
+
+TACO_MAX_K = 16
+TACO_FORMAT_E4M3 = 0
+TACO_IMPL_AUTO, TACO_IMPL_BUTTERFLY, TACO_IMPL_MFMA = 0, 1, 2
+
+EXPORTS = ("taco_default_params", "taco_payload_bytes", "taco_scales_bytes", "taco_compress",
+           "taco_decompress", "taco_decompress_sum", "taco_debug_cvt_e4m3", "taco_strerror",
+           "taco_version")
+
+
+class taco_params(ctypes.Structure):
+    _fields_ = [("block", ctypes.c_int32), ("tau", ctypes.c_float), ("eps", ctypes.c_float),
+                ("format", ctypes.c_int32), ("impl", ctypes.c_int32)]
+
+
+class TacoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {taco_strerror(status)} (status {status})")
+
+
+_LIB = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libtaco_hip.so (built in-tree by paper_2604_24088_amd.build)."""
+    global _LIB
+    if _LIB is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is missing: run `python -m paper_2604_24088_amd.build` "
+                              "(hipcc, gfx950); there is no fallback path")
+        L = ctypes.CDLL(path)
+        c = ctypes
+        L.taco_default_params.restype = None
+        L.taco_default_params.argtypes = [c.POINTER(taco_params)]
+        L.taco_payload_bytes.restype = c.c_size_t
+        L.taco_payload_bytes.argtypes = [c.c_int64, c.c_int32]
+        L.taco_scales_bytes.restype = c.c_size_t
+        L.taco_scales_bytes.argtypes = [c.c_int64, c.c_int32]
+        L.taco_compress.restype = c.c_int
+        L.taco_compress.argtypes = [c.c_void_p, c.c_int64, c.c_int64, c.POINTER(taco_params),
+                                    c.c_void_p, c.c_void_p, c.c_void_p]
+        L.taco_decompress.restype = c.c_int
+        L.taco_decompress.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_int64,
+                                      c.POINTER(taco_params), c.c_void_p, c.c_void_p]
+        L.taco_decompress_sum.restype = c.c_int
+        L.taco_decompress_sum.argtypes = [c.POINTER(c.c_void_p), c.POINTER(c.c_void_p), c.c_int32,
+                                          c.c_int64, c.c_int64, c.POINTER(taco_params),
+                                          c.c_void_p, c.c_void_p]
+        L.taco_debug_cvt_e4m3.restype = c.c_int
+        L.taco_debug_cvt_e4m3.argtypes = [c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p]
+        L.taco_strerror.restype = c.c_char_p
+        L.taco_strerror.argtypes = [c.c_int]
+        L.taco_version.restype = c.c_char_p
+        L.taco_version.argtypes = []
+        _LIB = L
+    return _LIB
+
+
+def taco_strerror(status: int) -> str:
+    return lib().taco_strerror(int(status)).decode()
+
+
+def taco_version() -> str:
+    return lib().taco_version().decode()
+
+
+def taco_default_params(block: int = 128, tau: float = 1.0, eps: float = 1e-12,
+                        impl: int = TACO_IMPL_AUTO) -> taco_params:
+    p = taco_params()
+    lib().taco_default_params(ctypes.byref(p))
+    p.block, p.tau, p.eps, p.impl = block, tau, eps, impl
+    return p
+
+
+def taco_payload_bytes(n: int, block: int) -> int:
+    return int(lib().taco_payload_bytes(n, block))
+
+
+def taco_scales_bytes(n: int, block: int) -> int:
+    return int(lib().taco_scales_bytes(n, block))
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise TacoError(status, where)
+
+
+def _rows_cols(shape) -> tuple:
+    if len(shape) == 1:
+        return 1, int(shape[0])
+    rows = 1
+    for d in shape[:-1]:
+        rows *= int(d)
+    return rows, int(shape[-1])
+
+
+def taco_compress(x: torch.Tensor, params: Optional[taco_params] = None,
+                  payload: Optional[torch.Tensor] = None, scales: Optional[torch.Tensor] = None,
+                  stream=None):
+    """Sender side of Algorithm 1.  x: contiguous CUDA bf16 tensor.  Returns (payload, scales)."""
+    p = params or taco_default_params()
+    assert x.is_cuda and x.dtype == torch.bfloat16 and x.is_contiguous()
+    rows, cols = _rows_cols(x.shape)
+    n = rows * cols
+    if payload is None:
+        payload = torch.empty(taco_payload_bytes(n, p.block), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty((taco_scales_bytes(n, p.block) // 8, 2), dtype=torch.float32, device=x.device)
+    st = lib().taco_compress(x.data_ptr(), rows, cols, ctypes.byref(p), payload.data_ptr(),
+                             scales.data_ptr(), _stream_handle(stream))
+    _check(st, "taco_compress")
+    return payload, scales
+
+
+def taco_decompress(payload: torch.Tensor, scales: torch.Tensor, shape,
+                    params: Optional[taco_params] = None, out: Optional[torch.Tensor] = None,
+                    stream=None) -> torch.Tensor:
+    """Receiver side of Algorithm 1.  Returns a bf16 tensor of `shape`."""
+    p = params or taco_default_params()
+    rows, cols = _rows_cols(tuple(shape))
+    if out is None:
+        out = torch.empty(tuple(shape), dtype=torch.bfloat16, device=payload.device)
+    st = lib().taco_decompress(payload.data_ptr(), scales.data_ptr(), rows, cols, ctypes.byref(p),
+                               out.data_ptr(), _stream_handle(stream))
+    _check(st, "taco_decompress")
+    return out
+
+
+def taco_decompress_sum(payloads: Sequence[torch.Tensor], scales: Sequence[torch.Tensor], shape,
+                        params: Optional[taco_params] = None, out: Optional[torch.Tensor] = None,
+                        stream=None) -> torch.Tensor:
+    """Decode k payloads and add them (fp32 accumulation, one bf16 rounding)."""
+    p = params or taco_default_params()
+    k = len(payloads)
+    assert k == len(scales)
+    rows, cols = _rows_cols(tuple(shape))
+    if out is None:
+        out = torch.empty(tuple(shape), dtype=torch.bfloat16, device=payloads[0].device)
+    parr = (ctypes.c_void_p * max(k, 1))(*[t.data_ptr() for t in payloads])
+    sarr = (ctypes.c_void_p * max(k, 1))(*[t.data_ptr() for t in scales])
+    st = lib().taco_decompress_sum(parr, sarr, k, rows, cols, ctypes.byref(p), out.data_ptr(),
+                                   _stream_handle(stream))
+    _check(st, "taco_decompress_sum")
+    return out
+
+
+def taco_debug_cvt_e4m3(values: torch.Tensor, stream=None) -> torch.Tensor:
+    """Hardware float32 -> E4M3 conversion of a CUDA float tensor (diagnostic)."""
+    assert values.is_cuda and values.dtype == torch.float32 and values.is_contiguous()
+    out = torch.empty(values.numel(), dtype=torch.uint8, device=values.device)
+    st = lib().taco_debug_cvt_e4m3(values.data_ptr(), values.numel(), out.data_ptr(),
+                                   _stream_handle(stream))
+    _check(st, "taco_debug_cvt_e4m3")
+    return out

@@ -1,0 +1,84 @@
+"""Comparison rules between the HIP path and the CPU oracle (used by the GPU parity tests
+and by the smoke check).  Tolerances:
+
+  scales  alpha, s    |gpu - ref| <= 1e-6 * |ref|  (fp32 values; s = 0 must match exactly)
+  codes               identical on >= 99.99 % of elements, the rest at most one code away
+                      in sign-magnitude order, +0 and -0 merged.  Where the block scale s
+                      is zero the sign bit is unspecified.
+  reconstruction      per element |gpu - ref| <= max(one bf16 ulp of ref, 1e-3 * max|ref| of
+                      its block); at least 99.9 % of the elements bit-identical; and
+                      max|gpu - ref| / max|ref| over the tensor at most one bf16 ulp (2^-8).
+
+The code rule follows from the arithmetic: the kernels compute Z/s in fp32 (relative error a
+few 2^-24) while the oracle works in double, so only values within ~1e-7 relative of a
+rounding boundary (spacing 2^-4 relative) can land on the neighbouring code: ~1e-5 of the
+elements at most.  The reconstruction rule allows the one legal bf16 rounding flip (2^-8
+relative to the element) that the same fp32-vs-double difference can cause."""
+import numpy as np
+
+CODE_MATCH_MIN = 0.9999
+SCALE_RTOL = 1e-6
+RECON_RTOL = 1e-3
+RECON_EXACT_MIN = 0.999
+
+
+def code_rank(codes: np.ndarray) -> np.ndarray:
+    c = codes.astype(np.int32)
+    mag = c & 0x7F
+    return np.where(c & 0x80, -mag, mag)
+
+
+def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def check_scales(gpu: np.ndarray, ref: np.ndarray, what: str = ""):
+    gpu = gpu.reshape(-1, 2).astype(np.float64)
+    ref = ref.reshape(-1, 2).astype(np.float64)
+    assert gpu.shape == ref.shape, (gpu.shape, ref.shape)
+    assert np.all(np.isfinite(gpu)), f"{what}: non-finite scale"
+    for col, name in ((0, "alpha"), (1, "s")):
+        g, r = gpu[:, col], ref[:, col]
+        zero = r == 0.0
+        assert np.all(g[zero] == 0.0), f"{what}: {name} must be zero where the oracle's is"
+        rel = np.abs(g[~zero] - r[~zero]) / np.abs(r[~zero])
+        worst = rel.max() if rel.size else 0.0
+        assert worst <= SCALE_RTOL, f"{what}: {name} relative error {worst:.3e} > {SCALE_RTOL}"
+    return True
+
+
+def check_codes(gpu: np.ndarray, ref: np.ndarray, ref_scales: np.ndarray, block: int, what: str = ""):
+    gpu = gpu.reshape(-1, block)
+    ref = ref.reshape(-1, block)
+    assert gpu.shape == ref.shape, (gpu.shape, ref.shape)
+    assert not np.any((gpu & 0x7F) == 0x7F), f"{what}: NaN code produced"
+    dist = np.abs(code_rank(gpu) - code_rank(ref))
+    zero_blocks = ref_scales.reshape(-1, 2)[:, 1] == 0.0
+    assert np.all((gpu[zero_blocks] & 0x7F) == 0), f"{what}: non-zero code in an all-zero block"
+    match = float((dist == 0).mean())
+    assert dist.max() <= 1, f"{what}: a code is {dist.max()} steps from the oracle's"
+    assert match >= CODE_MATCH_MIN, f"{what}: only {match:.6f} of codes identical"
+    return match
+
+
+def check_recon(gpu_bits: np.ndarray, ref_bits: np.ndarray, block: int, what: str = ""):
+    g = bf16_to_f64(gpu_bits.reshape(-1))
+    r = bf16_to_f64(ref_bits.reshape(-1))
+    assert g.shape == r.shape
+    assert np.all(np.isfinite(g)), f"{what}: non-finite output"
+    n = g.size
+    pad = (-n) % block
+    rp = np.concatenate([np.abs(r), np.zeros(pad)]).reshape(-1, block)
+    block_max = np.repeat(rp.max(axis=1), block)[:n]
+    # one bf16 ulp of the oracle value: 2^(floor(log2|r|) - 7)
+    with np.errstate(divide="ignore"):
+        ulp = np.where(r != 0.0, 2.0 ** (np.floor(np.log2(np.abs(r), where=r != 0, out=np.zeros_like(r))) - 7), 0.0)
+    tol = np.maximum(ulp, RECON_RTOL * block_max)
+    err = np.abs(g - r)
+    bad = err > tol
+    assert not bad.any(), f"{what}: {int(bad.sum())} elements off by more than one bf16 ulp / 1e-3 of block max"
+    overall = err.max() / max(np.abs(r).max(), 1e-300)
+    assert overall <= 2.0 ** -8, f"{what}: max error {overall:.3e} of the tensor's max"
+    exact = float((err == 0).mean())
+    assert exact >= RECON_EXACT_MIN, f"{what}: only {exact:.6f} of outputs identical"
+    return exact

@@ -1,0 +1,98 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+include/taco.h declares, answers the size queries and rejects bad arguments before any
+launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2604_24088_amd import taco
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "taco.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(taco_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = taco.lib()
+    names = declared_functions()
+    assert set(names) == set(taco.EXPORTS)
+    for name in names:
+        assert getattr(L, name) is not None, name
+
+
+def test_version_and_strerror():
+    assert re.fullmatch(r"\d+\.\d+", taco.taco_version())
+    assert taco.taco_strerror(0) == "ok"
+    for st in range(-9, 0):
+        assert taco.taco_strerror(st) not in ("ok", "unknown status")
+    assert taco.taco_strerror(-100) == "unknown status"
+
+
+def test_default_params():
+    p = taco.taco_default_params()
+    assert (p.block, p.format, p.impl) == (128, 0, 0)
+    assert p.tau == 1.0 and abs(p.eps - 1e-12) < 1e-18
+
+
+@pytest.mark.parametrize("n,block,codes,scales", [
+    (262144, 128, 262144, 16384), (1, 128, 128, 8), (129, 128, 256, 16), (33554432, 256, 33554432, 1048576),
+    (100, 32, 128, 32), (0, 128, 0, 0), (-5, 128, 0, 0), (1000, 100, 0, 0)])
+def test_size_queries(n, block, codes, scales):
+    assert taco.taco_payload_bytes(n, block) == codes
+    assert taco.taco_scales_bytes(n, block) == scales
+
+
+def _params(**kw):
+    p = taco.taco_default_params()
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+A = 0x1000  # a fake, 16-byte aligned, non-null "device pointer": never dereferenced on these paths
+
+
+@pytest.mark.parametrize("args,status", [
+    (dict(x=0), -1), (dict(payload=0), -1), (dict(scales=0), -1), (dict(p=None), -1),
+    (dict(rows=0), -2), (dict(cols=-4), -2), (dict(rows=1 << 30, cols=1 << 30), -2),
+    (dict(p=_params(block=96)), -3), (dict(p=_params(block=1024)), -3),
+    (dict(x=A + 2), -4), (dict(payload=A + 8), -4), (dict(scales=A + 4), -4),
+    (dict(p=_params(format=1)), -6),
+    (dict(p=_params(impl=7)), -8), (dict(p=_params(impl=2, block=256)), -8),
+    (dict(p=_params(tau=0.0)), -9), (dict(p=_params(eps=-1.0)), -9), (dict(p=_params(tau=float("nan"))), -9),
+])
+def test_compress_rejects_bad_arguments(args, status):
+    L = taco.lib()
+    a = dict(x=A, rows=4, cols=512, p=_params(), payload=A, scales=A)
+    a.update(args)
+    pp = ctypes.byref(a["p"]) if a["p"] is not None else None
+    assert L.taco_compress(a["x"], a["rows"], a["cols"], pp, a["payload"], a["scales"], None) == status
+
+
+@pytest.mark.parametrize("k,status", [(0, -5), (17, -5), (-1, -5)])
+def test_decompress_sum_rejects_bad_k(k, status):
+    L = taco.lib()
+    arr = (ctypes.c_void_p * 17)(*([A] * 17))
+    p = _params()
+    assert L.taco_decompress_sum(arr, arr, k, 4, 512, ctypes.byref(p), A, None) == status
+
+
+def test_decompress_rejects_bad_arguments():
+    L = taco.lib()
+    p = _params()
+    arr = (ctypes.c_void_p * 2)(A, 0)
+    assert L.taco_decompress(0, A, 4, 512, ctypes.byref(p), A, None) == -1
+    assert L.taco_decompress(A, A, 4, 512, ctypes.byref(p), 0, None) == -1
+    assert L.taco_decompress(A, A, 4, 512, ctypes.byref(p), A + 2, None) == -4
+    assert L.taco_decompress_sum(arr, arr, 2, 4, 512, ctypes.byref(p), A, None) == -1     # null entry
+    assert L.taco_decompress_sum(None, arr, 1, 4, 512, ctypes.byref(p), A, None) == -1
+    assert L.taco_debug_cvt_e4m3(0, 4, A, None) == -1
+    assert L.taco_debug_cvt_e4m3(A, 0, A, None) == -2
+    with pytest.raises(taco.TacoError):
+        taco._check(-3, "x")

@@ -1,0 +1,291 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded
+inputs, element by element, at sizes the oracle finishes in seconds.  Tolerances and the
+reasons for them are in tests/parity_util.py."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_24088_amd import taco
+from paper_2604_24088_amd import workloads as W
+
+import parity_util as P
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+IMPLS = {"butterfly": taco.TACO_IMPL_BUTTERFLY, "mfma": taco.TACO_IMPL_MFMA, "auto": taco.TACO_IMPL_AUTO}
+
+
+def to_dev(bits: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def bits_of(t: torch.Tensor) -> np.ndarray:
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def sample_rows(w, payload=0, rows=32):
+    """A slice of a workload that spans several tiles: `rows` rows from the top."""
+    return W.generate_rows(w, payload, 0, rows)
+
+
+def run_compress(x_bits, block, impl, tau=1.0, eps=1e-12):
+    p = taco.taco_default_params(block=block, tau=tau, eps=eps, impl=impl)
+    payload, scales = taco.taco_compress(to_dev(x_bits), p)
+    torch.cuda.synchronize()
+    return payload.cpu().numpy(), scales.cpu().numpy()
+
+
+# ---- the hardware conversion the kernels rely on -------------------------------------------
+
+def test_hardware_e4m3_conversion_matches_oracle(oracle):
+    rng = np.random.default_rng(123)
+    mids = []
+    for c in range(0x7E):
+        lo, hi = oracle.e4m3_decode(c), oracle.e4m3_decode(c + 1)
+        m = np.float32(0.5 * (lo + hi))
+        mids += [m, np.nextafter(m, np.float32(0)), np.nextafter(m, np.float32(1e9))]
+    vals = np.concatenate([
+        np.array(mids, dtype=np.float32), -np.array(mids, dtype=np.float32),
+        np.array([oracle.e4m3_decode(c) for c in range(256) if c & 0x7F != 0x7F], dtype=np.float32),
+        rng.uniform(-448, 448, 20000).astype(np.float32),
+        (rng.standard_normal(20000) * 0.05).astype(np.float32),
+        np.array([448.0, np.nextafter(np.float32(448), np.float32(1e9)), 448.0 * (1 + 2.0 ** -22), -448.00006,
+                  0.0, -0.0, 1e-30, -1e-30, 2.0 ** -10, 2.0 ** -9], dtype=np.float32),
+    ])
+    got = taco.taco_debug_cvt_e4m3(torch.from_numpy(vals).to(DEV)).cpu().numpy()
+    want = np.array([oracle.e4m3_encode(float(v)) for v in vals], dtype=np.uint8)
+    assert np.array_equal(got, want)
+
+
+# ---- compress ------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("impl", ["butterfly", "mfma"])
+def test_compress_tiny_config_full(oracle, impl):
+    w = W.WORKLOADS["tiny"]
+    x = W.generate(w)
+    payload, scales = run_compress(x, 128, IMPLS[impl])
+    rp, rs = oracle.compress(x, block=128)
+    P.check_scales(scales, rs, f"tiny/{impl}")
+    P.check_codes(payload, rp, rs, 128, f"tiny/{impl}")
+
+
+@pytest.mark.parametrize("name", ["gpt_rowpar", "qwen_act", "bwd_grad", "large_k8"])
+@pytest.mark.parametrize("impl", ["butterfly", "mfma"])
+def test_compress_workload_slices(oracle, name, impl):
+    w = W.WORKLOADS[name]
+    x = sample_rows(w, rows=24)
+    payload, scales = run_compress(x, 128, IMPLS[impl])
+    rp, rs = oracle.compress(x, block=128)
+    P.check_scales(scales, rs, f"{name}/{impl}")
+    P.check_codes(payload, rp, rs, 128, f"{name}/{impl}")
+
+
+@pytest.mark.parametrize("block", [32, 64, 256, 512])
+def test_compress_other_block_sizes(oracle, block):
+    w = W.WORKLOADS["qwen_act"]
+    x = sample_rows(w, rows=8)
+    payload, scales = run_compress(x, block, IMPLS["auto"])
+    rp, rs = oracle.compress(x, block=block)
+    P.check_scales(scales, rs, f"B={block}")
+    P.check_codes(payload, rp, rs, block, f"B={block}")
+
+
+@pytest.mark.parametrize("n", [1, 127, 128, 129, 2047, 2048, 2049, 5 * 2048 + 300, 37 * 2048 + 128 * 5 + 77])
+@pytest.mark.parametrize("impl", ["auto", "butterfly"])
+def test_compress_ragged_sizes(oracle, n, impl):
+    """Whole tiles go to the matrix-core kernel, the remaining blocks and the zero-padded last
+    block to the butterfly kernel."""
+    rng = np.random.default_rng(n)
+    x = W.float32_to_bf16_bits((rng.standard_normal(n) * 0.02).astype(np.float32))
+    padded = np.concatenate([x, np.zeros((-n) % 8, dtype=np.uint16)])   # keep the device buffer 16-byte sized
+    p = taco.taco_default_params(block=128, impl=IMPLS[impl])
+    xd = to_dev(padded)[:n]
+    payload, scales = taco.taco_compress(xd, p)
+    torch.cuda.synchronize()
+    rp, rs = oracle.compress(x, block=128)
+    assert payload.numel() == rp.size and scales.numel() == rs.size
+    P.check_scales(scales.cpu().numpy(), rs, f"n={n}")
+    P.check_codes(payload.cpu().numpy(), rp, rs, 128, f"n={n}")
+
+
+@pytest.mark.parametrize("impl", ["butterfly", "mfma"])
+def test_compress_degenerate_blocks(oracle, impl):
+    """All-zero blocks, single-outlier blocks, constant blocks, tiny and huge magnitudes."""
+    B, tiles = 128, 3
+    g = np.zeros((tiles * 16, B), dtype=np.float32)
+    g[1, 77] = -0.0234375                     # single outlier
+    g[2, :] = 0.0078125                       # constant block
+    g[3, 0] = 1.5
+    g[5, :] = np.float32(2.0 ** -60)          # energy far below eps
+    g[6, 5] = 3.0e4
+    g[7, :] = np.linspace(-1, 1, B)
+    g[20, 127] = 2.0 ** -20
+    g[33] = np.random.default_rng(1).standard_normal(B) * 1e-4
+    x = W.float32_to_bf16_bits(g)
+    payload, scales = run_compress(x, B, IMPLS[impl])
+    rp, rs = oracle.compress(x, block=B)
+    P.check_scales(scales, rs, impl)
+    P.check_codes(payload, rp, rs, B, impl)
+    assert np.all(scales.reshape(-1, 2)[0] == rs[0])        # all-zero block: alpha = tau/sqrt(eps), s = 0
+    codes = payload.reshape(-1, B)
+    assert np.all((codes[1] & 0x7F) == 0x7E)                # single outlier: every code is +-Q_max
+    assert (codes[2, 0] & 0x7F) == 0x7E and np.all((codes[2, 1:] & 0x7F) == 0)
+
+
+@pytest.mark.parametrize("impl", ["butterfly", "mfma"])
+def test_compress_tau_eps_parameters(oracle, impl):
+    x = sample_rows(W.WORKLOADS["bwd_grad"], rows=4)
+    for tau, eps in ((2.0, 1e-12), (0.5, 1e-6), (8.0, 0.0)):
+        payload, scales = run_compress(x, 128, IMPLS[impl], tau=tau, eps=eps)
+        rp, rs = oracle.compress(x, block=128, tau=tau, eps=eps)
+        P.check_scales(scales, rs, f"tau={tau} eps={eps}")
+        P.check_codes(payload, rp, rs, 128, f"tau={tau} eps={eps}")
+
+
+def test_compress_is_deterministic():
+    x = to_dev(W.generate(W.WORKLOADS["tiny"]))
+    for impl in ("butterfly", "mfma"):
+        p = taco.taco_default_params(impl=IMPLS[impl])
+        a = taco.taco_compress(x, p)
+        b = taco.taco_compress(x, p)
+        torch.cuda.synchronize()
+        assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+# ---- decompress ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["tiny", "gpt_rowpar", "qwen_act", "bwd_grad"])
+@pytest.mark.parametrize("impl", ["butterfly", "mfma"])
+def test_decompress_oracle_payload(oracle, name, impl):
+    """Decode the ORACLE's payload on the GPU and compare with the oracle's decode."""
+    w = W.WORKLOADS[name]
+    x = W.generate(w) if name == "tiny" else sample_rows(w, rows=24)
+    rp, rs = oracle.compress(x, block=128)
+    ref = oracle.decompress(rp, rs, x.size, block=128)
+    p = taco.taco_default_params(impl=IMPLS[impl])
+    out = taco.taco_decompress(torch.from_numpy(rp).to(DEV), torch.from_numpy(rs).to(DEV), x.shape, p)
+    torch.cuda.synchronize()
+    P.check_recon(bits_of(out), ref, 128, f"{name}/{impl}")
+
+
+@pytest.mark.parametrize("block", [32, 64, 256, 512])
+def test_decompress_other_block_sizes(oracle, block):
+    x = sample_rows(W.WORKLOADS["gpt_rowpar"], rows=8)
+    rp, rs = oracle.compress(x, block=block)
+    ref = oracle.decompress(rp, rs, x.size, block=block)
+    p = taco.taco_default_params(block=block)
+    out = taco.taco_decompress(torch.from_numpy(rp).to(DEV), torch.from_numpy(rs).to(DEV), x.shape, p)
+    torch.cuda.synchronize()
+    P.check_recon(bits_of(out), ref, block, f"B={block}")
+
+
+@pytest.mark.parametrize("n", [1, 129, 2049, 3 * 2048 + 5 * 128 + 9])
+def test_decompress_ragged_sizes(oracle, n):
+    rng = np.random.default_rng(n + 1)
+    x = W.float32_to_bf16_bits((rng.standard_normal(n) * 0.02).astype(np.float32))
+    rp, rs = oracle.compress(x, block=128)
+    ref = oracle.decompress(rp, rs, n, block=128)
+    buf = torch.zeros(n + ((-n) % 8) + 8, dtype=torch.bfloat16, device=DEV)
+    out = taco.taco_decompress(torch.from_numpy(rp).to(DEV), torch.from_numpy(rs).to(DEV), (n,),
+                               out=buf[:n])
+    torch.cuda.synchronize()
+    P.check_recon(bits_of(out), ref, 128, f"n={n}")
+    assert torch.all(buf[n:] == 0)                          # nothing written past n
+
+
+def test_decompress_arbitrary_codes(oracle):
+    """Every finite code value, random scales: decode only, no compressor involved."""
+    rng = np.random.default_rng(9)
+    M, B = 64, 128
+    codes = rng.integers(0, 256, M * B).astype(np.uint8)
+    codes[(codes & 0x7F) == 0x7F] = 0x7E
+    scales = np.stack([np.exp(rng.uniform(0, 8, M)), np.exp(rng.uniform(-9, -3, M))], axis=1).astype(np.float32)
+    ref = oracle.decompress(codes, scales, M * B, block=B)
+    for impl in ("butterfly", "mfma"):
+        p = taco.taco_default_params(impl=IMPLS[impl])
+        out = taco.taco_decompress(torch.from_numpy(codes).to(DEV), torch.from_numpy(scales).to(DEV), (M * B,), p)
+        torch.cuda.synchronize()
+        P.check_recon(bits_of(out), ref, B, impl)
+
+
+@pytest.mark.parametrize("impl", ["butterfly", "mfma"])
+def test_round_trip_end_to_end(oracle, impl):
+    """GPU compress -> GPU decompress against oracle compress -> oracle decompress.  Blocks in
+    which a code differs legitimately move by up to one FP8 step, so they are compared only
+    through the error bound; all others must agree to the reconstruction rule."""
+    w = W.WORKLOADS["tiny"]
+    x = W.generate(w)
+    p = taco.taco_default_params(impl=IMPLS[impl])
+    payload, scales = taco.taco_compress(to_dev(x), p)
+    out = taco.taco_decompress(payload, scales, x.shape, p)
+    torch.cuda.synchronize()
+    rp, rs = oracle.compress(x)
+    ref = oracle.decompress(rp, rs, x.size)
+    same = np.all(payload.cpu().numpy().reshape(-1, 128) == rp.reshape(-1, 128), axis=1) & \
+        np.all(scales.cpu().numpy().reshape(-1, 2) == rs, axis=1)
+    got = bits_of(out).reshape(-1, 128)
+    P.check_recon(got[same], ref.reshape(-1, 128)[same], 128, impl)
+    g = P.bf16_to_f64(x.reshape(-1)).reshape(-1, 128)
+    rec = P.bf16_to_f64(got.reshape(-1)).reshape(-1, 128)
+    rel = np.linalg.norm(rec - g, axis=1) / np.linalg.norm(g, axis=1)
+    assert np.all(rel <= 2.0 ** -4 + 2.0 ** -8 + 1e-3)
+
+
+# ---- decompress_sum --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("k", [1, 2, 3, 8, 16])
+@pytest.mark.parametrize("impl", ["butterfly", "mfma"])
+def test_decompress_sum(oracle, k, impl):
+    w = W.WORKLOADS["large_k8"]
+    rows = 8
+    ps, ss = [], []
+    for i in range(k):
+        x = W.generate_rows(w, i % w.payloads, 16 * (i // w.payloads), rows)
+        rp, rs = oracle.compress(x, block=128)
+        ps.append(rp)
+        ss.append(rs)
+    n = rows * w.hidden
+    ref = oracle.decompress_sum(ps, ss, n, block=128)
+    p = taco.taco_default_params(impl=IMPLS[impl])
+    out = taco.taco_decompress_sum([torch.from_numpy(a).to(DEV) for a in ps],
+                                   [torch.from_numpy(a).to(DEV) for a in ss], (rows, w.hidden), p)
+    torch.cuda.synchronize()
+    P.check_recon(bits_of(out), ref, 128, f"k={k}/{impl}")
+    if k == 1:
+        single = taco.taco_decompress(torch.from_numpy(ps[0]).to(DEV), torch.from_numpy(ss[0]).to(DEV),
+                                      (rows, w.hidden), p)
+        assert torch.equal(single, out)
+
+
+def test_decompress_sum_ragged_and_other_blocks(oracle):
+    rng = np.random.default_rng(4)
+    for block, n in ((128, 2048 * 2 + 700), (256, 5000), (64, 3000)):
+        ps, ss = [], []
+        for i in range(3):
+            x = W.float32_to_bf16_bits((rng.standard_normal(n) * 0.02).astype(np.float32))
+            rp, rs = oracle.compress(x, block=block)
+            ps.append(rp)
+            ss.append(rs)
+        ref = oracle.decompress_sum(ps, ss, n, block=block)
+        p = taco.taco_default_params(block=block)
+        buf = torch.zeros(n + ((-n) % 8) + 8, dtype=torch.bfloat16, device=DEV)
+        out = taco.taco_decompress_sum([torch.from_numpy(a).to(DEV) for a in ps],
+                                       [torch.from_numpy(a).to(DEV) for a in ss], (n,), p, out=buf[:n])
+        torch.cuda.synchronize()
+        P.check_recon(bits_of(out), ref, block, f"B={block} n={n}")
+        assert torch.all(buf[n:] == 0)
+
+
+def test_runs_on_a_side_stream(oracle):
+    x = W.generate(W.WORKLOADS["tiny"])
+    xd = to_dev(x)
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):
+        payload, scales = taco.taco_compress(xd)
+        out = taco.taco_decompress(payload, scales, x.shape)
+    st.synchronize()
+    rp, rs = oracle.compress(x)
+    P.check_codes(payload.cpu().numpy(), rp, rs, 128, "stream")
+    assert out.shape == x.shape
