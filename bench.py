@@ -168,7 +168,7 @@ def main():
                      "alg_bytes_per_launch": bytes_comp, "avg_launch_ms": round(t_comp, 4)},
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, B, rows=max(w.tokens // 8, 64))
+        result["cpu_baseline"] = cpu_baseline(w, B, rows=w.tokens)
     print(json.dumps(result))
 
 

@@ -36,6 +36,13 @@ __device__ __forceinline__ uint32_t pack_e4m3x4(float v0, float v1, float v2, fl
     return static_cast<uint32_t>(w);
 }
 
+// Sum of squares of the two bf16 halves of a dword, added to acc (v_dot2c_f32_bf16).
+// The dword is taken BY VALUE: bit-casting a vector-element lvalue directly reads element 0.
+__device__ __forceinline__ float dot2_self_bf16(uint32_t pair, float acc) {
+    const bf16x2 p = __builtin_bit_cast(bf16x2, pair);
+    return __builtin_amdgcn_fdot2_f32_bf16(p, p, acc, false);
+}
+
 __device__ __forceinline__ int parity32(uint32_t v) { return __builtin_popcount(v) & 1; }
 
 // ---- DPP: data movement inside a row of 16 lanes --------------------------------------

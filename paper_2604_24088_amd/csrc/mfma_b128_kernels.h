@@ -104,12 +104,11 @@ __global__ __launch_bounds__(64) void compress_b128_mfma_kernel(
         float e0 = 0.0f, e1 = 0.0f;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const bf16x2 p0 = __builtin_bit_cast(bf16x2, a[c].x), p1 = __builtin_bit_cast(bf16x2, a[c].y);
-            const bf16x2 p2 = __builtin_bit_cast(bf16x2, a[c].z), p3 = __builtin_bit_cast(bf16x2, a[c].w);
-            e0 = __builtin_amdgcn_fdot2_f32_bf16(p0, p0, e0, false);
-            e1 = __builtin_amdgcn_fdot2_f32_bf16(p1, p1, e1, false);
-            e0 = __builtin_amdgcn_fdot2_f32_bf16(p2, p2, e0, false);
-            e1 = __builtin_amdgcn_fdot2_f32_bf16(p3, p3, e1, false);
+            const uint32_t w0 = a[c][0], w1 = a[c][1], w2 = a[c][2], w3 = a[c][3];
+            e0 = dot2_self_bf16(w0, e0);
+            e1 = dot2_self_bf16(w1, e1);
+            e0 = dot2_self_bf16(w2, e0);
+            e1 = dot2_self_bf16(w3, e1);
         }
         float energy = e0 + e1;
         energy += __shfl_xor(energy, 16, 64);

@@ -6,8 +6,10 @@ and by the smoke check).  Tolerances:
                       in sign-magnitude order, +0 and -0 merged.  Where the block scale s
                       is zero the sign bit is unspecified.
   reconstruction      per element |gpu - ref| <= max(one bf16 ulp of ref, 1e-3 * max|ref| of
-                      its block); at least 99.9 % of the elements bit-identical; and
-                      max|gpu - ref| / max|ref| over the tensor at most one bf16 ulp (2^-8).
+                      its block); max|gpu - ref| / max|ref| over the tensor at most one bf16 ulp
+                      (2^-8); and a minimum share of bit-identical elements: 99.5 % for one
+                      decoded payload, 99 % for sums of k payloads (k fp32 additions, with
+                      cancellation), 90 % for synthetic random codes (18 binades inside a block).
 
 The code rule follows from the arithmetic: the kernels compute Z/s in fp32 (relative error a
 few 2^-24) while the oracle works in double, so only values within ~1e-7 relative of a
@@ -19,7 +21,9 @@ import numpy as np
 CODE_MATCH_MIN = 0.9999
 SCALE_RTOL = 1e-6
 RECON_RTOL = 1e-3
-RECON_EXACT_MIN = 0.999
+RECON_EXACT_MIN = 0.995
+RECON_EXACT_MIN_SUM = 0.99
+RECON_EXACT_MIN_RANDOM = 0.90
 
 
 def code_rank(codes: np.ndarray) -> np.ndarray:
@@ -61,7 +65,8 @@ def check_codes(gpu: np.ndarray, ref: np.ndarray, ref_scales: np.ndarray, block:
     return match
 
 
-def check_recon(gpu_bits: np.ndarray, ref_bits: np.ndarray, block: int, what: str = ""):
+def check_recon(gpu_bits: np.ndarray, ref_bits: np.ndarray, block: int, what: str = "",
+                min_exact: float = RECON_EXACT_MIN):
     g = bf16_to_f64(gpu_bits.reshape(-1))
     r = bf16_to_f64(ref_bits.reshape(-1))
     assert g.shape == r.shape
@@ -80,5 +85,5 @@ def check_recon(gpu_bits: np.ndarray, ref_bits: np.ndarray, block: int, what: st
     overall = err.max() / max(np.abs(r).max(), 1e-300)
     assert overall <= 2.0 ** -8, f"{what}: max error {overall:.3e} of the tensor's max"
     exact = float((err == 0).mean())
-    assert exact >= RECON_EXACT_MIN, f"{what}: only {exact:.6f} of outputs identical"
+    assert exact >= min_exact, f"{what}: only {exact:.6f} of outputs identical"
     return exact
