@@ -121,6 +121,20 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
+    # ---- yardstick outside the timed region: plain copy of 1 GiB (reads 1 GiB, writes 1 GiB)
+    src = xs[0].view(torch.uint8)[: 1 << 30] if xs[0].numel() * 2 >= (1 << 30) else xs[0].view(torch.uint8)
+    dst = torch.empty_like(src)
+    cev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for _ in range(2):
+        taco.taco_debug_copy(src, dst, stream)
+    cev[0].record(stream)
+    for _ in range(10):
+        taco.taco_debug_copy(src, dst, stream)
+    cev[1].record(stream)
+    torch.cuda.synchronize()
+    copy_gbps = 2.0 * src.numel() * 10 / (cev[0].elapsed_time(cev[1]) * 1e6)
+    del dst
+
     ms_step = wall * 1e3 / args.steps
     t_comp = sum(e[0].elapsed_time(e[1]) for e in events) / (args.steps * k)   # ms per compress launch
     t_dec = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
@@ -158,6 +172,7 @@ def main():
         "value_out_basis": round(real_bf16 / (ms_step * 1e6), 1),
         "moved_GBps": round(moved / (ms_step * 1e6), 1),
         "hbm_frac_step": round(moved / (ms_step * 1e6) / HBM_PEAK_GBPS, 4),
+        "copy_yardstick_GBps": round(copy_gbps, 1),
         "calls": {"compress": call(t_comp, bytes_comp, 2.0 * n),
                   "decompress": call(t_dec, bytes_dec, 2.0 * n),
                   f"decompress_sum_k{k}": call(t_sum, bytes_sum, k * 2.0 * n)},

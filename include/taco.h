@@ -113,6 +113,11 @@ int taco_decompress_sum(const void* const* payloads, const void* const* scales, 
  * against a code table.  in_f32: device, n floats; out_codes: device, n bytes. */
 int taco_debug_cvt_e4m3(const void* in_f32, int64_t n, void* out_codes, void* stream);
 
+/* Diagnostic: plain device-to-device copy of `bytes` bytes (a multiple of 16) with 16-byte
+ * loads and stores.  A yardstick for the memory system (reads `bytes`, writes `bytes`) and
+ * the known-size kernel that calibrates hardware traffic counters.  src, dst: device. */
+int taco_debug_copy(const void* src, void* dst, int64_t bytes, void* stream);
+
 /* Text for a taco_status value (static storage, never NULL). */
 const char* taco_strerror(int status);
 

@@ -148,4 +148,10 @@ __global__ void cvt_e4m3_kernel(const float* __restrict__ in, int64_t n, uint8_t
     }
 }
 
+// Plain copy, 16 bytes per lane, grid-stride (diagnostic entry point).
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t n16) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 }  // namespace taco

@@ -193,6 +193,19 @@ int taco_debug_cvt_e4m3(const void* in_f32, int64_t n, void* out_codes, void* st
     return launch_status();
 }
 
+int taco_debug_copy(const void* src, void* dst, int64_t bytes, void* stream) {
+    if (!src || !dst) return TACO_ERR_NULL;
+    if (bytes <= 0 || (bytes & 15) != 0) return TACO_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(dst)) return TACO_ERR_ALIGN;
+    const int64_t n16 = bytes / 16;
+    const int64_t want = (n16 + 255) / 256;
+    const int64_t cap = static_cast<int64_t>(device_cus()) * 32;
+    hipLaunchKernelGGL(taco::copy_kernel, dim3(static_cast<unsigned>(want < cap ? want : cap)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const taco::u32x4*>(src),
+                       static_cast<taco::u32x4*>(dst), n16);
+    return launch_status();
+}
+
 const char* taco_strerror(int status) {
     switch (status) {
         case TACO_OK: return "ok";

@@ -21,7 +21,7 @@ TACO_FORMAT_E4M3 = 0
 TACO_IMPL_AUTO, TACO_IMPL_BUTTERFLY, TACO_IMPL_MFMA = 0, 1, 2
 
 EXPORTS = ("taco_default_params", "taco_payload_bytes", "taco_scales_bytes", "taco_compress",
-           "taco_decompress", "taco_decompress_sum", "taco_debug_cvt_e4m3", "taco_strerror",
+           "taco_decompress", "taco_decompress_sum", "taco_debug_cvt_e4m3", "taco_debug_copy", "taco_strerror",
            "taco_version")
 
 
@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
                                           c.c_void_p, c.c_void_p]
         L.taco_debug_cvt_e4m3.restype = c.c_int
         L.taco_debug_cvt_e4m3.argtypes = [c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p]
+        L.taco_debug_copy.restype = c.c_int
+        L.taco_debug_copy.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p]
         L.taco_strerror.restype = c.c_char_p
         L.taco_strerror.argtypes = [c.c_int]
         L.taco_version.restype = c.c_char_p
@@ -177,3 +179,12 @@ def taco_debug_cvt_e4m3(values: torch.Tensor, stream=None) -> torch.Tensor:
                                    _stream_handle(stream))
     _check(st, "taco_debug_cvt_e4m3")
     return out
+
+
+def taco_debug_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> torch.Tensor:
+    """Plain device copy of src into dst (same byte size, a multiple of 16): bandwidth yardstick."""
+    nbytes = src.numel() * src.element_size()
+    assert src.is_cuda and dst.is_cuda and nbytes == dst.numel() * dst.element_size()
+    st = lib().taco_debug_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_handle(stream))
+    _check(st, "taco_debug_copy")
+    return dst
