@@ -28,7 +28,10 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
 # HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); None until measured.  The summary
 # the number comes from is committed under profiles/.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # fetch 393266 KiB + write 208897 KiB per compress launch: profiles/b128_mfma_kernels_large_k8.txt
+    ("large_k8", 128, "auto"): 616614909,
+}
 
 
 def parse():
@@ -176,7 +179,7 @@ def main():
         "calls": {"compress": call(t_comp, bytes_comp, 2.0 * n),
                   "decompress": call(t_dec, bytes_dec, 2.0 * n),
                   f"decompress_sum_k{k}": call(t_sum, bytes_sum, k * 2.0 * n)},
-        "roofline": {"kernel": "compress_b128_mfma_kernel" if (B == 128 and args.impl != "butterfly") else "compress_butterfly_kernel",
+        "roofline": {"kernel": "compress_b128_mfma_kernel<2,true>" if (B == 128 and args.impl != "butterfly") else "compress_butterfly_kernel",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, B, args.impl)),

@@ -8,6 +8,7 @@
 namespace taco {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));   // one {alpha, s} record
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
@@ -43,6 +44,17 @@ __device__ __forceinline__ float dot2_self_bf16(uint32_t pair, float acc) {
     return __builtin_amdgcn_fdot2_f32_bf16(p, p, acc, false);
 }
 
+// Streaming (non-temporal) global accesses: data that is touched once should not displace
+// anything in the caches.  kStream = false gives the ordinary access.
+template <bool kStream>
+__device__ __forceinline__ u32x4 load16(const u32x4* p) {
+    return kStream ? __builtin_nontemporal_load(p) : *p;
+}
+template <bool kStream, typename T>
+__device__ __forceinline__ void store_stream(T* p, T v) {
+    if (kStream) __builtin_nontemporal_store(v, p); else *p = v;
+}
+
 __device__ __forceinline__ int parity32(uint32_t v) { return __builtin_popcount(v) & 1; }
 
 // ---- DPP: data movement inside a row of 16 lanes --------------------------------------
@@ -51,6 +63,11 @@ template <int kCtrl>
 __device__ __forceinline__ float dpp_f32(float v) {
     int r = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), kCtrl, 0xF, 0xF, true);
     return __builtin_bit_cast(float, r);
+}
+
+template <int kCtrl>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), kCtrl, 0xF, 0xF, true));
 }
 
 constexpr int kDppRowRor(int n) { return 0x120 + n; }                  // rotate right by n in the row

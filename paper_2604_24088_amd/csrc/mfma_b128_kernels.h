@@ -22,7 +22,7 @@
 // Index maps (all bijections; correctness only needs A and B to agree on them):
 //   block of MFMA row i          beta(i) = 4 (i % 4) + i / 4      (tile-local block index)
 //   output position of column n  p(nt, n) = 8 n + nt              (nt = which of 8 MFMA column tiles)
-//   element of A slot            compress: e(c, g, t) = 8 (4 c + g) + t,  c = MFMA step 0..3, t = 0..7
+//   element of A slot            compress: e(c, g, m, y) = 8 (4 g + m) + 2 c + y,  c = MFMA step 0..3 (see below)
 //                                decode:   e(m, g, b) = 64 m + 16 g + b,  m = 0..1, b = 0..15
 //   B entry                      H[e][p] = (-1)^popcount(e & p)
 #pragma once
@@ -40,126 +40,157 @@ __device__ __forceinline__ int tile_block_of_row(int i) { return 4 * (i & 3) + (
 // ------------------------------------------------------------------------------------------
 // compress
 // ------------------------------------------------------------------------------------------
+//
+// Element map of the compress kernel.  A 16-byte chunk j (0..15) of a block holds 8 elements,
+// i.e. 4 dwords c = 0..3 of two bf16 (y = 0, 1):  e = 8 j + 2 c + y.  MFMA step c takes, from
+// the four chunks j = 4g + m (m = 0..3) of the lane's block row, dword c: A slot t = 2m + y.
+// Against output position p = 8 n + nt the sign of H[e][p] splits into
+//     parity((4g+m) & n) ^ (y & nt)           a pattern that depends on nt only through nt & 1
+//   ^ parity(c & (nt >> 1))                   one sign for the whole MFMA
+// so four register tiles (two patterns, two signs) serve all 32 MFMAs of a tile.
+//
+// To hand step c its operand with one 16-byte LDS read, the tile is written to LDS
+// transposed at dword granularity: block row b (padded to 512 bytes), 16-byte slot
+// (4 (j/4) + c + b) holds dword c of chunks 4 (j/4) .. 4 (j/4) + 3.  The "+ b" rotation
+// spreads the 16 rows a read instruction touches over all banks, and because rows are
+// padded the rotation never wraps: every LDS address is one per-lane base plus an
+// immediate.  Writes (4-byte) and reads (16-byte) are both bank-conflict free.
+
+constexpr int kCompressLdsDwords = 16 * 128;   // 16 block rows of 128 dwords (64 used + rotation room)
+
+// max over the 16 lanes of a row of m[q], q = lane % 4, delivered to the lanes with that q
+// (values must be non-negative floats: compared as unsigned integers).
+__device__ __forceinline__ float row16_max_scatter(float m0, float m1, float m2, float m3, int n16) {
+    const bool b0 = (n16 & 1) != 0, b1 = (n16 & 2) != 0;
+    const uint32_t u0 = __builtin_bit_cast(uint32_t, m0), u1 = __builtin_bit_cast(uint32_t, m1);
+    const uint32_t u2 = __builtin_bit_cast(uint32_t, m2), u3 = __builtin_bit_cast(uint32_t, m3);
+    const uint32_t keep01 = b0 ? u1 : u0, send01 = b0 ? u0 : u1;
+    const uint32_t keep23 = b0 ? u3 : u2, send23 = b0 ? u2 : u3;
+    const uint32_t a0 = max(keep01, dpp_u32<0xB1>(send01));   // quad_perm [1,0,3,2]: lane ^ 1
+    const uint32_t a1 = max(keep23, dpp_u32<0xB1>(send23));
+    const uint32_t keep = b1 ? a1 : a0, send = b1 ? a0 : a1;
+    uint32_t v = max(keep, dpp_u32<0x4E>(send));               // quad_perm [2,3,0,1]: lane ^ 2
+    v = max(v, dpp_u32<kDppRowRor(4)>(v));
+    v = max(v, dpp_u32<kDppRowRor(8)>(v));
+    return __builtin_bit_cast(float, v);
+}
 
 // x: n_tiles * 2048 bf16 (as 16-byte words); payload: n_tiles * 2048 codes (as 8-byte
 // words); scales: n_tiles * 16 records {alpha, s}.
+// Workgroup w (one wave) handles the kTiles consecutive tiles starting at w * kTiles and
+// exits: no persistent loop.  The hardware dispatcher hands out workgroups in index order, so
+// the set of tiles in flight at any moment is one dense, slowly advancing window of memory,
+// which measured faster on HBM than a grid-stride loop over the same tiles.  All loads of the
+// wave are issued before the first tile is processed.
+template <int kTiles, bool kStream>
 __global__ __launch_bounds__(64) void compress_b128_mfma_kernel(
     const u32x4* __restrict__ x, int64_t n_tiles, float tau, float eps,
-    u32x2* __restrict__ payload, float2* __restrict__ scales) {
-    __shared__ u32x4 lds[256];   // one tile: 16 block rows x 16 chunks of 16 bytes
+    u32x2* __restrict__ payload, f32x2* __restrict__ scales) {
+    __shared__ uint32_t lds[kCompressLdsDwords];
     const int lane = threadIdx.x;
     const int g = lane >> 4;
     const int n16 = lane & 15;
+    const int64_t first_tile = static_cast<int64_t>(blockIdx.x) * kTiles;
 
-    // B operand: the 32 tiles (c, nt) of H_128, 8 bf16 (+-1) per lane each.
-    // Sign of entry (c, g, t) x (nt, n16): parity((4c+g) & n16) ^ parity(t & nt).
-    uint32_t hb[4][8][4];
+    u32x4 stage[kTiles][4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const uint32_t lane_sign = parity32((4 * c + g) & n16) ? 0x80008000u : 0u;
+    for (int p = 0; p < kTiles; ++p) {
+        int64_t t = first_tile + p;
+        if (t >= n_tiles) t = n_tiles - 1;      // ragged last wave: re-read a valid tile, result unused
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint32_t lo = __builtin_popcount((2 * u) & nt) & 1;
-                const uint32_t hi = __builtin_popcount((2 * u + 1) & nt) & 1;
-                hb[c][nt][u] = (0x3F803F80u ^ (lo << 15) ^ (hi << 31)) ^ lane_sign;
-            }
-        }
+        for (int c = 0; c < 4; ++c) stage[p][c] = load16<kStream>(&x[t * 256 + 64 * c + lane]);
     }
 
-    // LDS slots.  Writer: load c covers tile blocks 4c .. 4c+3, this lane holds chunk n16 of
-    // block 4c+g.  Reader: MFMA row i = n16 is block beta(i); step c wants chunk 4c+g.
-    int wr_slot[4], rd_slot[4];
+    // B operand: patterns P0 / P1 (nt even / odd) and their negatives, 8 bf16 (+-1) per lane.
+    u32x4 hb[2][2];   // [nt & 1][sign]
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const uint32_t s0 = parity32((4 * g + m) & n16) ? 0x80008000u : 0u;
+        hb[0][0][m] = 0x3F803F80u ^ s0;
+        hb[1][0][m] = hb[0][0][m] ^ 0x80000000u;      // y = 1 half flips when nt is odd
+        hb[0][1][m] = hb[0][0][m] ^ 0x80008000u;
+        hb[1][1][m] = hb[1][0][m] ^ 0x80008000u;
+    }
+
+    // LDS addresses (dword units): one base per lane, the rest are immediates.
+    // Writer: load cp covers tile blocks 4cp .. 4cp+3; this lane holds chunk j = n16 of block
+    // 4cp + g; its dword c goes to row b, slot 4(j/4) + c + b, dword j%4.
+    const int wr_base = g * 128 + (4 * (n16 >> 2) + g) * 4 + (n16 & 3);
+    // Reader: MFMA row i = n16 is block beta(i); step c reads slot 4g + c + beta.
     const int rd_block = tile_block_of_row(n16);
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const int wb = 4 * c + g;
-        wr_slot[c] = wb * 16 + (n16 ^ wb);
-        rd_slot[c] = rd_block * 16 + ((4 * c + g) ^ rd_block);
-    }
-    // Lane that ends up holding the sum of squares of the block this lane finishes:
-    // row 4g + (n16 % 4) of the A layout, i.e. any lane whose lane%16 equals that row.
-    const int energy_src = 4 * g + (n16 & 3);
+    const int rd_base = rd_block * 128 + (4 * g + rd_block) * 4;
 
-    int64_t tile = blockIdx.x;
-    if (tile >= n_tiles) return;
-    u32x4 stage[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) stage[c] = x[tile * 256 + 64 * c + lane];
-    for (; tile < n_tiles; tile += gridDim.x) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) lds[wr_slot[c]] = stage[c];
-        __syncthreads();
-        u32x4 a[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) a[c] = lds[rd_slot[c]];
-        __syncthreads();
-        // Prefetch the next tile of this wave (the last iteration re-reads a valid tile).
-        const int64_t next = (tile + gridDim.x < n_tiles) ? tile + gridDim.x : n_tiles - 1;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) stage[c] = x[next * 256 + 64 * c + lane];
+    const int my_r = n16 & 3;
+    const bool owns_scales = (n16 >> 2) == g;     // lane (4g + r, g) holds the energy of row 4g + r
 
-        // Sum of squares of this lane's 32 values (Eq. ash_sigma), two chains.
-        float e0 = 0.0f, e1 = 0.0f;
+    {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const uint32_t w0 = a[c][0], w1 = a[c][1], w2 = a[c][2], w3 = a[c][3];
-            e0 = dot2_self_bf16(w0, e0);
-            e1 = dot2_self_bf16(w1, e1);
-            e0 = dot2_self_bf16(w2, e0);
-            e1 = dot2_self_bf16(w3, e1);
-        }
-        float energy = e0 + e1;
-        energy += __shfl_xor(energy, 16, 64);
-        energy += __shfl_xor(energy, 32, 64);     // every lane (i, *) now has the sum for row i
-        energy = __shfl(energy, energy_src, 64);  // ... and this lane the sum for its own block
-
-        // W = X H_128 (unnormalised rotation, Eq. ash_rotation without alpha / sqrt(B)).
-        f32x4 acc[8];
+        for (int p = 0; p < kTiles; ++p) {
+            const int64_t tile = first_tile + p;
+            if (tile >= n_tiles) break;
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt) acc[nt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            for (int cp = 0; cp < 4; ++cp) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const bf16x8 av = __builtin_bit_cast(bf16x8, a[c]);
-#pragma unroll
-            for (int nt = 0; nt < 8; ++nt) {
-                const u32x4 hw = {hb[c][nt][0], hb[c][nt][1], hb[c][nt][2], hb[c][nt][3]};
-                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, hw), acc[nt], 0, 0, 0);
+                for (int c = 0; c < 4; ++c) lds[wr_base + cp * 528 + 4 * c] = stage[p][cp][c];
             }
-        }
-
-        // max|W| per block row (16 lanes of a row share rows 4g .. 4g+3).
-        float wmax[4];
+            __syncthreads();
+            u32x4 a[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            float m = 0.0f;
-#pragma unroll
-            for (int nt = 0; nt < 8; ++nt) m = fmaxf(m, __builtin_fabsf(acc[nt][r]));
-            wmax[r] = row16_allreduce_max(m);
-        }
-        // Block scalars, computed by the lane for row r = n16 % 4 only.
-        const int my_r = n16 & 3;
-        const float my_wmax = my_r == 0 ? wmax[0] : my_r == 1 ? wmax[1] : my_r == 2 ? wmax[2] : wmax[3];
-        const float alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / 128.0f) + eps);   // Eq. ash_sigma, ash_alpha
-        const float s = (my_wmax * alpha) * (0.08838834764831845f / kQmax);               // Eq. post_scale, 1/sqrt(128)
-        const float to_code = my_wmax > 0.0f ? kQmax * __builtin_amdgcn_rcpf(my_wmax) : 0.0f;
-        if (n16 < 4) scales[tile * 16 + 4 * n16 + g] = make_float2(alpha, s);
+            for (int c = 0; c < 4; ++c) a[c] = *reinterpret_cast<const u32x4*>(&lds[rd_base + 4 * c]);
+            __syncthreads();
 
-        // Eq. quantization: codes of Z / s = W * (Q_max / max|W|); 8 consecutive codes per lane and row.
+            // W = X H_128 (unnormalised rotation of Eq. ash_rotation) and the Gram diagonal
+            // sum_j G_kj^2 (Eq. ash_sigma), all on the matrix cores.
+            f32x4 acc[8];
+            f32x4 gram = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt) acc[nt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bf16x8 av = __builtin_bit_cast(bf16x8, a[c]);
+                gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, av, gram, 0, 0, 0);
+#pragma unroll
+                for (int nt = 0; nt < 8; ++nt) {
+                    const int sign = __builtin_popcount(c & (nt >> 1)) & 1;
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        av, __builtin_bit_cast(bf16x8, hb[nt & 1][sign]), acc[nt], 0, 0, 0);
+                }
+            }
+
+            // max|W| of each block row, delivered to the lanes with lane % 4 == row.
+            float m[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float v = 0.0f;
+#pragma unroll
+                for (int nt = 0; nt < 8; ++nt) v = __builtin_fmaxf(v, __builtin_fabsf(acc[nt][r]));
+                m[r] = v;
+            }
+            const float wmax = row16_max_scatter(m[0], m[1], m[2], m[3], n16);
+            // Z / s = W * Q_max / max|W| in exact arithmetic (Eq. post_scale, Eq. quantization).
+            const float to_code = wmax > 0.0f ? kQmax * __builtin_amdgcn_rcpf(wmax) : 0.0f;
+            if (owns_scales) {
+                const float energy = my_r == 0 ? gram[0] : my_r == 1 ? gram[1] : my_r == 2 ? gram[2] : gram[3];
+                const float alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / 128.0f) + eps);   // Eq. ash_sigma, ash_alpha
+                const float s = (wmax * alpha) * (0.08838834764831845f / kQmax);                  // max|Z| / Q_max
+                store_stream<kStream>(&scales[tile * 16 + 4 * my_r + g], f32x2{alpha, s});
+            }
+
+            // 8 consecutive codes per lane and row; one contiguous 512-byte span per store.
 #define TACO_STORE_ROW(R)                                                                      \
-        {                                                                                      \
-            const float f = dpp_f32<kDppQuadBcast(R)>(to_code);                                \
-            u32x2 w;                                                                           \
-            w.x = pack_e4m3x4(acc[0][R] * f, acc[1][R] * f, acc[2][R] * f, acc[3][R] * f);     \
-            w.y = pack_e4m3x4(acc[4][R] * f, acc[5][R] * f, acc[6][R] * f, acc[7][R] * f);     \
-            payload[tile * 256 + 64 * R + lane] = w;                                           \
-        }
-        TACO_STORE_ROW(0)
-        TACO_STORE_ROW(1)
-        TACO_STORE_ROW(2)
-        TACO_STORE_ROW(3)
+            {                                                                                  \
+                const float f = dpp_f32<kDppQuadBcast(R)>(to_code);                            \
+                u32x2 w;                                                                       \
+                w.x = pack_e4m3x4(acc[0][R] * f, acc[1][R] * f, acc[2][R] * f, acc[3][R] * f); \
+                w.y = pack_e4m3x4(acc[4][R] * f, acc[5][R] * f, acc[6][R] * f, acc[7][R] * f); \
+                store_stream<kStream>(&payload[tile * 256 + 64 * R + lane], w);                \
+            }
+            TACO_STORE_ROW(0)
+            TACO_STORE_ROW(1)
+            TACO_STORE_ROW(2)
+            TACO_STORE_ROW(3)
 #undef TACO_STORE_ROW
+        }
     }
 }
 
@@ -169,12 +200,38 @@ __global__ __launch_bounds__(64) void compress_b128_mfma_kernel(
 
 // out = bf16( sum_i  H (codes_i) * s_i / (alpha_i sqrt(128)) ), fp32 accumulation, i ascending.
 // payloads: n_tiles * 2048 codes each; scales: n_tiles * 16 records; out: n_tiles * 2048 bf16.
+// Workgroup w (one wave) handles output tiles [w * tiles_per_wave, (w+1) * tiles_per_wave) and
+// exits.  Its work is the flattened list of (tile, payload) items, payload fastest; a ring of
+// kRing items is kept in flight in registers.
+template <int kRing, bool kStream>
 __global__ __launch_bounds__(64) void decompress_sum_b128_mfma_kernel(
-    PayloadTable tab, int k, int64_t n_tiles, u32x4* __restrict__ out) {
+    PayloadTable tab, int k, int64_t n_tiles, int tiles_per_wave, u32x4* __restrict__ out) {
     __shared__ u32x4 lds[128];   // one tile of codes: 16 block rows x 8 chunks of 16 bytes
     const int lane = threadIdx.x;
     const int g = lane >> 4;
     const int n16 = lane & 15;
+    const int my_block = 4 * (n16 & 3) + g;   // block whose factor this lane computes
+
+    const int64_t tile_begin = static_cast<int64_t>(blockIdx.x) * tiles_per_wave;
+    int64_t tile_end = tile_begin + tiles_per_wave;
+    if (tile_end > n_tiles) tile_end = n_tiles;
+    const int n_items = static_cast<int>(tile_end - tile_begin) * k;
+
+    // Ring fill.  (pf_tile, pf_i) walks the item list ahead of the consumer.
+    u32x4 stage[kRing][2];
+    f32x2 stage_sc[kRing];
+    int64_t pf_tile = tile_begin;
+    int pf_i = 0;
+#pragma unroll
+    for (int p = 0; p < kRing; ++p) {
+        if (p < n_items) {
+            const u32x4* src = static_cast<const u32x4*>(tab.payload[pf_i]);
+            stage[p][0] = load16<kStream>(&src[pf_tile * 128 + lane]);
+            stage[p][1] = load16<kStream>(&src[pf_tile * 128 + 64 + lane]);
+            stage_sc[p] = static_cast<const f32x2*>(tab.scales[pf_i])[pf_tile * 16 + my_block];
+            if (++pf_i == k) { pf_i = 0; ++pf_tile; }
+        }
+    }
 
     // B operand: 8 column tiles of H_128 in E4M3 (+1 = 0x38, -1 = 0xB8), 32 bytes per lane each.
     // Slot (m, b) of lane (n16, g) is element e = 64 m + 16 g + b against position p = 8 n16 + nt:
@@ -209,43 +266,28 @@ __global__ __launch_bounds__(64) void decompress_sum_b128_mfma_kernel(
         wr_slot[m] = wb * 8 + ((lane & 7) ^ ((wb >> 1) & 7));
         rd_slot[m] = rd_block * 8 + ((4 * m + g) ^ ((rd_block >> 1) & 7));
     }
-    const int my_block = 4 * (n16 & 3) + g;   // block whose factor this lane computes
 
-    const int64_t total = n_tiles * k;
-    int64_t item = static_cast<int64_t>(blockIdx.x) * k;   // (tile, payload) pairs, payload fastest
-    const int64_t item_stride = static_cast<int64_t>(gridDim.x) * k;
-    if (item >= total) return;
-    u32x4 stage[2];
-    float2 stage_sc;
-    {
-        const u32x4* src = static_cast<const u32x4*>(tab.payload[0]);
-        stage[0] = src[(item / k) * 128 + lane];
-        stage[1] = src[(item / k) * 128 + 64 + lane];
-        stage_sc = static_cast<const float2*>(tab.scales[0])[(item / k) * 16 + my_block];
-    }
-    for (; item < total; item += item_stride) {
-        const int64_t tile = item / k;
-        f32x4 sum[8];
+    f32x4 sum[8];
+    int64_t tile = tile_begin;
+    int i = 0;
+    for (int q0 = 0; q0 < n_items; q0 += kRing) {
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt) sum[nt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-        for (int i = 0; i < k; ++i) {
-            lds[wr_slot[0]] = stage[0];
-            lds[wr_slot[1]] = stage[1];
-            const float2 sc = stage_sc;
+        for (int p = 0; p < kRing; ++p) {
+            const int q = q0 + p;
+            if (q >= n_items) break;
+            lds[wr_slot[0]] = stage[p][0];
+            lds[wr_slot[1]] = stage[p][1];
+            const f32x2 sc = stage_sc[p];
             __syncthreads();
             const u32x4 a0 = lds[rd_slot[0]];
             const u32x4 a1 = lds[rd_slot[1]];
             __syncthreads();
-            // Prefetch the next (tile, payload) pair (the very last one re-reads a valid tile).
-            {
-                int ni = i + 1;
-                int64_t nt_tile = tile;
-                if (ni == k) { ni = 0; nt_tile = tile + gridDim.x; }
-                if (nt_tile >= n_tiles) nt_tile = n_tiles - 1;
-                const u32x4* src = static_cast<const u32x4*>(tab.payload[ni]);
-                stage[0] = src[nt_tile * 128 + lane];
-                stage[1] = src[nt_tile * 128 + 64 + lane];
-                stage_sc = static_cast<const float2*>(tab.scales[ni])[nt_tile * 16 + my_block];
+            if (q + kRing < n_items) {      // refill this ring slot
+                const u32x4* src = static_cast<const u32x4*>(tab.payload[pf_i]);
+                stage[p][0] = load16<kStream>(&src[pf_tile * 128 + lane]);
+                stage[p][1] = load16<kStream>(&src[pf_tile * 128 + 64 + lane]);
+                stage_sc[p] = static_cast<const f32x2*>(tab.scales[pf_i])[pf_tile * 16 + my_block];
+                if (++pf_i == k) { pf_i = 0; ++pf_tile; }
             }
             i32x8 av;
             av[0] = a0.x; av[1] = a0.y; av[2] = a0.z; av[3] = a0.w;
@@ -257,30 +299,38 @@ __global__ __launch_bounds__(64) void decompress_sum_b128_mfma_kernel(
             for (int nt = 0; nt < 8; ++nt) {
                 i32x8 bv;
 #pragma unroll
-                for (int q = 0; q < 8; ++q) bv[q] = hb[nt][q];
+                for (int w = 0; w < 8; ++w) bv[w] = hb[nt][w];
                 d[nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
                     av, bv, f32x4{0.0f, 0.0f, 0.0f, 0.0f}, 0, 0, 0, 0, 0, 0);
             }
-#define TACO_ACC_ROW(R)                                                                        \
-            {                                                                                  \
-                const float f = dpp_f32<kDppQuadBcast(R)>(factor);                             \
-                _Pragma("unroll") for (int nt = 0; nt < 8; ++nt)                               \
-                    sum[nt][R] = __builtin_fmaf(d[nt][R], f, sum[nt][R]);                      \
-            }
-            TACO_ACC_ROW(0)
-            TACO_ACC_ROW(1)
-            TACO_ACC_ROW(2)
-            TACO_ACC_ROW(3)
-#undef TACO_ACC_ROW
-        }
+            const float f0 = dpp_f32<kDppQuadBcast(0)>(factor), f1 = dpp_f32<kDppQuadBcast(1)>(factor);
+            const float f2 = dpp_f32<kDppQuadBcast(2)>(factor), f3 = dpp_f32<kDppQuadBcast(3)>(factor);
+            if (i == 0) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            u32x4 w;
-            w.x = pack_bf16x2(sum[0][r], sum[1][r]);
-            w.y = pack_bf16x2(sum[2][r], sum[3][r]);
-            w.z = pack_bf16x2(sum[4][r], sum[5][r]);
-            w.w = pack_bf16x2(sum[6][r], sum[7][r]);
-            out[tile * 256 + 64 * r + lane] = w;
+                for (int nt = 0; nt < 8; ++nt)
+                    sum[nt] = f32x4{d[nt][0] * f0, d[nt][1] * f1, d[nt][2] * f2, d[nt][3] * f3};
+            } else {
+#pragma unroll
+                for (int nt = 0; nt < 8; ++nt) {
+                    sum[nt][0] = __builtin_fmaf(d[nt][0], f0, sum[nt][0]);
+                    sum[nt][1] = __builtin_fmaf(d[nt][1], f1, sum[nt][1]);
+                    sum[nt][2] = __builtin_fmaf(d[nt][2], f2, sum[nt][2]);
+                    sum[nt][3] = __builtin_fmaf(d[nt][3], f3, sum[nt][3]);
+                }
+            }
+            if (++i == k) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    u32x4 w;
+                    w.x = pack_bf16x2(sum[0][r], sum[1][r]);
+                    w.y = pack_bf16x2(sum[2][r], sum[3][r]);
+                    w.z = pack_bf16x2(sum[4][r], sum[5][r]);
+                    w.w = pack_bf16x2(sum[6][r], sum[7][r]);
+                    store_stream<kStream>(&out[tile * 256 + 64 * r + lane], w);
+                }
+                i = 0;
+                ++tile;
+            }
         }
     }
 }

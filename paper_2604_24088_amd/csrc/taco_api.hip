@@ -110,9 +110,11 @@ int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_par
     if (use_mfma(p)) {
         const int64_t n_tiles = n / taco::kTileElems;
         if (n_tiles > 0) {
-            hipLaunchKernelGGL(taco::compress_b128_mfma_kernel, dim3(grid_for(n_tiles, 8)), dim3(64), 0, st,
-                               static_cast<const taco::u32x4*>(x_bf16), n_tiles, p->tau, p->eps,
-                               static_cast<taco::u32x2*>(payload), static_cast<float2*>(scales));
+            constexpr int kTilesPerWave = 2;   // measured best on MI355X (1..4 tried)
+            const int64_t waves = (n_tiles + kTilesPerWave - 1) / kTilesPerWave;
+            hipLaunchKernelGGL((taco::compress_b128_mfma_kernel<kTilesPerWave, true>), dim3(static_cast<unsigned>(waves)),
+                               dim3(64), 0, st, static_cast<const taco::u32x4*>(x_bf16), n_tiles, p->tau, p->eps,
+                               static_cast<taco::u32x2*>(payload), static_cast<taco::f32x2*>(scales));
             if (int rc = launch_status()) return rc;
         }
         first_block = n_tiles * taco::kTileBlocks;
@@ -154,8 +156,13 @@ int taco_decompress_sum(const void* const* payloads, const void* const* scales, 
     if (use_mfma(p)) {
         const int64_t n_tiles = n / taco::kTileElems;
         if (n_tiles > 0) {
-            hipLaunchKernelGGL(taco::decompress_sum_b128_mfma_kernel, dim3(grid_for(n_tiles, 8)), dim3(64), 0, st,
-                               tab, static_cast<int>(k), n_tiles, static_cast<taco::u32x4*>(out_bf16));
+            // Two output tiles per wave and a ring of four (tile, payload) items in flight: measured
+            // best on MI355X for k = 1 and k = 8 (1..16 tiles, rings of 2..8 tried).
+            const int tiles_per_wave = 2;
+            const int64_t waves = (n_tiles + tiles_per_wave - 1) / tiles_per_wave;
+            hipLaunchKernelGGL((taco::decompress_sum_b128_mfma_kernel<4, true>), dim3(static_cast<unsigned>(waves)),
+                               dim3(64), 0, st, tab, static_cast<int>(k), n_tiles, tiles_per_wave,
+                               static_cast<taco::u32x4*>(out_bf16));
             if (int rc = launch_status()) return rc;
         }
         first_block = n_tiles * taco::kTileBlocks;
