@@ -37,8 +37,8 @@ MEASURED_TRAFFIC_BYTES = {
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="large_k8")
     ap.add_argument("--block", type=int, default=128)
     ap.add_argument("--impl", default="auto", choices=["auto", "butterfly", "mfma"])
@@ -179,7 +179,7 @@ def main():
         "calls": {"compress": call(t_comp, bytes_comp, 2.0 * n),
                   "decompress": call(t_dec, bytes_dec, 2.0 * n),
                   f"decompress_sum_k{k}": call(t_sum, bytes_sum, k * 2.0 * n)},
-        "roofline": {"kernel": "compress_b128_mfma_kernel<2,true>" if (B == 128 and args.impl != "butterfly") else "compress_butterfly_kernel",
+        "roofline": {"kernel": f"compress_mfma_kernel<{B // 128},2,true>" if (B >= 128 and args.impl != "butterfly") else f"compress_butterfly_kernel<{B}>",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, B, args.impl)),

@@ -64,9 +64,9 @@ typedef enum taco_status {
 
 enum { TACO_FORMAT_E4M3 = 0 };
 
-/* Kernel selection.  AUTO picks the matrix-core kernel when the block size has one and
- * the plain butterfly kernel otherwise; the other two values force one of them (used by
- * tests and benchmarks to compare the two). */
+/* Kernel selection.  AUTO picks the matrix-core kernel when the block size has one (128,
+ * 256, 512) and the plain butterfly kernel otherwise; the other two values force one of
+ * them (used by tests and benchmarks to compare the two). */
 enum { TACO_IMPL_AUTO = 0, TACO_IMPL_BUTTERFLY = 1, TACO_IMPL_MFMA = 2 };
 
 /* Hyper-parameters of Algorithm 1 ("Require" line): block size B, target energy tau,

@@ -1,0 +1,399 @@
+// Matrix-core kernels for block sizes B = 128, 256 and 512 on gfx950.
+//
+// The Hadamard rotation of Algorithm 1 runs as a dense product on MFMA.  A TILE is 2048
+// consecutive elements, seen as 16 UNITS (rows) of 128 elements:  V[16, 128] = X[16, 128] H_128.
+// Both operands are exact in the input format (bf16 data or E4M3 codes, +-1 entries), products
+// are exact and accumulation is fp32.  A block of B = 128 kRB elements is kRB consecutive units;
+// because H_B = H_kRB (x) H_128, its rotation is the 128-point product of each unit followed by
+// log2(kRB) butterfly stages ACROSS the units of the block, which live in registers of one lane.
+// Everything else (sum of squares, max|W|, the two block scalars, conversion) rides along in
+// the same pass, so each byte of the tensor crosses HBM once.
+//
+// One 64-lane wavefront per workgroup (the workgroup barrier is then free) handles a few
+// consecutive tiles and exits: no persistent loop.  The dispatcher hands out workgroups in
+// index order, so the tiles in flight form one dense, advancing window of memory, which
+// measured ~15 % faster on HBM than a grid-stride loop over the same tiles.
+//
+//   global -> registers   coalesced 16-byte non-temporal loads, 1 KiB per wave instruction
+//   registers -> LDS      the tile, unit row by unit row, swizzled
+//   LDS -> A operand      lane (i = lane%16, g = lane/16) reads 16-byte pieces of unit row i
+//   MFMA                  D[i][n] += sum_k A[i][k] B[k][n],  B = tiles of H_128 in registers
+//   D -> HBM              lane (n = lane%16, g), register r holds row 4g+r, column n
+//
+// Index maps (all bijections; correctness only needs the A and B operands to agree on them):
+//   unit of MFMA row i           u(i) = 4 (i % 4) + i / 4 for B = 128 (each store instruction of the
+//                                wave then covers one contiguous span); u(i) = i for B > 128 (the
+//                                units of a block must sit in one lane: rows 4g .. 4g+3)
+//   output position of column n  p(nt, n) = 8 n + nt   (nt = which of 8 MFMA column tiles): every lane
+//                                owns 8 consecutive outputs of each of its rows
+//   element of A slot            compress: e(c, g, m, y) = 8 (4 g + m) + 2 c + y,  c = MFMA step 0..3
+//                                decode:   e(m, g, b) = 64 m + 16 g + b,  m = 0..1, b = 0..15
+//   B entry                      H[e][p] = (-1)^popcount(e & p)
+#pragma once
+
+#include "butterfly_kernels.h"  // PayloadTable
+#include "device_util.h"
+
+namespace taco {
+
+constexpr int kTileElems = 2048;
+
+template <int kRB>
+__device__ __forceinline__ int unit_of_row(int i) {
+    return kRB == 1 ? 4 * (i & 3) + (i >> 2) : i;
+}
+
+// In-register butterfly across the kRB units of a block: v[r] -> sum_h (-1)^popcount(h & r) v[h]
+// within each aligned group of kRB registers (natural order, H_kRB).
+template <int kRB>
+__device__ __forceinline__ void units_butterfly(f32x4& v) {
+    if (kRB >= 2) {
+        const float a0 = v[0] + v[1], a1 = v[0] - v[1], a2 = v[2] + v[3], a3 = v[2] - v[3];
+        v[0] = a0; v[1] = a1; v[2] = a2; v[3] = a3;
+    }
+    if (kRB == 4) {
+        const float b0 = v[0] + v[2], b2 = v[0] - v[2], b1 = v[1] + v[3], b3 = v[1] - v[3];
+        v[0] = b0; v[1] = b1; v[2] = b2; v[3] = b3;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// compress
+// ------------------------------------------------------------------------------------------
+//
+// Element map of the compress kernel.  A 16-byte chunk j (0..15) of a unit holds 8 elements,
+// i.e. 4 dwords c = 0..3 of two bf16 (y = 0, 1):  e = 8 j + 2 c + y.  MFMA step c takes, from
+// the four chunks j = 4g + m (m = 0..3) of the lane's unit row, dword c: A slot t = 2m + y.
+// Against output position p = 8 n + nt the sign of H[e][p] splits into
+//     parity((4g+m) & n) ^ (y & nt)           a pattern that depends on nt only through nt & 1
+//   ^ parity(c & (nt >> 1))                   one sign for the whole MFMA
+// so four register tiles (two patterns, two signs) serve all 32 MFMAs of a tile.
+//
+// To hand step c its operand with one 16-byte LDS read, the tile is written to LDS
+// transposed at dword granularity: unit row b (padded to 512 bytes), 16-byte slot
+// (4 (j/4) + c + b) holds dword c of chunks 4 (j/4) .. 4 (j/4) + 3.  The "+ b" rotation
+// spreads the 16 rows a read instruction touches over all banks, and because rows are
+// padded the rotation never wraps: every LDS address is one per-lane base plus an
+// immediate.  Writes (4-byte) and reads (16-byte) are both bank-conflict free.
+
+constexpr int kCompressLdsDwords = 16 * 128;   // 16 unit rows of 128 dwords (64 used + rotation room)
+
+// Maximum, over the 16 lanes of a DPP row, of per-block values, for non-negative floats
+// (compared as unsigned integers).  m[r] is this lane's maximum over row r.
+//   kRB = 1: four blocks (rows); the maximum of row q ends up in the lanes with lane % 4 == q.
+//   kRB = 2: two blocks (rows 0-1, 2-3); block j ends up in the lanes with lane % 2 == j.
+//   kRB = 4: one block; every lane gets it.
+template <int kRB>
+__device__ __forceinline__ float row16_block_max(const float (&m)[4], int n16) {
+    const bool b0 = (n16 & 1) != 0, b1 = (n16 & 2) != 0;
+    uint32_t v;
+    if (kRB == 1) {
+        const uint32_t u0 = __builtin_bit_cast(uint32_t, m[0]), u1 = __builtin_bit_cast(uint32_t, m[1]);
+        const uint32_t u2 = __builtin_bit_cast(uint32_t, m[2]), u3 = __builtin_bit_cast(uint32_t, m[3]);
+        const uint32_t keep01 = b0 ? u1 : u0, send01 = b0 ? u0 : u1;
+        const uint32_t keep23 = b0 ? u3 : u2, send23 = b0 ? u2 : u3;
+        const uint32_t a0 = max(keep01, dpp_u32<0xB1>(send01));   // quad_perm [1,0,3,2]: lane ^ 1
+        const uint32_t a1 = max(keep23, dpp_u32<0xB1>(send23));
+        const uint32_t keep = b1 ? a1 : a0, send = b1 ? a0 : a1;
+        v = max(keep, dpp_u32<0x4E>(send));                       // quad_perm [2,3,0,1]: lane ^ 2
+    } else if (kRB == 2) {
+        const uint32_t u0 = __builtin_bit_cast(uint32_t, __builtin_fmaxf(m[0], m[1]));
+        const uint32_t u1 = __builtin_bit_cast(uint32_t, __builtin_fmaxf(m[2], m[3]));
+        const uint32_t keep = b0 ? u1 : u0, send = b0 ? u0 : u1;
+        v = max(keep, dpp_u32<0xB1>(send));
+        v = max(v, dpp_u32<0x4E>(v));
+    } else {
+        v = __builtin_bit_cast(uint32_t, __builtin_fmaxf(__builtin_fmaxf(m[0], m[1]), __builtin_fmaxf(m[2], m[3])));
+        v = max(v, dpp_u32<0xB1>(v));
+        v = max(v, dpp_u32<0x4E>(v));
+    }
+    v = max(v, dpp_u32<kDppRowRor(4)>(v));
+    v = max(v, dpp_u32<kDppRowRor(8)>(v));
+    return __builtin_bit_cast(float, v);
+}
+
+// x: n_tiles * 2048 bf16 (as 16-byte words); payload: n_tiles * 2048 codes (as 8-byte
+// words); scales: n_tiles * (16 / kRB) records {alpha, s}.  Block size B = 128 kRB.
+// Workgroup w (one wave) handles the kTiles consecutive tiles starting at w * kTiles; all its
+// loads are issued before the first tile is processed.
+template <int kRB, int kTiles, bool kStream>
+__global__ __launch_bounds__(64) void compress_mfma_kernel(
+    const u32x4* __restrict__ x, int64_t n_tiles, float tau, float eps,
+    u32x2* __restrict__ payload, f32x2* __restrict__ scales) {
+    static_assert(kRB == 1 || kRB == 2 || kRB == 4, "block size must be 128, 256 or 512");
+    constexpr int kBlock = 128 * kRB;
+    constexpr int kBlocksPerTile = 16 / kRB;
+    __shared__ uint32_t lds[kCompressLdsDwords];
+    const int lane = threadIdx.x;
+    const int g = lane >> 4;
+    const int n16 = lane & 15;
+    const int64_t first_tile = static_cast<int64_t>(blockIdx.x) * kTiles;
+
+    u32x4 stage[kTiles][4];
+#pragma unroll
+    for (int p = 0; p < kTiles; ++p) {
+        int64_t t = first_tile + p;
+        if (t >= n_tiles) t = n_tiles - 1;      // ragged last wave: re-read a valid tile, result unused
+#pragma unroll
+        for (int c = 0; c < 4; ++c) stage[p][c] = load16<kStream>(&x[t * 256 + 64 * c + lane]);
+    }
+
+    // B operand: patterns P0 / P1 (nt even / odd) and their negatives, 8 bf16 (+-1) per lane.
+    u32x4 hb[2][2];   // [nt & 1][sign]
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const uint32_t s0 = parity32((4 * g + m) & n16) ? 0x80008000u : 0u;
+        hb[0][0][m] = 0x3F803F80u ^ s0;
+        hb[1][0][m] = hb[0][0][m] ^ 0x80000000u;      // y = 1 half flips when nt is odd
+        hb[0][1][m] = hb[0][0][m] ^ 0x80008000u;
+        hb[1][1][m] = hb[1][0][m] ^ 0x80008000u;
+    }
+
+    // LDS addresses (dword units): one base per lane, the rest are immediates.
+    // Writer: load cp covers tile units 4cp .. 4cp+3; this lane holds chunk j = n16 of unit
+    // 4cp + g; its dword c goes to row b, slot 4(j/4) + c + b, dword j%4.
+    const int wr_base = g * 128 + (4 * (n16 >> 2) + g) * 4 + (n16 & 3);
+    // Reader: MFMA row i = n16 is unit u(i); step c reads slot 4g + c + u.
+    const int rd_unit = unit_of_row<kRB>(n16);
+    const int rd_base = rd_unit * 128 + (4 * g + rd_unit) * 4;
+
+    // Which block this lane finishes (computes alpha and s for, and stores them).  The Gram
+    // diagonal of row i sits in lane (i, i/4), register i%4, so only the quad n16/4 == g of
+    // each DPP row holds energies; within it the lane must also hold the block's max|W|.
+    const int q = n16 & 3;
+    bool owns_scales = (n16 >> 2) == g;
+    int my_block;                       // tile-local block index of the owned block
+    if (kRB == 1) { my_block = 4 * q + g; }
+    else if (kRB == 2) { owns_scales = owns_scales && ((q >> 1) == (q & 1)); my_block = 2 * g + (q & 1); }
+    else { owns_scales = owns_scales && q == 0; my_block = g; }
+
+#pragma unroll
+    for (int p = 0; p < kTiles; ++p) {
+        const int64_t tile = first_tile + p;
+        if (tile >= n_tiles) break;
+#pragma unroll
+        for (int cp = 0; cp < 4; ++cp) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) lds[wr_base + cp * 528 + 4 * c] = stage[p][cp][c];
+        }
+        __syncthreads();
+        u32x4 a[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) a[c] = *reinterpret_cast<const u32x4*>(&lds[rd_base + 4 * c]);
+        __syncthreads();
+
+        // V = X H_128 (unnormalised rotation of Eq. ash_rotation, per unit) and the Gram diagonal
+        // sum_j x_j^2 of every unit (Eq. ash_sigma), all on the matrix cores.
+        f32x4 acc[8];
+        f32x4 gram = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) acc[nt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const bf16x8 av = __builtin_bit_cast(bf16x8, a[c]);
+            gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, av, gram, 0, 0, 0);
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt) {
+                const int sign = __builtin_popcount(c & (nt >> 1)) & 1;
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                    av, __builtin_bit_cast(bf16x8, hb[nt & 1][sign]), acc[nt], 0, 0, 0);
+            }
+        }
+        // W = H_B G for blocks of more than one unit: butterfly across the block's units.
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) units_butterfly<kRB>(acc[nt]);
+
+        // max|W| of each block.
+        float m[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float v = 0.0f;
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt) v = __builtin_fmaxf(v, __builtin_fabsf(acc[nt][r]));
+            m[r] = v;
+        }
+        const float wmax = row16_block_max<kRB>(m, n16);
+        // Z / s = W * Q_max / max|W| in exact arithmetic (Eq. post_scale, Eq. quantization).
+        const float to_code = wmax > 0.0f ? kQmax * __builtin_amdgcn_rcpf(wmax) : 0.0f;
+
+        // Energy of the owned block: own Gram diagonal plus those of the block's other units,
+        // which sit in the neighbouring lanes of the quad.
+        float energy = q == 0 ? gram[0] : q == 1 ? gram[1] : q == 2 ? gram[2] : gram[3];
+        if (kRB >= 2) energy += dpp_f32<0xB1>(energy);
+        if (kRB == 4) energy += dpp_f32<0x4E>(energy);
+        if (owns_scales) {
+            const float alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / kBlock) + eps);   // Eq. ash_sigma, ash_alpha
+            const float inv_root_b = kRB == 1 ? 0.08838834764831845f : kRB == 2 ? 0.0625f : 0.04419417382415922f;
+            const float s = (wmax * alpha) * (inv_root_b / kQmax);                             // max|Z| / Q_max
+            store_stream<kStream>(&scales[tile * kBlocksPerTile + my_block], f32x2{alpha, s});
+        }
+
+        // 8 consecutive codes per lane and row.  The factor of row R's block comes from the quad
+        // lane that holds it (kRB = 1: lane R; kRB = 2: lane R / 2; kRB = 4: any).
+#define TACO_STORE_ROW(R)                                                                      \
+        {                                                                                      \
+            const float f = dpp_f32<kDppQuadBcast(kRB == 1 ? R : kRB == 2 ? R / 2 : 0)>(to_code); \
+            u32x2 w;                                                                           \
+            w.x = pack_e4m3x4(acc[0][R] * f, acc[1][R] * f, acc[2][R] * f, acc[3][R] * f);     \
+            w.y = pack_e4m3x4(acc[4][R] * f, acc[5][R] * f, acc[6][R] * f, acc[7][R] * f);     \
+            store_stream<kStream>(&payload[tile * 256 + unit_of_row<kRB>(4 * g + R) * 16 + n16], w); \
+        }
+        TACO_STORE_ROW(0)
+        TACO_STORE_ROW(1)
+        TACO_STORE_ROW(2)
+        TACO_STORE_ROW(3)
+#undef TACO_STORE_ROW
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// decompress / decompress_sum
+// ------------------------------------------------------------------------------------------
+
+// out = bf16( sum_i  H_B (codes_i) * s_i / (alpha_i sqrt(B)) ), fp32 accumulation, i ascending.
+// payloads: n_tiles * 2048 codes each; scales: n_tiles * (16 / kRB) records; out: n_tiles * 2048 bf16.
+// Workgroup w (one wave) handles output tiles [w * tiles_per_wave, (w+1) * tiles_per_wave) and
+// exits.  Its work is the flattened list of (tile, payload) items, payload fastest; a ring of
+// kRing items is kept in flight in registers.  For blocks of several units the per-payload work
+// is the 128-point product of every unit times the block factor; the butterfly across units is
+// linear, so it runs once on the accumulated sums.
+template <int kRB, int kRing, bool kStream>
+__global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
+    PayloadTable tab, int k, int64_t n_tiles, int tiles_per_wave, u32x4* __restrict__ out) {
+    static_assert(kRB == 1 || kRB == 2 || kRB == 4, "block size must be 128, 256 or 512");
+    constexpr int kBlocksPerTile = 16 / kRB;
+    __shared__ u32x4 lds[128];   // one tile of codes: 16 unit rows x 8 chunks of 16 bytes
+    const int lane = threadIdx.x;
+    const int g = lane >> 4;
+    const int n16 = lane & 15;
+    // Block whose factor this lane computes: the one that contains row 4g + n16 % 4.
+    const int my_block = unit_of_row<kRB>(4 * g + (n16 & 3)) / kRB;
+
+    const int64_t tile_begin = static_cast<int64_t>(blockIdx.x) * tiles_per_wave;
+    int64_t tile_end = tile_begin + tiles_per_wave;
+    if (tile_end > n_tiles) tile_end = n_tiles;
+    const int n_items = static_cast<int>(tile_end - tile_begin) * k;
+
+    // Ring fill.  (pf_tile, pf_i) walks the item list ahead of the consumer.
+    u32x4 stage[kRing][2];
+    f32x2 stage_sc[kRing];
+    int64_t pf_tile = tile_begin;
+    int pf_i = 0;
+#pragma unroll
+    for (int p = 0; p < kRing; ++p) {
+        if (p < n_items) {
+            const u32x4* src = static_cast<const u32x4*>(tab.payload[pf_i]);
+            stage[p][0] = load16<kStream>(&src[pf_tile * 128 + lane]);
+            stage[p][1] = load16<kStream>(&src[pf_tile * 128 + 64 + lane]);
+            stage_sc[p] = static_cast<const f32x2*>(tab.scales[pf_i])[pf_tile * kBlocksPerTile + my_block];
+            if (++pf_i == k) { pf_i = 0; ++pf_tile; }
+        }
+    }
+
+    // B operand: 8 column tiles of H_128 in E4M3 (+1 = 0x38, -1 = 0xB8), 32 bytes per lane each.
+    // Slot (m, b) of lane (n16, g) is element e = 64 m + 16 g + b against position p = 8 n16 + nt:
+    // sign = parity(b%8 & nt) ^ (b/8 & n16) ^ parity(g & (n16 >> 1)) ^ (m & n16 >> 3).
+    uint32_t hb[8][8];
+#pragma unroll
+    for (int d = 0; d < 8; ++d) {
+        const int m = d >> 2;
+        const int b_hi = (d & 3) >> 1;    // bit 3 of b for the 4 bytes of dword d
+        const int sgn = (b_hi & n16) ^ parity32(g & (n16 >> 1) & 3) ^ (m & (n16 >> 3));
+        const uint32_t lane_sign = (sgn & 1) ? 0x80808080u : 0u;
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) {
+            uint32_t w = 0x38383838u;
+#pragma unroll
+            for (int bb = 0; bb < 4; ++bb) {
+                const int b_lo = (4 * (d & 3) + bb) & 7;
+                w ^= static_cast<uint32_t>(__builtin_popcount(b_lo & nt) & 1) << (8 * bb + 7);
+            }
+            hb[nt][d] = w ^ lane_sign;
+        }
+    }
+
+    // LDS slots (16-byte units, 8 per unit row).  Writer: load m covers tile units 8m .. 8m+7,
+    // this lane holds chunk lane%8 of unit 8m + lane/8.  Reader: row i = n16 is unit u(i),
+    // half m wants chunk 4m + g.  The XOR swizzle keeps both sides bank-conflict free.
+    int wr_slot[2], rd_slot[2];
+    const int rd_unit = unit_of_row<kRB>(n16);
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const int wb = 8 * m + (lane >> 3);
+        wr_slot[m] = wb * 8 + ((lane & 7) ^ ((wb >> 1) & 7));
+        rd_slot[m] = rd_unit * 8 + ((4 * m + g) ^ ((rd_unit >> 1) & 7));
+    }
+    const float inv_root_b = kRB == 1 ? 0.08838834764831845f : kRB == 2 ? 0.0625f : 0.04419417382415922f;
+
+    f32x4 sum[8];
+    int64_t tile = tile_begin;
+    int i = 0;
+    for (int q0 = 0; q0 < n_items; q0 += kRing) {
+#pragma unroll
+        for (int p = 0; p < kRing; ++p) {
+            const int q = q0 + p;
+            if (q >= n_items) break;
+            lds[wr_slot[0]] = stage[p][0];
+            lds[wr_slot[1]] = stage[p][1];
+            const f32x2 sc = stage_sc[p];
+            __syncthreads();
+            const u32x4 a0 = lds[rd_slot[0]];
+            const u32x4 a1 = lds[rd_slot[1]];
+            __syncthreads();
+            if (q + kRing < n_items) {      // refill this ring slot
+                const u32x4* src = static_cast<const u32x4*>(tab.payload[pf_i]);
+                stage[p][0] = load16<kStream>(&src[pf_tile * 128 + lane]);
+                stage[p][1] = load16<kStream>(&src[pf_tile * 128 + 64 + lane]);
+                stage_sc[p] = static_cast<const f32x2*>(tab.scales[pf_i])[pf_tile * kBlocksPerTile + my_block];
+                if (++pf_i == k) { pf_i = 0; ++pf_tile; }
+            }
+            i32x8 av;
+            av[0] = a0.x; av[1] = a0.y; av[2] = a0.z; av[3] = a0.w;
+            av[4] = a1.x; av[5] = a1.y; av[6] = a1.z; av[7] = a1.w;
+            // Eq. recon_dequant .. recon_rescale: factor s / (alpha sqrt(B)) for this lane's block.
+            const float factor = sc.y * __builtin_amdgcn_rcpf(sc.x) * inv_root_b;
+            f32x4 d[8];
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt) {
+                i32x8 bv;
+#pragma unroll
+                for (int w = 0; w < 8; ++w) bv[w] = hb[nt][w];
+                d[nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                    av, bv, f32x4{0.0f, 0.0f, 0.0f, 0.0f}, 0, 0, 0, 0, 0, 0);
+            }
+            // Row r of this lane belongs to the block whose factor quad lane r computed.
+            const float f0 = dpp_f32<kDppQuadBcast(0)>(factor), f1 = dpp_f32<kDppQuadBcast(1)>(factor);
+            const float f2 = dpp_f32<kDppQuadBcast(2)>(factor), f3 = dpp_f32<kDppQuadBcast(3)>(factor);
+            if (i == 0) {
+#pragma unroll
+                for (int nt = 0; nt < 8; ++nt)
+                    sum[nt] = f32x4{d[nt][0] * f0, d[nt][1] * f1, d[nt][2] * f2, d[nt][3] * f3};
+            } else {
+#pragma unroll
+                for (int nt = 0; nt < 8; ++nt) {
+                    sum[nt][0] = __builtin_fmaf(d[nt][0], f0, sum[nt][0]);
+                    sum[nt][1] = __builtin_fmaf(d[nt][1], f1, sum[nt][1]);
+                    sum[nt][2] = __builtin_fmaf(d[nt][2], f2, sum[nt][2]);
+                    sum[nt][3] = __builtin_fmaf(d[nt][3], f3, sum[nt][3]);
+                }
+            }
+            if (++i == k) {
+#pragma unroll
+                for (int nt = 0; nt < 8; ++nt) units_butterfly<kRB>(sum[nt]);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    u32x4 w;
+                    w.x = pack_bf16x2(sum[0][r], sum[1][r]);
+                    w.y = pack_bf16x2(sum[2][r], sum[3][r]);
+                    w.z = pack_bf16x2(sum[4][r], sum[5][r]);
+                    w.w = pack_bf16x2(sum[6][r], sum[7][r]);
+                    store_stream<kStream>(&out[tile * 256 + unit_of_row<kRB>(4 * g + r) * 16 + n16], w);
+                }
+                i = 0;
+                ++tile;
+            }
+        }
+    }
+}
+
+}  // namespace taco

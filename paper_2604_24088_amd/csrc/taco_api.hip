@@ -10,7 +10,7 @@
 #include "../../include/taco.h"
 #include "butterfly_kernels.h"
 #include "device_util.h"
-#include "mfma_b128_kernels.h"
+#include "mfma_kernels.h"
 
 namespace {
 
@@ -45,12 +45,12 @@ int check_common(int64_t rows, int64_t cols, const taco_params* p, int64_t* n_ou
     if (!block_ok(p->block)) return TACO_ERR_BLOCK;
     if (p->format != TACO_FORMAT_E4M3) return TACO_ERR_FORMAT;
     if (p->impl != TACO_IMPL_AUTO && p->impl != TACO_IMPL_BUTTERFLY && p->impl != TACO_IMPL_MFMA) return TACO_ERR_IMPL;
-    if (p->impl == TACO_IMPL_MFMA && p->block != 128) return TACO_ERR_IMPL;
+    if (p->impl == TACO_IMPL_MFMA && p->block < 128) return TACO_ERR_IMPL;
     *n_out = rows * cols;
     return TACO_OK;
 }
 
-bool use_mfma(const taco_params* p) { return p->block == 128 && p->impl != TACO_IMPL_BUTTERFLY; }
+bool use_mfma(const taco_params* p) { return p->block >= 128 && p->impl != TACO_IMPL_BUTTERFLY; }
 
 // Persistent grids: enough single-wave workgroups to fill every SIMD several times over.
 int grid_for(int64_t work_items, int waves_per_cu) {
@@ -111,13 +111,22 @@ int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_par
         const int64_t n_tiles = n / taco::kTileElems;
         if (n_tiles > 0) {
             constexpr int kTilesPerWave = 2;   // measured best on MI355X (1..4 tried)
-            const int64_t waves = (n_tiles + kTilesPerWave - 1) / kTilesPerWave;
-            hipLaunchKernelGGL((taco::compress_b128_mfma_kernel<kTilesPerWave, true>), dim3(static_cast<unsigned>(waves)),
-                               dim3(64), 0, st, static_cast<const taco::u32x4*>(x_bf16), n_tiles, p->tau, p->eps,
-                               static_cast<taco::u32x2*>(payload), static_cast<taco::f32x2*>(scales));
+            const unsigned waves = static_cast<unsigned>((n_tiles + kTilesPerWave - 1) / kTilesPerWave);
+            const auto* xin = static_cast<const taco::u32x4*>(x_bf16);
+            auto* pout = static_cast<taco::u32x2*>(payload);
+            auto* sout = static_cast<taco::f32x2*>(scales);
+            if (B == 128)
+                hipLaunchKernelGGL((taco::compress_mfma_kernel<1, kTilesPerWave, true>), dim3(waves), dim3(64), 0, st,
+                                   xin, n_tiles, p->tau, p->eps, pout, sout);
+            else if (B == 256)
+                hipLaunchKernelGGL((taco::compress_mfma_kernel<2, kTilesPerWave, true>), dim3(waves), dim3(64), 0, st,
+                                   xin, n_tiles, p->tau, p->eps, pout, sout);
+            else
+                hipLaunchKernelGGL((taco::compress_mfma_kernel<4, kTilesPerWave, true>), dim3(waves), dim3(64), 0, st,
+                                   xin, n_tiles, p->tau, p->eps, pout, sout);
             if (int rc = launch_status()) return rc;
         }
-        first_block = n_tiles * taco::kTileBlocks;
+        first_block = n_tiles * (taco::kTileElems / B);
     }
     const int64_t rest = n_blocks - first_block;
     if (rest > 0) {
@@ -159,13 +168,20 @@ int taco_decompress_sum(const void* const* payloads, const void* const* scales, 
             // Two output tiles per wave and a ring of four (tile, payload) items in flight: measured
             // best on MI355X for k = 1 and k = 8 (1..16 tiles, rings of 2..8 tried).
             const int tiles_per_wave = 2;
-            const int64_t waves = (n_tiles + tiles_per_wave - 1) / tiles_per_wave;
-            hipLaunchKernelGGL((taco::decompress_sum_b128_mfma_kernel<4, true>), dim3(static_cast<unsigned>(waves)),
-                               dim3(64), 0, st, tab, static_cast<int>(k), n_tiles, tiles_per_wave,
-                               static_cast<taco::u32x4*>(out_bf16));
+            const unsigned waves = static_cast<unsigned>((n_tiles + tiles_per_wave - 1) / tiles_per_wave);
+            auto* o = static_cast<taco::u32x4*>(out_bf16);
+            if (B == 128)
+                hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<1, 4, true>), dim3(waves), dim3(64), 0, st,
+                                   tab, static_cast<int>(k), n_tiles, tiles_per_wave, o);
+            else if (B == 256)
+                hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<2, 4, true>), dim3(waves), dim3(64), 0, st,
+                                   tab, static_cast<int>(k), n_tiles, tiles_per_wave, o);
+            else
+                hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<4, 4, true>), dim3(waves), dim3(64), 0, st,
+                                   tab, static_cast<int>(k), n_tiles, tiles_per_wave, o);
             if (int rc = launch_status()) return rc;
         }
-        first_block = n_tiles * taco::kTileBlocks;
+        first_block = n_tiles * (taco::kTileElems / B);
     }
     const int64_t rest = n_blocks - first_block;
     if (rest > 0) {

@@ -2,8 +2,9 @@
 and by the smoke check).  Tolerances:
 
   scales  alpha, s    |gpu - ref| <= 1e-6 * |ref|  (fp32 values; s = 0 must match exactly)
-  codes               identical on >= 99.99 % of elements, the rest at most one code away
-                      in sign-magnitude order, +0 and -0 merged.  Where the block scale s
+  codes               identical on >= 99.99 % of elements (at most one differing code in samples
+                      too small to resolve that), the rest at most one code away in
+                      sign-magnitude order, +0 and -0 merged.  Where the block scale s
                       is zero the sign bit is unspecified.
   reconstruction      per element |gpu - ref| <= max(one bf16 ulp of ref, 1e-3 * max|ref| of
                       its block); max|gpu - ref| / max|ref| over the tensor at most one bf16 ulp
@@ -61,7 +62,9 @@ def check_codes(gpu: np.ndarray, ref: np.ndarray, ref_scales: np.ndarray, block:
     assert np.all((gpu[zero_blocks] & 0x7F) == 0), f"{what}: non-zero code in an all-zero block"
     match = float((dist == 0).mean())
     assert dist.max() <= 1, f"{what}: a code is {dist.max()} steps from the oracle's"
-    assert match >= CODE_MATCH_MIN, f"{what}: only {match:.6f} of codes identical"
+    # A sample of fewer than 10^4 codes cannot resolve 99.99 %: there a single off-by-one code is let through.
+    allowed = max(1, int((1.0 - CODE_MATCH_MIN) * dist.size))
+    assert int((dist != 0).sum()) <= allowed, f"{what}: only {match:.6f} of codes identical"
     return match
 
 

@@ -24,8 +24,7 @@ import parity_util as P
 pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
-B = 128
-TILE = 16 * B
+TILE = 2048            # elements handled by one wave iteration of the matrix-core kernels, any block size
 N_SAMPLED_TILES = 96
 
 
@@ -44,19 +43,21 @@ def gather_tiles(flat: np.ndarray, tiles: np.ndarray, per_tile: int) -> np.ndarr
     return flat[idx]
 
 
-@pytest.mark.parametrize("name", ["gpt_rowpar", "qwen_act", "bwd_grad", "large_k8"])
-def test_full_size_workload(oracle, name):
+@pytest.mark.parametrize("name,B", [("gpt_rowpar", 128), ("qwen_act", 128), ("bwd_grad", 128), ("large_k8", 128),
+                                    ("gpt_rowpar", 256), ("qwen_act", 256), ("bwd_grad", 256), ("qwen_act", 512)])
+def test_full_size_workload(oracle, name, B):
     w = W.WORKLOADS[name]
     n = w.numel
     n_tiles = n // TILE
     k = w.payloads
     tiles = sampled_tiles(n_tiles, w.seed)
-    params = taco.taco_default_params()
+    params = taco.taco_default_params(block=B)
+    per_tile = TILE // B
     host = np.empty((w.tokens, w.hidden), dtype=np.uint16)
     payloads, scales, ref_payloads, ref_scales = [], [], [], []
     for i in range(k):
         W.generate(w, i, threads=16, out=host)
-        print(f"[{name}] payload {i}: generated", flush=True)
+        print(f"[{name}/B{B}] payload {i}: generated", flush=True)
         xd = to_dev(host)
         pl, sc = taco.taco_compress(xd, params)
         torch.cuda.synchronize()
@@ -65,13 +66,13 @@ def test_full_size_workload(oracle, name):
         x_s = gather_tiles(host.reshape(-1), tiles, TILE)
         rp, rs = oracle.compress(x_s, block=B)
         gp = gather_tiles(pl.cpu().numpy(), tiles, TILE)
-        gs = gather_tiles(sc.cpu().numpy().reshape(-1), tiles, 32).reshape(-1, 2)
-        P.check_scales(gs, rs, f"{name}[{i}]")
-        match = P.check_codes(gp, rp, rs, B, f"{name}[{i}]")
-        print(f"[{name}] payload {i}: compress parity ok, {match:.6f} of sampled codes identical", flush=True)
+        gs = gather_tiles(sc.cpu().numpy().reshape(-1), tiles, 2 * per_tile).reshape(-1, 2)
+        P.check_scales(gs, rs, f"{name}/B{B}[{i}]")
+        match = P.check_codes(gp, rp, rs, B, f"{name}/B{B}[{i}]")
+        print(f"[{name}/B{B}] payload {i}: compress parity ok, {match:.6f} of sampled codes identical", flush=True)
         # --- patch the oracle's payload into the sampled tiles for the decode test
         idx_c = torch.from_numpy((tiles[:, None] * TILE + np.arange(TILE)[None, :]).reshape(-1)).to(DEV)
-        idx_s = torch.from_numpy((tiles[:, None] * 16 + np.arange(16)[None, :]).reshape(-1)).to(DEV)
+        idx_s = torch.from_numpy((tiles[:, None] * per_tile + np.arange(per_tile)[None, :]).reshape(-1)).to(DEV)
         pl[idx_c] = torch.from_numpy(rp).to(DEV)
         sc[idx_s] = torch.from_numpy(rs).to(DEV)
         payloads.append(pl)
@@ -85,7 +86,7 @@ def test_full_size_workload(oracle, name):
     ref = oracle.decompress_sum(ref_payloads, ref_scales, tiles.size * TILE, block=B)
     exact = P.check_recon(got, ref, B, f"{name} decompress_sum k={k}",
                           min_exact=P.RECON_EXACT_MIN if k == 1 else P.RECON_EXACT_MIN_SUM)
-    print(f"[{name}] decompress_sum k={k}: parity ok, {exact:.6f} of sampled outputs identical", flush=True)
+    print(f"[{name}/B{B}] decompress_sum k={k}: parity ok, {exact:.6f} of sampled outputs identical", flush=True)
     if k == 1:
         out1 = taco.taco_decompress(payloads[0], scales[0], (w.tokens, w.hidden), params)
         torch.cuda.synchronize()

@@ -81,14 +81,51 @@ def test_compress_workload_slices(oracle, name, impl):
     P.check_codes(payload, rp, rs, 128, f"{name}/{impl}")
 
 
-@pytest.mark.parametrize("block", [32, 64, 256, 512])
-def test_compress_other_block_sizes(oracle, block):
-    w = W.WORKLOADS["qwen_act"]
-    x = sample_rows(w, rows=8)
-    payload, scales = run_compress(x, block, IMPLS["auto"])
+@pytest.mark.parametrize("block,impl", [(32, "auto"), (64, "auto"), (256, "mfma"), (256, "butterfly"),
+                                        (512, "mfma"), (512, "butterfly")])
+@pytest.mark.parametrize("name", ["qwen_act", "tiny", "bwd_grad"])
+def test_compress_other_block_sizes(oracle, block, impl, name):
+    w = W.WORKLOADS[name]
+    x = W.generate(w) if name == "tiny" else sample_rows(w, rows=8)
+    payload, scales = run_compress(x, block, IMPLS[impl])
+    rp, rs = oracle.compress(x, block=block)
+    P.check_scales(scales, rs, f"B={block}/{impl}")
+    P.check_codes(payload, rp, rs, block, f"B={block}/{impl}")
+
+
+@pytest.mark.parametrize("block", [256, 512])
+def test_compress_degenerate_blocks_large_b(oracle, block):
+    rng = np.random.default_rng(block)
+    g = np.zeros((2 * 2048 // block * 3, block), dtype=np.float32)
+    g[1, block - 3] = -0.0234375                  # single outlier in the last unit of the block
+    g[2, :] = 0.0078125                           # constant block
+    g[3, 130] = 1.5
+    g[4, :] = np.float32(2.0 ** -60)
+    g[5] = rng.standard_normal(block) * 1e-4
+    g[6, :128] = rng.standard_normal(128) * 0.02  # energy only in the first unit
+    g[7, block - 128:] = rng.standard_normal(128) * 0.02
+    x = W.float32_to_bf16_bits(g)
+    payload, scales = run_compress(x, block, IMPLS["mfma"])
     rp, rs = oracle.compress(x, block=block)
     P.check_scales(scales, rs, f"B={block}")
     P.check_codes(payload, rp, rs, block, f"B={block}")
+    codes = payload.reshape(-1, block)
+    assert np.all((codes[1] & 0x7F) == 0x7E)
+    assert (codes[2, 0] & 0x7F) == 0x7E and np.all((codes[2, 1:] & 0x7F) == 0)
+
+
+@pytest.mark.parametrize("block,n", [(256, 3 * 2048 + 5 * 256 + 77), (512, 2 * 2048 + 512 + 1), (256, 255), (512, 2048)])
+def test_compress_ragged_sizes_large_b(oracle, block, n):
+    rng = np.random.default_rng(n)
+    x = W.float32_to_bf16_bits((rng.standard_normal(n) * 0.02).astype(np.float32))
+    padded = np.concatenate([x, np.zeros((-n) % 8, dtype=np.uint16)])
+    p = taco.taco_default_params(block=block)
+    payload, scales = taco.taco_compress(to_dev(padded)[:n], p)
+    torch.cuda.synchronize()
+    rp, rs = oracle.compress(x, block=block)
+    assert payload.numel() == rp.size and scales.numel() == rs.size
+    P.check_scales(scales.cpu().numpy(), rs, f"B={block} n={n}")
+    P.check_codes(payload.cpu().numpy(), rp, rs, block, f"B={block} n={n}")
 
 
 @pytest.mark.parametrize("n", [1, 127, 128, 129, 2047, 2048, 2049, 5 * 2048 + 300, 37 * 2048 + 128 * 5 + 77])
@@ -169,12 +206,13 @@ def test_decompress_oracle_payload(oracle, name, impl):
     P.check_recon(bits_of(out), ref, 128, f"{name}/{impl}")
 
 
-@pytest.mark.parametrize("block", [32, 64, 256, 512])
-def test_decompress_other_block_sizes(oracle, block):
+@pytest.mark.parametrize("block,impl", [(32, "auto"), (64, "auto"), (256, "mfma"), (256, "butterfly"),
+                                        (512, "mfma"), (512, "butterfly")])
+def test_decompress_other_block_sizes(oracle, block, impl):
     x = sample_rows(W.WORKLOADS["gpt_rowpar"], rows=8)
     rp, rs = oracle.compress(x, block=block)
     ref = oracle.decompress(rp, rs, x.size, block=block)
-    p = taco.taco_default_params(block=block)
+    p = taco.taco_default_params(block=block, impl=IMPLS[impl])
     out = taco.taco_decompress(torch.from_numpy(rp).to(DEV), torch.from_numpy(rs).to(DEV), x.shape, p)
     torch.cuda.synchronize()
     P.check_recon(bits_of(out), ref, block, f"B={block}")
@@ -261,7 +299,7 @@ def test_decompress_sum(oracle, k, impl):
 
 def test_decompress_sum_ragged_and_other_blocks(oracle):
     rng = np.random.default_rng(4)
-    for block, n in ((128, 2048 * 2 + 700), (256, 5000), (64, 3000)):
+    for block, n in ((128, 2048 * 2 + 700), (256, 5000), (64, 3000), (512, 2048 * 3 + 512 + 9), (256, 2048 * 6)):
         ps, ss = [], []
         for i in range(3):
             x = W.float32_to_bf16_bits((rng.standard_normal(n) * 0.02).astype(np.float32))
