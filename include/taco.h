@@ -58,15 +58,15 @@ typedef enum taco_status {
     TACO_ERR_K = -5,      /* k outside 1..TACO_MAX_K                                  */
     TACO_ERR_FORMAT = -6, /* params->format is not TACO_FORMAT_E4M3                   */
     TACO_ERR_LAUNCH = -7, /* the HIP runtime refused the launch (hipGetLastError)     */
-    TACO_ERR_IMPL = -8,   /* params->impl names a kernel that cannot run this shape   */
+    TACO_ERR_IMPL = -8,   /* params->impl is not one of TACO_IMPL_*                   */
     TACO_ERR_PARAM = -9   /* tau <= 0, eps < 0, or a non-finite parameter             */
 } taco_status;
 
 enum { TACO_FORMAT_E4M3 = 0 };
 
-/* Kernel selection.  AUTO picks the matrix-core kernel when the block size has one (128,
- * 256, 512) and the plain butterfly kernel otherwise; the other two values force one of
- * them (used by tests and benchmarks to compare the two). */
+/* Kernel selection.  AUTO and MFMA run whole tiles of 2048 elements on the matrix-core
+ * kernel and the rest of the tensor on the plain butterfly kernel; BUTTERFLY runs everything
+ * on the butterfly kernel (kept for tests and benchmarks that compare the two). */
 enum { TACO_IMPL_AUTO = 0, TACO_IMPL_BUTTERFLY = 1, TACO_IMPL_MFMA = 2 };
 
 /* Hyper-parameters of Algorithm 1 ("Require" line): block size B, target energy tau,

@@ -1,4 +1,4 @@
-// Matrix-core kernels for block sizes B = 128, 256 and 512 on gfx950.
+// Matrix-core kernels for block sizes B = 32 .. 512 on gfx950.
 //
 // The Hadamard rotation of Algorithm 1 runs as a dense product on MFMA.  A TILE is 2048
 // consecutive elements, seen as 16 UNITS (rows) of 128 elements:  V[16, 128] = X[16, 128] H_128.
@@ -6,6 +6,9 @@
 // are exact and accumulation is fp32.  A block of B = 128 kRB elements is kRB consecutive units;
 // because H_B = H_kRB (x) H_128, its rotation is the 128-point product of each unit followed by
 // log2(kRB) butterfly stages ACROSS the units of the block, which live in registers of one lane.
+// A block of B = 128 / kSub elements (kSub = 2, 4) is an aligned part of a unit; the product
+// then uses I_kSub (x) H_B instead of H_128: the same +-1 tiles with the entries that pair
+// different blocks set to zero (a whole lane of the B operand at a time).
 // Everything else (sum of squares, max|W|, the two block scalars, conversion) rides along in
 // the same pass, so each byte of the tensor crosses HBM once.
 //
@@ -37,6 +40,12 @@
 namespace taco {
 
 constexpr int kTileElems = 2048;
+
+template <int kBlock>
+__device__ __forceinline__ constexpr float inv_sqrt_block() {
+    return kBlock == 32 ? 0.17677669529663687f : kBlock == 64 ? 0.125f : kBlock == 128 ? 0.08838834764831845f
+         : kBlock == 256 ? 0.0625f : 0.04419417382415922f;
+}
 
 template <int kRB>
 __device__ __forceinline__ int unit_of_row(int i) {
@@ -112,17 +121,39 @@ __device__ __forceinline__ float row16_block_max(const float (&m)[4], int n16) {
     return __builtin_bit_cast(float, v);
 }
 
+// Blocks smaller than a unit (kSub = 2 or 4 blocks per row): the outputs of block (row, sub) sit
+// in the 16 / kSub lanes with lane / (16 / kSub) == sub.  The maximum of row q's block ends up in
+// the lanes with lane % 4 == q of that lane group.
+template <int kSub>
+__device__ __forceinline__ float sub_block_max(const float (&m)[4], int n16) {
+    const bool b0 = (n16 & 1) != 0, b1 = (n16 & 2) != 0;
+    uint32_t u[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        u[r] = __builtin_bit_cast(uint32_t, m[r]);
+        if (kSub == 2) u[r] = max(u[r], dpp_u32<0x141>(u[r]));    // row_half_mirror: joins the two quads of an 8-lane half
+    }
+    const uint32_t keep01 = b0 ? u[1] : u[0], send01 = b0 ? u[0] : u[1];
+    const uint32_t keep23 = b0 ? u[3] : u[2], send23 = b0 ? u[2] : u[3];
+    const uint32_t a0 = max(keep01, dpp_u32<0xB1>(send01));
+    const uint32_t a1 = max(keep23, dpp_u32<0xB1>(send23));
+    const uint32_t keep = b1 ? a1 : a0, send = b1 ? a0 : a1;
+    return __builtin_bit_cast(float, max(keep, dpp_u32<0x4E>(send)));
+}
+
 // x: n_tiles * 2048 bf16 (as 16-byte words); payload: n_tiles * 2048 codes (as 8-byte
-// words); scales: n_tiles * (16 / kRB) records {alpha, s}.  Block size B = 128 kRB.
+// words); scales: n_tiles * (2048 / B) records {alpha, s}.  Block size B = 128 kRB / kSub
+// (at most one of kRB, kSub differs from 1).
 // Workgroup w (one wave) handles the kTiles consecutive tiles starting at w * kTiles; all its
 // loads are issued before the first tile is processed.
-template <int kRB, int kTiles, bool kStream>
+template <int kRB, int kSub, int kTiles, bool kStream>
 __global__ __launch_bounds__(64) void compress_mfma_kernel(
     const u32x4* __restrict__ x, int64_t n_tiles, float tau, float eps,
     u32x2* __restrict__ payload, f32x2* __restrict__ scales) {
-    static_assert(kRB == 1 || kRB == 2 || kRB == 4, "block size must be 128, 256 or 512");
-    constexpr int kBlock = 128 * kRB;
-    constexpr int kBlocksPerTile = 16 / kRB;
+    static_assert((kRB == 1 || kRB == 2 || kRB == 4) && (kSub == 1 || kSub == 2 || kSub == 4) && (kRB == 1 || kSub == 1),
+                  "block size must be 32, 64, 128, 256 or 512");
+    constexpr int kBlock = 128 * kRB / kSub;
+    constexpr int kBlocksPerTile = 2048 / kBlock;
     __shared__ uint32_t lds[kCompressLdsDwords];
     const int lane = threadIdx.x;
     const int g = lane >> 4;
@@ -139,14 +170,22 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
     }
 
     // B operand: patterns P0 / P1 (nt even / odd) and their negatives, 8 bf16 (+-1) per lane.
+    // For kSub > 1 the element's block within the unit is eh (top bits of 4g+m, i.e. of g) and
+    // the output's is ph (top bits of n16): the entry is H_B's where eh == ph (the eh & ph term
+    // of the 128-point sign drops out) and zero elsewhere.
     u32x4 hb[2][2];   // [nt & 1][sign]
+    const int eh = kSub == 2 ? (g >> 1) : g;
+    const int ph = kSub == 2 ? (n16 >> 3) : (n16 >> 2);
+    const bool same_block = kSub == 1 || eh == ph;
+    const uint32_t block_flip = (kSub > 1 && parity32(eh & ph)) ? 0x80008000u : 0u;
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
-        const uint32_t s0 = parity32((4 * g + m) & n16) ? 0x80008000u : 0u;
-        hb[0][0][m] = 0x3F803F80u ^ s0;
-        hb[1][0][m] = hb[0][0][m] ^ 0x80000000u;      // y = 1 half flips when nt is odd
-        hb[0][1][m] = hb[0][0][m] ^ 0x80008000u;
-        hb[1][1][m] = hb[1][0][m] ^ 0x80008000u;
+        const uint32_t s0 = (parity32((4 * g + m) & n16) ? 0x80008000u : 0u) ^ block_flip;
+        const uint32_t base = 0x3F803F80u ^ s0;
+        hb[0][0][m] = same_block ? base : 0u;
+        hb[1][0][m] = same_block ? base ^ 0x80000000u : 0u;      // y = 1 half flips when nt is odd
+        hb[0][1][m] = same_block ? base ^ 0x80008000u : 0u;
+        hb[1][1][m] = same_block ? base ^ 0x00008000u : 0u;
     }
 
     // LDS addresses (dword units): one base per lane, the rest are immediates.
@@ -160,10 +199,16 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
     // Which block this lane finishes (computes alpha and s for, and stores them).  The Gram
     // diagonal of row i sits in lane (i, i/4), register i%4, so only the quad n16/4 == g of
     // each DPP row holds energies; within it the lane must also hold the block's max|W|.
+    // For kSub > 1 the energy comes from VALU partial sums instead (see below): lane (n16, g)
+    // finishes block (row 4g + n16 % 4, sub ph) and fetches its energy from the A-layout lane
+    // that summed that part of the row.
     const int q = n16 & 3;
     bool owns_scales = (n16 >> 2) == g;
     int my_block;                       // tile-local block index of the owned block
-    if (kRB == 1) { my_block = 4 * q + g; }
+    int energy_src = 0;                 // kSub > 1: lane holding the block's sum of squares
+    if (kSub == 4) { owns_scales = true; my_block = unit_of_row<1>(4 * g + q) * 4 + ph; energy_src = 16 * ph + 4 * g + q; }
+    else if (kSub == 2) { owns_scales = ((n16 >> 2) & 1) == 0; my_block = unit_of_row<1>(4 * g + q) * 2 + ph; energy_src = 32 * ph + 4 * g + q; }
+    else if (kRB == 1) { my_block = 4 * q + g; }
     else if (kRB == 2) { owns_scales = owns_scales && ((q >> 1) == (q & 1)); my_block = 2 * g + (q & 1); }
     else { owns_scales = owns_scales && q == 0; my_block = g; }
 
@@ -191,7 +236,7 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const bf16x8 av = __builtin_bit_cast(bf16x8, a[c]);
-            gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, av, gram, 0, 0, 0);
+            if (kSub == 1) gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, av, gram, 0, 0, 0);
 #pragma unroll
             for (int nt = 0; nt < 8; ++nt) {
                 const int sign = __builtin_popcount(c & (nt >> 1)) & 1;
@@ -212,19 +257,36 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
             for (int nt = 0; nt < 8; ++nt) v = __builtin_fmaxf(v, __builtin_fabsf(acc[nt][r]));
             m[r] = v;
         }
-        const float wmax = row16_block_max<kRB>(m, n16);
+        const float wmax = kSub == 1 ? row16_block_max<kRB>(m, n16) : sub_block_max<kSub>(m, n16);
         // Z / s = W * Q_max / max|W| in exact arithmetic (Eq. post_scale, Eq. quantization).
         const float to_code = wmax > 0.0f ? kQmax * __builtin_amdgcn_rcpf(wmax) : 0.0f;
 
         // Energy of the owned block: own Gram diagonal plus those of the block's other units,
         // which sit in the neighbouring lanes of the quad.
-        float energy = q == 0 ? gram[0] : q == 1 ? gram[1] : q == 2 ? gram[2] : gram[3];
-        if (kRB >= 2) energy += dpp_f32<0xB1>(energy);
-        if (kRB == 4) energy += dpp_f32<0x4E>(energy);
+        float energy;
+        if (kSub == 1) {
+            energy = q == 0 ? gram[0] : q == 1 ? gram[1] : q == 2 ? gram[2] : gram[3];
+            if (kRB >= 2) energy += dpp_f32<0xB1>(energy);
+            if (kRB == 4) energy += dpp_f32<0x4E>(energy);
+        } else {
+            // A-layout lane (i, g) holds elements 32g .. 32g+31 of unit row i: one block for
+            // B = 32, half a block for B = 64 (the other half is 16 lanes away).
+            float e0 = 0.0f, e1 = 0.0f;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t w0 = a[c][0], w1 = a[c][1], w2 = a[c][2], w3 = a[c][3];
+                e0 = dot2_self_bf16(w0, e0);
+                e1 = dot2_self_bf16(w1, e1);
+                e0 = dot2_self_bf16(w2, e0);
+                e1 = dot2_self_bf16(w3, e1);
+            }
+            energy = e0 + e1;
+            if (kSub == 2) energy += __shfl_xor(energy, 16, 64);
+            energy = __shfl(energy, energy_src, 64);
+        }
         if (owns_scales) {
             const float alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / kBlock) + eps);   // Eq. ash_sigma, ash_alpha
-            const float inv_root_b = kRB == 1 ? 0.08838834764831845f : kRB == 2 ? 0.0625f : 0.04419417382415922f;
-            const float s = (wmax * alpha) * (inv_root_b / kQmax);                             // max|Z| / Q_max
+            const float s = (wmax * alpha) * (inv_sqrt_block<kBlock>() / kQmax);               // max|Z| / Q_max
             store_stream<kStream>(&scales[tile * kBlocksPerTile + my_block], f32x2{alpha, s});
         }
 
@@ -257,17 +319,22 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
 // kRing items is kept in flight in registers.  For blocks of several units the per-payload work
 // is the 128-point product of every unit times the block factor; the butterfly across units is
 // linear, so it runs once on the accumulated sums.
-template <int kRB, int kRing, bool kStream>
+template <int kRB, int kSub, int kRing, bool kStream>
 __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
     PayloadTable tab, int k, int64_t n_tiles, int tiles_per_wave, u32x4* __restrict__ out) {
-    static_assert(kRB == 1 || kRB == 2 || kRB == 4, "block size must be 128, 256 or 512");
-    constexpr int kBlocksPerTile = 16 / kRB;
+    static_assert((kRB == 1 || kRB == 2 || kRB == 4) && (kSub == 1 || kSub == 2 || kSub == 4) && (kRB == 1 || kSub == 1),
+                  "block size must be 32, 64, 128, 256 or 512");
+    constexpr int kBlock = 128 * kRB / kSub;
+    constexpr int kBlocksPerTile = 2048 / kBlock;
     __shared__ u32x4 lds[128];   // one tile of codes: 16 unit rows x 8 chunks of 16 bytes
     const int lane = threadIdx.x;
     const int g = lane >> 4;
     const int n16 = lane & 15;
-    // Block whose factor this lane computes: the one that contains row 4g + n16 % 4.
-    const int my_block = unit_of_row<kRB>(4 * g + (n16 & 3)) / kRB;
+    // Block whose factor this lane computes: the one that contains this lane's outputs of row
+    // 4g + n16 % 4 (for kSub > 1 the part ph of that row; a quad never straddles two parts).
+    const int ph = kSub == 1 ? 0 : kSub == 2 ? (n16 >> 3) : (n16 >> 2);
+    const int my_block = kSub == 1 ? unit_of_row<kRB>(4 * g + (n16 & 3)) / kRB
+                                   : unit_of_row<kRB>(4 * g + (n16 & 3)) * kSub + ph;
 
     const int64_t tile_begin = static_cast<int64_t>(blockIdx.x) * tiles_per_wave;
     int64_t tile_end = tile_begin + tiles_per_wave;
@@ -293,12 +360,17 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
     // B operand: 8 column tiles of H_128 in E4M3 (+1 = 0x38, -1 = 0xB8), 32 bytes per lane each.
     // Slot (m, b) of lane (n16, g) is element e = 64 m + 16 g + b against position p = 8 n16 + nt:
     // sign = parity(b%8 & nt) ^ (b/8 & n16) ^ parity(g & (n16 >> 1)) ^ (m & n16 >> 3).
+    // For kSub > 1 the element's block within the unit is eh (top bits of e: m, then g / 2) and the
+    // output's is ph: entries with eh != ph are zero and the eh & ph term of the sign drops out.
     uint32_t hb[8][8];
 #pragma unroll
     for (int d = 0; d < 8; ++d) {
         const int m = d >> 2;
         const int b_hi = (d & 3) >> 1;    // bit 3 of b for the 4 bytes of dword d
-        const int sgn = (b_hi & n16) ^ parity32(g & (n16 >> 1) & 3) ^ (m & (n16 >> 3));
+        const int eh = kSub == 2 ? m : 2 * m + (g >> 1);
+        const bool same_block = kSub == 1 || eh == ph;
+        int sgn = (b_hi & n16) ^ parity32(g & (n16 >> 1) & 3) ^ (m & (n16 >> 3));
+        if (kSub > 1) sgn ^= parity32(eh & ph);
         const uint32_t lane_sign = (sgn & 1) ? 0x80808080u : 0u;
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) {
@@ -308,7 +380,7 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
                 const int b_lo = (4 * (d & 3) + bb) & 7;
                 w ^= static_cast<uint32_t>(__builtin_popcount(b_lo & nt) & 1) << (8 * bb + 7);
             }
-            hb[nt][d] = w ^ lane_sign;
+            hb[nt][d] = same_block ? (w ^ lane_sign) : 0u;
         }
     }
 
@@ -323,7 +395,7 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
         wr_slot[m] = wb * 8 + ((lane & 7) ^ ((wb >> 1) & 7));
         rd_slot[m] = rd_unit * 8 + ((4 * m + g) ^ ((rd_unit >> 1) & 7));
     }
-    const float inv_root_b = kRB == 1 ? 0.08838834764831845f : kRB == 2 ? 0.0625f : 0.04419417382415922f;
+    const float inv_root_b = inv_sqrt_block<kBlock>();
 
     f32x4 sum[8];
     int64_t tile = tile_begin;

@@ -45,12 +45,11 @@ int check_common(int64_t rows, int64_t cols, const taco_params* p, int64_t* n_ou
     if (!block_ok(p->block)) return TACO_ERR_BLOCK;
     if (p->format != TACO_FORMAT_E4M3) return TACO_ERR_FORMAT;
     if (p->impl != TACO_IMPL_AUTO && p->impl != TACO_IMPL_BUTTERFLY && p->impl != TACO_IMPL_MFMA) return TACO_ERR_IMPL;
-    if (p->impl == TACO_IMPL_MFMA && p->block < 128) return TACO_ERR_IMPL;
     *n_out = rows * cols;
     return TACO_OK;
 }
 
-bool use_mfma(const taco_params* p) { return p->block >= 128 && p->impl != TACO_IMPL_BUTTERFLY; }
+bool use_mfma(const taco_params* p) { return p->impl != TACO_IMPL_BUTTERFLY; }
 
 // Persistent grids: enough single-wave workgroups to fill every SIMD several times over.
 int grid_for(int64_t work_items, int waves_per_cu) {
@@ -115,15 +114,17 @@ int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_par
             const auto* xin = static_cast<const taco::u32x4*>(x_bf16);
             auto* pout = static_cast<taco::u32x2*>(payload);
             auto* sout = static_cast<taco::f32x2*>(scales);
-            if (B == 128)
-                hipLaunchKernelGGL((taco::compress_mfma_kernel<1, kTilesPerWave, true>), dim3(waves), dim3(64), 0, st,
-                                   xin, n_tiles, p->tau, p->eps, pout, sout);
-            else if (B == 256)
-                hipLaunchKernelGGL((taco::compress_mfma_kernel<2, kTilesPerWave, true>), dim3(waves), dim3(64), 0, st,
-                                   xin, n_tiles, p->tau, p->eps, pout, sout);
-            else
-                hipLaunchKernelGGL((taco::compress_mfma_kernel<4, kTilesPerWave, true>), dim3(waves), dim3(64), 0, st,
-                                   xin, n_tiles, p->tau, p->eps, pout, sout);
+#define TACO_LAUNCH_COMPRESS(RB, SUB)                                                                           \
+            hipLaunchKernelGGL((taco::compress_mfma_kernel<RB, SUB, kTilesPerWave, true>), dim3(waves), dim3(64), 0, st, \
+                               xin, n_tiles, p->tau, p->eps, pout, sout)
+            switch (B) {
+                case 32: TACO_LAUNCH_COMPRESS(1, 4); break;
+                case 64: TACO_LAUNCH_COMPRESS(1, 2); break;
+                case 128: TACO_LAUNCH_COMPRESS(1, 1); break;
+                case 256: TACO_LAUNCH_COMPRESS(2, 1); break;
+                default: TACO_LAUNCH_COMPRESS(4, 1); break;
+            }
+#undef TACO_LAUNCH_COMPRESS
             if (int rc = launch_status()) return rc;
         }
         first_block = n_tiles * (taco::kTileElems / B);
@@ -170,15 +171,17 @@ int taco_decompress_sum(const void* const* payloads, const void* const* scales, 
             const int tiles_per_wave = 2;
             const unsigned waves = static_cast<unsigned>((n_tiles + tiles_per_wave - 1) / tiles_per_wave);
             auto* o = static_cast<taco::u32x4*>(out_bf16);
-            if (B == 128)
-                hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<1, 4, true>), dim3(waves), dim3(64), 0, st,
-                                   tab, static_cast<int>(k), n_tiles, tiles_per_wave, o);
-            else if (B == 256)
-                hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<2, 4, true>), dim3(waves), dim3(64), 0, st,
-                                   tab, static_cast<int>(k), n_tiles, tiles_per_wave, o);
-            else
-                hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<4, 4, true>), dim3(waves), dim3(64), 0, st,
-                                   tab, static_cast<int>(k), n_tiles, tiles_per_wave, o);
+#define TACO_LAUNCH_DECODE(RB, SUB)                                                                            \
+            hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<RB, SUB, 4, true>), dim3(waves), dim3(64), 0, st,     \
+                               tab, static_cast<int>(k), n_tiles, tiles_per_wave, o)
+            switch (B) {
+                case 32: TACO_LAUNCH_DECODE(1, 4); break;
+                case 64: TACO_LAUNCH_DECODE(1, 2); break;
+                case 128: TACO_LAUNCH_DECODE(1, 1); break;
+                case 256: TACO_LAUNCH_DECODE(2, 1); break;
+                default: TACO_LAUNCH_DECODE(4, 1); break;
+            }
+#undef TACO_LAUNCH_DECODE
             if (int rc = launch_status()) return rc;
         }
         first_block = n_tiles * (taco::kTileElems / B);

@@ -64,7 +64,7 @@ A = 0x1000  # a fake, 16-byte aligned, non-null "device pointer": never derefere
     (dict(p=_params(block=96)), -3), (dict(p=_params(block=1024)), -3),
     (dict(x=A + 2), -4), (dict(payload=A + 8), -4), (dict(scales=A + 4), -4),
     (dict(p=_params(format=1)), -6),
-    (dict(p=_params(impl=7)), -8), (dict(p=_params(impl=2, block=64)), -8),
+    (dict(p=_params(impl=7)), -8), (dict(p=_params(impl=-1)), -8),
     (dict(p=_params(tau=0.0)), -9), (dict(p=_params(eps=-1.0)), -9), (dict(p=_params(tau=float("nan"))), -9),
 ])
 def test_compress_rejects_bad_arguments(args, status):

@@ -44,7 +44,8 @@ def gather_tiles(flat: np.ndarray, tiles: np.ndarray, per_tile: int) -> np.ndarr
 
 
 @pytest.mark.parametrize("name,B", [("gpt_rowpar", 128), ("qwen_act", 128), ("bwd_grad", 128), ("large_k8", 128),
-                                    ("gpt_rowpar", 256), ("qwen_act", 256), ("bwd_grad", 256), ("qwen_act", 512)])
+                                    ("gpt_rowpar", 256), ("qwen_act", 256), ("bwd_grad", 256), ("qwen_act", 512),
+                                    ("gpt_rowpar", 64), ("bwd_grad", 32)])
 def test_full_size_workload(oracle, name, B):
     w = W.WORKLOADS[name]
     n = w.numel

@@ -81,8 +81,8 @@ def test_compress_workload_slices(oracle, name, impl):
     P.check_codes(payload, rp, rs, 128, f"{name}/{impl}")
 
 
-@pytest.mark.parametrize("block,impl", [(32, "auto"), (64, "auto"), (256, "mfma"), (256, "butterfly"),
-                                        (512, "mfma"), (512, "butterfly")])
+@pytest.mark.parametrize("block,impl", [(32, "mfma"), (32, "butterfly"), (64, "mfma"), (64, "butterfly"),
+                                        (256, "mfma"), (256, "butterfly"), (512, "mfma"), (512, "butterfly")])
 @pytest.mark.parametrize("name", ["qwen_act", "tiny", "bwd_grad"])
 def test_compress_other_block_sizes(oracle, block, impl, name):
     w = W.WORKLOADS[name]
@@ -93,17 +93,20 @@ def test_compress_other_block_sizes(oracle, block, impl, name):
     P.check_codes(payload, rp, rs, block, f"B={block}/{impl}")
 
 
-@pytest.mark.parametrize("block", [256, 512])
-def test_compress_degenerate_blocks_large_b(oracle, block):
+@pytest.mark.parametrize("block", [32, 64, 256, 512])
+def test_compress_degenerate_blocks_other_b(oracle, block):
     rng = np.random.default_rng(block)
     g = np.zeros((2 * 2048 // block * 3, block), dtype=np.float32)
-    g[1, block - 3] = -0.0234375                  # single outlier in the last unit of the block
+    g[1, block - 3] = -0.0234375                  # single outlier near the end of the block
     g[2, :] = 0.0078125                           # constant block
-    g[3, 130] = 1.5
+    g[3, block // 2 + 2] = 1.5
     g[4, :] = np.float32(2.0 ** -60)
     g[5] = rng.standard_normal(block) * 1e-4
-    g[6, :128] = rng.standard_normal(128) * 0.02  # energy only in the first unit
-    g[7, block - 128:] = rng.standard_normal(128) * 0.02
+    part = min(block, 128)
+    g[6, :part] = rng.standard_normal(part) * 0.02  # energy only at the start of the block
+    g[7, block - part:] = rng.standard_normal(part) * 0.02
+    g[9] = rng.standard_normal(block) * 30.0      # neighbours of very different magnitude inside one unit
+    g[10] = rng.standard_normal(block) * 1e-3
     x = W.float32_to_bf16_bits(g)
     payload, scales = run_compress(x, block, IMPLS["mfma"])
     rp, rs = oracle.compress(x, block=block)
@@ -114,8 +117,9 @@ def test_compress_degenerate_blocks_large_b(oracle, block):
     assert (codes[2, 0] & 0x7F) == 0x7E and np.all((codes[2, 1:] & 0x7F) == 0)
 
 
-@pytest.mark.parametrize("block,n", [(256, 3 * 2048 + 5 * 256 + 77), (512, 2 * 2048 + 512 + 1), (256, 255), (512, 2048)])
-def test_compress_ragged_sizes_large_b(oracle, block, n):
+@pytest.mark.parametrize("block,n", [(256, 3 * 2048 + 5 * 256 + 77), (512, 2 * 2048 + 512 + 1), (256, 255), (512, 2048),
+                                     (64, 2048 * 2 + 64 * 3 + 5), (32, 2048 + 31), (32, 7)])
+def test_compress_ragged_sizes_other_b(oracle, block, n):
     rng = np.random.default_rng(n)
     x = W.float32_to_bf16_bits((rng.standard_normal(n) * 0.02).astype(np.float32))
     padded = np.concatenate([x, np.zeros((-n) % 8, dtype=np.uint16)])
@@ -206,10 +210,11 @@ def test_decompress_oracle_payload(oracle, name, impl):
     P.check_recon(bits_of(out), ref, 128, f"{name}/{impl}")
 
 
-@pytest.mark.parametrize("block,impl", [(32, "auto"), (64, "auto"), (256, "mfma"), (256, "butterfly"),
-                                        (512, "mfma"), (512, "butterfly")])
-def test_decompress_other_block_sizes(oracle, block, impl):
-    x = sample_rows(W.WORKLOADS["gpt_rowpar"], rows=8)
+@pytest.mark.parametrize("block,impl", [(32, "mfma"), (32, "butterfly"), (64, "mfma"), (64, "butterfly"),
+                                        (256, "mfma"), (256, "butterfly"), (512, "mfma"), (512, "butterfly")])
+@pytest.mark.parametrize("name", ["gpt_rowpar", "qwen_act"])
+def test_decompress_other_block_sizes(oracle, block, impl, name):
+    x = sample_rows(W.WORKLOADS[name], rows=8)
     rp, rs = oracle.compress(x, block=block)
     ref = oracle.decompress(rp, rs, x.size, block=block)
     p = taco.taco_default_params(block=block, impl=IMPLS[impl])
@@ -299,7 +304,8 @@ def test_decompress_sum(oracle, k, impl):
 
 def test_decompress_sum_ragged_and_other_blocks(oracle):
     rng = np.random.default_rng(4)
-    for block, n in ((128, 2048 * 2 + 700), (256, 5000), (64, 3000), (512, 2048 * 3 + 512 + 9), (256, 2048 * 6)):
+    for block, n in ((128, 2048 * 2 + 700), (256, 5000), (64, 3000), (512, 2048 * 3 + 512 + 9), (256, 2048 * 6),
+                     (32, 2048 * 4 + 40), (64, 2048 * 5)):
         ps, ss = [], []
         for i in range(3):
             x = W.float32_to_bf16_bits((rng.standard_normal(n) * 0.02).astype(np.float32))
