@@ -138,6 +138,21 @@ def main():
     copy_gbps = 2.0 * src.numel() * 10 / (cev[0].elapsed_time(cev[1]) * 1e6)
     del dst
 
+    # ---- outside the timed region: the fused decompress_sum -> compress call (reduce-scatter receive
+    # side feeding the all-gather send side) on the same payloads
+    fev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    fp = torch.empty_like(payloads[0])
+    fs = torch.empty_like(scales[0])
+    for _ in range(3):
+        taco.taco_decompress_sum_compress(payloads, scales, outk.shape, params, fp, fs, stream)
+    fev[0].record(stream)
+    for _ in range(10):
+        taco.taco_decompress_sum_compress(payloads, scales, outk.shape, params, fp, fs, stream)
+    fev[1].record(stream)
+    torch.cuda.synchronize()
+    t_fused = fev[0].elapsed_time(fev[1]) / 10
+    del fp, fs
+
     ms_step = wall * 1e3 / args.steps
     t_comp = sum(e[0].elapsed_time(e[1]) for e in events) / (args.steps * k)   # ms per compress launch
     t_dec = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
@@ -178,7 +193,8 @@ def main():
         "copy_yardstick_GBps": round(copy_gbps, 1),
         "calls": {"compress": call(t_comp, bytes_comp, 2.0 * n),
                   "decompress": call(t_dec, bytes_dec, 2.0 * n),
-                  f"decompress_sum_k{k}": call(t_sum, bytes_sum, k * 2.0 * n)},
+                  f"decompress_sum_k{k}": call(t_sum, bytes_sum, k * 2.0 * n),
+                  f"decompress_sum_compress_k{k} (not in the step)": call(t_fused, (k + 1) * per_elem * n, k * 2.0 * n)},
         "roofline": {"kernel": f"compress_mfma_kernel<{B // 128},2,true>" if (B >= 128 and args.impl != "butterfly") else f"compress_butterfly_kernel<{B}>",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),

@@ -108,6 +108,18 @@ int taco_decompress_sum(const void* const* payloads, const void* const* scales, 
                         int64_t rows, int64_t cols, const taco_params* p, void* out_bf16,
                         void* stream);
 
+/* Receive side of the reduce-scatter immediately followed by the send side of the all-gather
+ * (Section 4.4.2: the two-shot AllReduce is ReduceScatter + AllGather, and the reduced shard is
+ * compressed again for the AllGather).  Equals taco_decompress_sum into a bf16 tensor followed by
+ * taco_compress of that tensor, bit for bit, but the bf16 tensor never reaches device memory.
+ *   payloads, scales  in   HOST arrays of k device pointers (as for taco_decompress_sum)
+ *   payload_out       out  device, taco_payload_bytes(rows*cols, B) bytes
+ *   scales_out        out  device, taco_scales_bytes(rows*cols, B) bytes
+ * Outputs must not overlap any input. */
+int taco_decompress_sum_compress(const void* const* payloads, const void* const* scales, int32_t k,
+                                 int64_t rows, int64_t cols, const taco_params* p, void* payload_out,
+                                 void* scales_out, void* stream);
+
 /* Diagnostic: converts n device floats to E4M3 codes with the same hardware conversion
  * the compression kernels use (Cvt_FP8 of Eq. quantization), so that it can be compared
  * against a code table.  in_f32: device, n floats; out_codes: device, n bytes. */

@@ -50,6 +50,40 @@ __device__ __forceinline__ void fwht_wave(float (&v)[ButterflyShape<B>::kRegs], 
     }
 }
 
+// Sender side of Algorithm 1 for one block whose elements are already in registers
+// (v[r] = element lane + 64 r, zeros past the end of the tensor).
+template <int B>
+__device__ __forceinline__ void compress_block_butterfly(float (&v)[ButterflyShape<B>::kRegs], int lane, int64_t blk,
+                                                         float tau, float eps, uint8_t* __restrict__ payload,
+                                                         float2* __restrict__ scales) {
+    constexpr int R = ButterflyShape<B>::kRegs;
+    const float inv_root_b = 1.0f / __builtin_sqrtf(static_cast<float>(B));
+    float energy = 0.0f;
+#pragma unroll
+    for (int r = 0; r < R; ++r) energy = __builtin_fmaf(v[r], v[r], energy);
+    energy = wave_allreduce_sum(energy);                 // sum_j G_kj^2
+    fwht_wave<B>(v, lane);                               // W = H G_k (unnormalised)
+    float wmax = 0.0f;
+#pragma unroll
+    for (int r = 0; r < R; ++r) wmax = fmaxf(wmax, __builtin_fabsf(v[r]));
+    wmax = wave_allreduce_max(wmax);
+    // Eq. ash_sigma, Eq. ash_alpha; Z = alpha W / sqrt(B); Eq. post_scale.
+    const float alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / B) + eps);
+    const float zmax = wmax * alpha * inv_root_b;
+    const float s = zmax * (1.0f / kQmax);
+    // Z / s = Q_max W / max|W| in exact arithmetic; zero blocks map to zero codes.
+    const float to_code = wmax > 0.0f ? kQmax * __builtin_amdgcn_rcpf(wmax) : 0.0f;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int e = lane + 64 * r;
+        if (e < B) {
+            const float q = v[r] * to_code;
+            payload[blk * B + e] = static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_fp8_f32(q, q, 0, false) & 0xFF);
+        }
+    }
+    if (lane == 0) scales[blk] = make_float2(alpha, s);
+}
+
 // Sender side of Algorithm 1 for blocks [first_block, first_block + n_blocks).
 template <int B>
 __global__ __launch_bounds__(64) void compress_butterfly_kernel(
@@ -57,38 +91,15 @@ __global__ __launch_bounds__(64) void compress_butterfly_kernel(
     float eps, uint8_t* __restrict__ payload, float2* __restrict__ scales) {
     constexpr int R = ButterflyShape<B>::kRegs;
     const int lane = threadIdx.x;
-    const float inv_root_b = 1.0f / __builtin_sqrtf(static_cast<float>(B));
     for (int64_t blk = first_block + blockIdx.x; blk < first_block + n_blocks; blk += gridDim.x) {
         float v[R];
-        float energy = 0.0f;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int e = lane + 64 * r;
             const int64_t idx = blk * B + e;
             v[r] = (e < B && idx < n) ? bf16_bits_to_f32(x[idx]) : 0.0f;   // zero padding
-            energy = __builtin_fmaf(v[r], v[r], energy);
         }
-        energy = wave_allreduce_sum(energy);                 // sum_j G_kj^2
-        fwht_wave<B>(v, lane);                               // W = H G_k (unnormalised)
-        float wmax = 0.0f;
-#pragma unroll
-        for (int r = 0; r < R; ++r) wmax = fmaxf(wmax, __builtin_fabsf(v[r]));
-        wmax = wave_allreduce_max(wmax);
-        // Eq. ash_sigma, Eq. ash_alpha; Z = alpha W / sqrt(B); Eq. post_scale.
-        const float alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / B) + eps);
-        const float zmax = wmax * alpha * inv_root_b;
-        const float s = zmax * (1.0f / kQmax);
-        // Z / s = Q_max W / max|W| in exact arithmetic; zero blocks map to zero codes.
-        const float to_code = wmax > 0.0f ? kQmax * __builtin_amdgcn_rcpf(wmax) : 0.0f;
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int e = lane + 64 * r;
-            if (e < B) {
-                const float q = v[r] * to_code;
-                payload[blk * B + e] = static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_fp8_f32(q, q, 0, false) & 0xFF);
-            }
-        }
-        if (lane == 0) scales[blk] = make_float2(alpha, s);
+        compress_block_butterfly<B>(v, lane, blk, tau, eps, payload, scales);
     }
 }
 
@@ -97,45 +108,76 @@ struct PayloadTable {
     const void* scales[16];
 };
 
-// Receiver side of Algorithm 1 plus the local reduction over k payloads.  The rotation is
-// linear, so for k > 1 the codes are first combined with their block factors
-// s / (alpha sqrt(B)) and rotated once; for k = 1 the raw codes are rotated (exact partial
-// sums) and the factor is applied afterwards.
+// Receiver side of Algorithm 1 plus the local reduction over k payloads for one block; the
+// result (before the final rounding to bf16) is left in v.  The rotation is linear, so for
+// k > 1 the codes are first combined with their block factors s / (alpha sqrt(B)) and rotated
+// once; for k = 1 the raw codes are rotated (exact partial sums) and the factor is applied
+// afterwards.
+template <int B>
+__device__ __forceinline__ void decode_sum_block_butterfly(const PayloadTable& tab, int k, int64_t blk, int lane,
+                                                           float (&v)[ButterflyShape<B>::kRegs]) {
+    constexpr int R = ButterflyShape<B>::kRegs;
+    const float inv_root_b = 1.0f / __builtin_sqrtf(static_cast<float>(B));
+#pragma unroll
+    for (int r = 0; r < R; ++r) v[r] = 0.0f;
+    float single = 1.0f;
+    for (int i = 0; i < k; ++i) {
+        const uint8_t* codes = static_cast<const uint8_t*>(tab.payload[i]);
+        const float2 sc = static_cast<const float2*>(tab.scales[i])[blk];
+        const float factor = sc.y * __builtin_amdgcn_rcpf(sc.x) * inv_root_b;   // s / (alpha sqrt(B))
+        const float w = (k == 1) ? 1.0f : factor;
+        single = factor;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int e = lane + 64 * r;
+            if (e < B) {
+                const float q = __builtin_amdgcn_cvt_f32_fp8(codes[blk * B + e], 0);
+                v[r] = __builtin_fmaf(q, w, v[r]);
+            }
+        }
+    }
+    fwht_wave<B>(v, lane);
+    const float post = (k == 1) ? single : 1.0f;
+#pragma unroll
+    for (int r = 0; r < R; ++r) v[r] *= post;
+}
+
 template <int B>
 __global__ __launch_bounds__(64) void decompress_sum_butterfly_kernel(
     PayloadTable tab, int k, int64_t n, int64_t first_block, int64_t n_blocks,
     uint16_t* __restrict__ out) {
     constexpr int R = ButterflyShape<B>::kRegs;
     const int lane = threadIdx.x;
-    const float inv_root_b = 1.0f / __builtin_sqrtf(static_cast<float>(B));
     for (int64_t blk = first_block + blockIdx.x; blk < first_block + n_blocks; blk += gridDim.x) {
         float v[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) v[r] = 0.0f;
-        float single = 1.0f;
-        for (int i = 0; i < k; ++i) {
-            const uint8_t* codes = static_cast<const uint8_t*>(tab.payload[i]);
-            const float2 sc = static_cast<const float2*>(tab.scales[i])[blk];
-            const float factor = sc.y * __builtin_amdgcn_rcpf(sc.x) * inv_root_b;   // s / (alpha sqrt(B))
-            const float w = (k == 1) ? 1.0f : factor;
-            single = factor;
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const int e = lane + 64 * r;
-                if (e < B) {
-                    const float q = __builtin_amdgcn_cvt_f32_fp8(codes[blk * B + e], 0);
-                    v[r] = __builtin_fmaf(q, w, v[r]);
-                }
-            }
-        }
-        fwht_wave<B>(v, lane);
-        const float post = (k == 1) ? single : 1.0f;
+        decode_sum_block_butterfly<B>(tab, k, blk, lane, v);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int e = lane + 64 * r;
             const int64_t idx = blk * B + e;
-            if (e < B && idx < n) out[idx] = static_cast<uint16_t>(pack_bf16x2(v[r] * post, 0.0f) & 0xFFFF);
+            if (e < B && idx < n) out[idx] = static_cast<uint16_t>(pack_bf16x2(v[r], 0.0f) & 0xFFFF);
         }
+    }
+}
+
+// decompress_sum followed by compress of the bf16-rounded sum, block by block, without the
+// bf16 tensor leaving the registers.
+template <int B>
+__global__ __launch_bounds__(64) void decompress_sum_compress_butterfly_kernel(
+    PayloadTable tab, int k, int64_t n, int64_t first_block, int64_t n_blocks, float tau, float eps,
+    uint8_t* __restrict__ payload_out, float2* __restrict__ scales_out) {
+    constexpr int R = ButterflyShape<B>::kRegs;
+    const int lane = threadIdx.x;
+    for (int64_t blk = first_block + blockIdx.x; blk < first_block + n_blocks; blk += gridDim.x) {
+        float v[R];
+        decode_sum_block_butterfly<B>(tab, k, blk, lane, v);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int e = lane + 64 * r;
+            const int64_t idx = blk * B + e;
+            v[r] = (e < B && idx < n) ? bf16_bits_to_f32(pack_bf16x2(v[r], 0.0f) & 0xFFFF) : 0.0f;
+        }
+        compress_block_butterfly<B>(v, lane, blk, tau, eps, payload_out, scales_out);
     }
 }
 

@@ -141,87 +141,71 @@ __device__ __forceinline__ float sub_block_max(const float (&m)[4], int n16) {
     return __builtin_bit_cast(float, max(keep, dpp_u32<0x4E>(send)));
 }
 
-// x: n_tiles * 2048 bf16 (as 16-byte words); payload: n_tiles * 2048 codes (as 8-byte
-// words); scales: n_tiles * (2048 / B) records {alpha, s}.  Block size B = 128 kRB / kSub
-// (at most one of kRB, kSub differs from 1).
-// Workgroup w (one wave) handles the kTiles consecutive tiles starting at w * kTiles; all its
-// loads are issued before the first tile is processed.
-template <int kRB, int kSub, int kTiles, bool kStream>
-__global__ __launch_bounds__(64) void compress_mfma_kernel(
-    const u32x4* __restrict__ x, int64_t n_tiles, float tau, float eps,
-    u32x2* __restrict__ payload, f32x2* __restrict__ scales) {
+// Per-lane constants of the compress stage and the stage itself (everything after the tile
+// has been written to LDS).  Shared by the compress kernel and by the fused
+// decompress_sum -> compress kernel.
+template <int kRB, int kSub>
+struct CompressLane {
     static_assert((kRB == 1 || kRB == 2 || kRB == 4) && (kSub == 1 || kSub == 2 || kSub == 4) && (kRB == 1 || kSub == 1),
                   "block size must be 32, 64, 128, 256 or 512");
-    constexpr int kBlock = 128 * kRB / kSub;
-    constexpr int kBlocksPerTile = 2048 / kBlock;
-    __shared__ uint32_t lds[kCompressLdsDwords];
-    const int lane = threadIdx.x;
-    const int g = lane >> 4;
-    const int n16 = lane & 15;
-    const int64_t first_tile = static_cast<int64_t>(blockIdx.x) * kTiles;
+    static constexpr int kBlock = 128 * kRB / kSub;
+    static constexpr int kBlocksPerTile = 2048 / kBlock;
 
-    u32x4 stage[kTiles][4];
-#pragma unroll
-    for (int p = 0; p < kTiles; ++p) {
-        int64_t t = first_tile + p;
-        if (t >= n_tiles) t = n_tiles - 1;      // ragged last wave: re-read a valid tile, result unused
-#pragma unroll
-        for (int c = 0; c < 4; ++c) stage[p][c] = load16<kStream>(&x[t * 256 + 64 * c + lane]);
-    }
+    u32x4 hb[2][2];     // B operand: patterns P0 / P1 (nt even / odd) [first index] and their negatives [second]
+    int g, n16, q;
+    int rd_base;        // LDS dword address of this lane's A operand for step 0
+    bool owns_scales;   // this lane computes and stores {alpha, s} of one block
+    int my_block;       // ... that block (tile-local index)
+    int energy_src;     // kSub > 1: lane that holds the block's sum of squares
 
-    // B operand: patterns P0 / P1 (nt even / odd) and their negatives, 8 bf16 (+-1) per lane.
-    // For kSub > 1 the element's block within the unit is eh (top bits of 4g+m, i.e. of g) and
-    // the output's is ph (top bits of n16): the entry is H_B's where eh == ph (the eh & ph term
-    // of the 128-point sign drops out) and zero elsewhere.
-    u32x4 hb[2][2];   // [nt & 1][sign]
-    const int eh = kSub == 2 ? (g >> 1) : g;
-    const int ph = kSub == 2 ? (n16 >> 3) : (n16 >> 2);
-    const bool same_block = kSub == 1 || eh == ph;
-    const uint32_t block_flip = (kSub > 1 && parity32(eh & ph)) ? 0x80008000u : 0u;
+    __device__ __forceinline__ explicit CompressLane(int lane) {
+        g = lane >> 4;
+        n16 = lane & 15;
+        q = n16 & 3;
+        // For kSub > 1 the element's block within the unit is eh (top bits of 4g+m, i.e. of g) and
+        // the output's is ph (top bits of n16): the entry is H_B's where eh == ph (the eh & ph term
+        // of the 128-point sign drops out) and zero elsewhere.
+        const int eh = kSub == 2 ? (g >> 1) : g;
+        const int ph = kSub == 2 ? (n16 >> 3) : (n16 >> 2);
+        const bool same_block = kSub == 1 || eh == ph;
+        const uint32_t block_flip = (kSub > 1 && parity32(eh & ph)) ? 0x80008000u : 0u;
 #pragma unroll
-    for (int m = 0; m < 4; ++m) {
-        const uint32_t s0 = (parity32((4 * g + m) & n16) ? 0x80008000u : 0u) ^ block_flip;
-        const uint32_t base = 0x3F803F80u ^ s0;
-        hb[0][0][m] = same_block ? base : 0u;
-        hb[1][0][m] = same_block ? base ^ 0x80000000u : 0u;      // y = 1 half flips when nt is odd
-        hb[0][1][m] = same_block ? base ^ 0x80008000u : 0u;
-        hb[1][1][m] = same_block ? base ^ 0x00008000u : 0u;
-    }
-
-    // LDS addresses (dword units): one base per lane, the rest are immediates.
-    // Writer: load cp covers tile units 4cp .. 4cp+3; this lane holds chunk j = n16 of unit
-    // 4cp + g; its dword c goes to row b, slot 4(j/4) + c + b, dword j%4.
-    const int wr_base = g * 128 + (4 * (n16 >> 2) + g) * 4 + (n16 & 3);
-    // Reader: MFMA row i = n16 is unit u(i); step c reads slot 4g + c + u.
-    const int rd_unit = unit_of_row<kRB>(n16);
-    const int rd_base = rd_unit * 128 + (4 * g + rd_unit) * 4;
-
-    // Which block this lane finishes (computes alpha and s for, and stores them).  The Gram
-    // diagonal of row i sits in lane (i, i/4), register i%4, so only the quad n16/4 == g of
-    // each DPP row holds energies; within it the lane must also hold the block's max|W|.
-    // For kSub > 1 the energy comes from VALU partial sums instead (see below): lane (n16, g)
-    // finishes block (row 4g + n16 % 4, sub ph) and fetches its energy from the A-layout lane
-    // that summed that part of the row.
-    const int q = n16 & 3;
-    bool owns_scales = (n16 >> 2) == g;
-    int my_block;                       // tile-local block index of the owned block
-    int energy_src = 0;                 // kSub > 1: lane holding the block's sum of squares
-    if (kSub == 4) { owns_scales = true; my_block = unit_of_row<1>(4 * g + q) * 4 + ph; energy_src = 16 * ph + 4 * g + q; }
-    else if (kSub == 2) { owns_scales = ((n16 >> 2) & 1) == 0; my_block = unit_of_row<1>(4 * g + q) * 2 + ph; energy_src = 32 * ph + 4 * g + q; }
-    else if (kRB == 1) { my_block = 4 * q + g; }
-    else if (kRB == 2) { owns_scales = owns_scales && ((q >> 1) == (q & 1)); my_block = 2 * g + (q & 1); }
-    else { owns_scales = owns_scales && q == 0; my_block = g; }
-
-#pragma unroll
-    for (int p = 0; p < kTiles; ++p) {
-        const int64_t tile = first_tile + p;
-        if (tile >= n_tiles) break;
-#pragma unroll
-        for (int cp = 0; cp < 4; ++cp) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) lds[wr_base + cp * 528 + 4 * c] = stage[p][cp][c];
+        for (int m = 0; m < 4; ++m) {
+            const uint32_t s0 = (parity32((4 * g + m) & n16) ? 0x80008000u : 0u) ^ block_flip;
+            const uint32_t base = 0x3F803F80u ^ s0;
+            hb[0][0][m] = same_block ? base : 0u;
+            hb[1][0][m] = same_block ? base ^ 0x80000000u : 0u;      // y = 1 half flips when nt is odd
+            hb[0][1][m] = same_block ? base ^ 0x80008000u : 0u;
+            hb[1][1][m] = same_block ? base ^ 0x00008000u : 0u;
         }
-        __syncthreads();
+        // Reader: MFMA row i = n16 is unit u(i); step c reads slot 4g + c + u.
+        const int rd_unit = unit_of_row<kRB>(n16);
+        rd_base = rd_unit * 128 + (4 * g + rd_unit) * 4;
+        // Which block this lane finishes.  The Gram diagonal of row i sits in lane (i, i/4),
+        // register i%4, so only the quad n16/4 == g of each DPP row holds energies; within it the
+        // lane must also hold the block's max|W|.  For kSub > 1 the energy comes from VALU partial
+        // sums instead: lane (n16, g) finishes block (row 4g + n16 % 4, part ph) and fetches its
+        // energy from the A-layout lane that summed that part of the row.
+        owns_scales = (n16 >> 2) == g;
+        energy_src = 0;
+        if (kSub == 4) { owns_scales = true; my_block = unit_of_row<1>(4 * g + q) * 4 + ph; energy_src = 16 * ph + 4 * g + q; }
+        else if (kSub == 2) { owns_scales = ((n16 >> 2) & 1) == 0; my_block = unit_of_row<1>(4 * g + q) * 2 + ph; energy_src = 32 * ph + 4 * g + q; }
+        else if (kRB == 1) { my_block = 4 * q + g; }
+        else if (kRB == 2) { owns_scales = owns_scales && ((q >> 1) == (q & 1)); my_block = 2 * g + (q & 1); }
+        else { owns_scales = owns_scales && q == 0; my_block = g; }
+    }
+
+    // LDS dword address at which the lane that holds elements 8j .. 8j+7 of unit `unit` (as four
+    // dwords c = 0..3) stores dword c:  lds_slot(unit, j) + 4 c.
+    static __device__ __forceinline__ int lds_slot(int unit, int j) {
+        return unit * 128 + (4 * (j >> 2) + unit) * 4 + (j & 3);
+    }
+
+    // Sender side of Algorithm 1 for the tile that sits in LDS.  Ends with the wave past its last
+    // LDS read (a barrier follows the reads), so the caller may overwrite the buffer afterwards.
+    template <bool kStream>
+    __device__ __forceinline__ void tile_from_lds(const uint32_t* lds, int64_t tile, float tau, float eps,
+                                                  u32x2* __restrict__ payload, f32x2* __restrict__ scales) const {
         u32x4 a[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) a[c] = *reinterpret_cast<const u32x4*>(&lds[rd_base + 4 * c]);
@@ -306,6 +290,47 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
         TACO_STORE_ROW(3)
 #undef TACO_STORE_ROW
     }
+};
+
+// x: n_tiles * 2048 bf16 (as 16-byte words); payload: n_tiles * 2048 codes (as 8-byte
+// words); scales: n_tiles * (2048 / B) records {alpha, s}.  Block size B = 128 kRB / kSub
+// (at most one of kRB, kSub differs from 1).
+// Workgroup w (one wave) handles the kTiles consecutive tiles starting at w * kTiles; all its
+// loads are issued before the first tile is processed.
+template <int kRB, int kSub, int kTiles, bool kStream>
+__global__ __launch_bounds__(64) void compress_mfma_kernel(
+    const u32x4* __restrict__ x, int64_t n_tiles, float tau, float eps,
+    u32x2* __restrict__ payload, f32x2* __restrict__ scales) {
+    __shared__ uint32_t lds[kCompressLdsDwords];
+    const int lane = threadIdx.x;
+    const int64_t first_tile = static_cast<int64_t>(blockIdx.x) * kTiles;
+
+    u32x4 stage[kTiles][4];
+#pragma unroll
+    for (int p = 0; p < kTiles; ++p) {
+        int64_t t = first_tile + p;
+        if (t >= n_tiles) t = n_tiles - 1;      // ragged last wave: re-read a valid tile, result unused
+#pragma unroll
+        for (int c = 0; c < 4; ++c) stage[p][c] = load16<kStream>(&x[t * 256 + 64 * c + lane]);
+    }
+
+    const CompressLane<kRB, kSub> cl(lane);
+    // Writer: load cp covers tile units 4cp .. 4cp+3; this lane holds chunk j = lane % 16 of unit
+    // 4cp + lane / 16.  One base address, the rest are immediates (unit + 4 -> + 528 dwords).
+    const int wr_base = CompressLane<kRB, kSub>::lds_slot(lane >> 4, lane & 15);
+
+#pragma unroll
+    for (int p = 0; p < kTiles; ++p) {
+        const int64_t tile = first_tile + p;
+        if (tile >= n_tiles) break;
+#pragma unroll
+        for (int cp = 0; cp < 4; ++cp) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) lds[wr_base + cp * 528 + 4 * c] = stage[p][cp][c];
+        }
+        __syncthreads();
+        cl.template tile_from_lds<kStream>(lds, tile, tau, eps, payload, scales);
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -319,14 +344,21 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
 // kRing items is kept in flight in registers.  For blocks of several units the per-payload work
 // is the 128-point product of every unit times the block factor; the butterfly across units is
 // linear, so it runs once on the accumulated sums.
-template <int kRB, int kSub, int kRing, bool kStream>
+//
+// kRecompress = true turns the kernel into decompress_sum followed by compress of the
+// bf16-rounded sum (the receive side of the reduce-scatter feeding the send side of the
+// all-gather, Section 4.4.2): the finished tile goes to LDS in the compress stage's layout
+// instead of HBM, and `out` is unused.
+template <int kRB, int kSub, int kRing, bool kStream, bool kRecompress>
 __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
-    PayloadTable tab, int k, int64_t n_tiles, int tiles_per_wave, u32x4* __restrict__ out) {
+    PayloadTable tab, int k, int64_t n_tiles, int tiles_per_wave, u32x4* __restrict__ out,
+    float tau, float eps, u32x2* __restrict__ payload_out, f32x2* __restrict__ scales_out) {
     static_assert((kRB == 1 || kRB == 2 || kRB == 4) && (kSub == 1 || kSub == 2 || kSub == 4) && (kRB == 1 || kSub == 1),
                   "block size must be 32, 64, 128, 256 or 512");
     constexpr int kBlock = 128 * kRB / kSub;
     constexpr int kBlocksPerTile = 2048 / kBlock;
     __shared__ u32x4 lds[128];   // one tile of codes: 16 unit rows x 8 chunks of 16 bytes
+    __shared__ uint32_t lds_c[kRecompress ? kCompressLdsDwords : 1];   // the bf16 tile for the compress stage
     const int lane = threadIdx.x;
     const int g = lane >> 4;
     const int n16 = lane & 15;
@@ -396,6 +428,7 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
         rd_slot[m] = rd_unit * 8 + ((4 * m + g) ^ ((rd_unit >> 1) & 7));
     }
     const float inv_root_b = inv_sqrt_block<kBlock>();
+    const CompressLane<kRB, kSub> cl(lane);    // used by the recompress form only
 
     f32x4 sum[8];
     int64_t tile = tile_begin;
@@ -459,7 +492,21 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
                     w.y = pack_bf16x2(sum[2][r], sum[3][r]);
                     w.z = pack_bf16x2(sum[4][r], sum[5][r]);
                     w.w = pack_bf16x2(sum[6][r], sum[7][r]);
-                    store_stream<kStream>(&out[tile * 256 + unit_of_row<kRB>(4 * g + r) * 16 + n16], w);
+                    const int unit = unit_of_row<kRB>(4 * g + r);
+                    if (kRecompress) {
+                        // This lane holds elements 8 n16 .. 8 n16 + 7 of the unit: chunk j = n16.
+                        const int slot = CompressLane<kRB, kSub>::lds_slot(unit, n16);
+                        lds_c[slot] = w.x;
+                        lds_c[slot + 4] = w.y;
+                        lds_c[slot + 8] = w.z;
+                        lds_c[slot + 12] = w.w;
+                    } else {
+                        store_stream<kStream>(&out[tile * 256 + unit * 16 + n16], w);
+                    }
+                }
+                if (kRecompress) {
+                    __syncthreads();
+                    cl.template tile_from_lds<kStream>(lds_c, tile, tau, eps, payload_out, scales_out);
                 }
                 i = 0;
                 ++tile;

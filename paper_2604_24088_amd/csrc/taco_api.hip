@@ -172,8 +172,8 @@ int taco_decompress_sum(const void* const* payloads, const void* const* scales, 
             const unsigned waves = static_cast<unsigned>((n_tiles + tiles_per_wave - 1) / tiles_per_wave);
             auto* o = static_cast<taco::u32x4*>(out_bf16);
 #define TACO_LAUNCH_DECODE(RB, SUB)                                                                            \
-            hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<RB, SUB, 4, true>), dim3(waves), dim3(64), 0, st,     \
-                               tab, static_cast<int>(k), n_tiles, tiles_per_wave, o)
+            hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<RB, SUB, 4, true, false>), dim3(waves), dim3(64), 0, st, \
+                               tab, static_cast<int>(k), n_tiles, tiles_per_wave, o, 0.0f, 0.0f, nullptr, nullptr)
             switch (B) {
                 case 32: TACO_LAUNCH_DECODE(1, 4); break;
                 case 64: TACO_LAUNCH_DECODE(1, 2); break;
@@ -192,6 +192,63 @@ int taco_decompress_sum(const void* const* payloads, const void* const* scales, 
             constexpr int kB = decltype(bc)::value;
             hipLaunchKernelGGL(taco::decompress_sum_butterfly_kernel<kB>, dim3(grid_for(rest, 32)), dim3(64), 0, st,
                                tab, static_cast<int>(k), n, first_block, rest, static_cast<uint16_t*>(out_bf16));
+        });
+        if (rc) return rc;
+        if (int rc2 = launch_status()) return rc2;
+    }
+    return TACO_OK;
+}
+
+int taco_decompress_sum_compress(const void* const* payloads, const void* const* scales, int32_t k,
+                                 int64_t rows, int64_t cols, const taco_params* p, void* payload_out,
+                                 void* scales_out, void* stream) {
+    if (!payloads || !scales || !payload_out || !scales_out) return TACO_ERR_NULL;
+    if (k < 1 || k > TACO_MAX_K) return TACO_ERR_K;
+    int64_t n = 0;
+    if (int rc = check_common(rows, cols, p, &n)) return rc;
+    if (!(p->tau > 0.0f) || !(p->eps >= 0.0f) || !std::isfinite(p->tau) || !std::isfinite(p->eps)) return TACO_ERR_PARAM;
+    taco::PayloadTable tab{};
+    for (int i = 0; i < k; ++i) {
+        if (!payloads[i] || !scales[i]) return TACO_ERR_NULL;
+        if (!aligned16(payloads[i]) || !aligned16(scales[i])) return TACO_ERR_ALIGN;
+        tab.payload[i] = payloads[i];
+        tab.scales[i] = scales[i];
+    }
+    if (!aligned16(payload_out) || !aligned16(scales_out)) return TACO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int B = p->block;
+    const int64_t n_blocks = (n + B - 1) / B;
+    int64_t first_block = 0;
+    if (use_mfma(p)) {
+        const int64_t n_tiles = n / taco::kTileElems;
+        if (n_tiles > 0) {
+            const int tiles_per_wave = 2;
+            const unsigned waves = static_cast<unsigned>((n_tiles + tiles_per_wave - 1) / tiles_per_wave);
+            auto* pout = static_cast<taco::u32x2*>(payload_out);
+            auto* sout = static_cast<taco::f32x2*>(scales_out);
+#define TACO_LAUNCH_FUSED(RB, SUB)                                                                             \
+            hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<RB, SUB, 4, true, true>), dim3(waves), dim3(64), 0, st,  \
+                               tab, static_cast<int>(k), n_tiles, tiles_per_wave, nullptr, p->tau, p->eps, pout, sout)
+            switch (B) {
+                case 32: TACO_LAUNCH_FUSED(1, 4); break;
+                case 64: TACO_LAUNCH_FUSED(1, 2); break;
+                case 128: TACO_LAUNCH_FUSED(1, 1); break;
+                case 256: TACO_LAUNCH_FUSED(2, 1); break;
+                default: TACO_LAUNCH_FUSED(4, 1); break;
+            }
+#undef TACO_LAUNCH_FUSED
+            if (int rc = launch_status()) return rc;
+        }
+        first_block = n_tiles * (taco::kTileElems / B);
+    }
+    const int64_t rest = n_blocks - first_block;
+    if (rest > 0) {
+        const float tau = p->tau, eps = p->eps;
+        int rc = dispatch_block(B, [&](auto bc) {
+            constexpr int kB = decltype(bc)::value;
+            hipLaunchKernelGGL(taco::decompress_sum_compress_butterfly_kernel<kB>, dim3(grid_for(rest, 32)), dim3(64), 0, st,
+                               tab, static_cast<int>(k), n, first_block, rest, tau, eps,
+                               static_cast<uint8_t*>(payload_out), static_cast<float2*>(scales_out));
         });
         if (rc) return rc;
         if (int rc2 = launch_status()) return rc2;

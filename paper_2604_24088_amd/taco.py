@@ -21,7 +21,7 @@ TACO_FORMAT_E4M3 = 0
 TACO_IMPL_AUTO, TACO_IMPL_BUTTERFLY, TACO_IMPL_MFMA = 0, 1, 2
 
 EXPORTS = ("taco_default_params", "taco_payload_bytes", "taco_scales_bytes", "taco_compress",
-           "taco_decompress", "taco_decompress_sum", "taco_debug_cvt_e4m3", "taco_debug_copy", "taco_strerror",
+           "taco_decompress", "taco_decompress_sum", "taco_decompress_sum_compress", "taco_debug_cvt_e4m3", "taco_debug_copy", "taco_strerror",
            "taco_version")
 
 
@@ -65,6 +65,10 @@ def lib() -> ctypes.CDLL:
         L.taco_decompress_sum.argtypes = [c.POINTER(c.c_void_p), c.POINTER(c.c_void_p), c.c_int32,
                                           c.c_int64, c.c_int64, c.POINTER(taco_params),
                                           c.c_void_p, c.c_void_p]
+        L.taco_decompress_sum_compress.restype = c.c_int
+        L.taco_decompress_sum_compress.argtypes = [c.POINTER(c.c_void_p), c.POINTER(c.c_void_p), c.c_int32,
+                                                   c.c_int64, c.c_int64, c.POINTER(taco_params),
+                                                   c.c_void_p, c.c_void_p, c.c_void_p]
         L.taco_debug_cvt_e4m3.restype = c.c_int
         L.taco_debug_cvt_e4m3.argtypes = [c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p]
         L.taco_debug_copy.restype = c.c_int
@@ -169,6 +173,29 @@ def taco_decompress_sum(payloads: Sequence[torch.Tensor], scales: Sequence[torch
                                    _stream_handle(stream))
     _check(st, "taco_decompress_sum")
     return out
+
+
+def taco_decompress_sum_compress(payloads: Sequence[torch.Tensor], scales: Sequence[torch.Tensor], shape,
+                                 params: Optional[taco_params] = None,
+                                 payload_out: Optional[torch.Tensor] = None,
+                                 scales_out: Optional[torch.Tensor] = None, stream=None):
+    """Decode and add k payloads, round the sum to bf16 and compress it again, in one pass."""
+    p = params or taco_default_params()
+    k = len(payloads)
+    assert k == len(scales)
+    rows, cols = _rows_cols(tuple(shape))
+    n = rows * cols
+    dev = payloads[0].device
+    if payload_out is None:
+        payload_out = torch.empty(taco_payload_bytes(n, p.block), dtype=torch.uint8, device=dev)
+    if scales_out is None:
+        scales_out = torch.empty((taco_scales_bytes(n, p.block) // 8, 2), dtype=torch.float32, device=dev)
+    parr = (ctypes.c_void_p * max(k, 1))(*[t.data_ptr() for t in payloads])
+    sarr = (ctypes.c_void_p * max(k, 1))(*[t.data_ptr() for t in scales])
+    st = lib().taco_decompress_sum_compress(parr, sarr, k, rows, cols, ctypes.byref(p), payload_out.data_ptr(),
+                                            scales_out.data_ptr(), _stream_handle(stream))
+    _check(st, "taco_decompress_sum_compress")
+    return payload_out, scales_out
 
 
 def taco_debug_cvt_e4m3(values: torch.Tensor, stream=None) -> torch.Tensor:

@@ -83,6 +83,19 @@ def test_decompress_sum_rejects_bad_k(k, status):
     assert L.taco_decompress_sum(arr, arr, k, 4, 512, ctypes.byref(p), A, None) == status
 
 
+def test_fused_rejects_bad_arguments():
+    L = taco.lib()
+    p = _params()
+    arr = (ctypes.c_void_p * 2)(A, A)
+    assert L.taco_decompress_sum_compress(arr, arr, 2, 4, 512, ctypes.byref(p), 0, A, None) == -1
+    assert L.taco_decompress_sum_compress(arr, arr, 2, 4, 512, ctypes.byref(p), A, 0, None) == -1
+    assert L.taco_decompress_sum_compress(arr, arr, 0, 4, 512, ctypes.byref(p), A, A, None) == -5
+    assert L.taco_decompress_sum_compress(arr, arr, 2, 0, 512, ctypes.byref(p), A, A, None) == -2
+    assert L.taco_decompress_sum_compress(arr, arr, 2, 4, 512, ctypes.byref(p), A + 4, A, None) == -4
+    bad = _params(tau=-1.0)
+    assert L.taco_decompress_sum_compress(arr, arr, 2, 4, 512, ctypes.byref(bad), A, A, None) == -9
+
+
 def test_decompress_rejects_bad_arguments():
     L = taco.lib()
     p = _params()

@@ -92,6 +92,22 @@ def test_full_size_workload(oracle, name, B):
         out1 = taco.taco_decompress(payloads[0], scales[0], (w.tokens, w.hidden), params)
         torch.cuda.synchronize()
         assert torch.equal(out1, out)
+    # --- fused decompress_sum -> compress at full size: no bit differs from the two separate calls,
+    # and on the sampled tiles the blocks whose bf16 intermediate equals the oracle's meet the usual bar
+    fp, fs = taco.taco_decompress_sum_compress(payloads, scales, (w.tokens, w.hidden), params)
+    up, us = taco.taco_compress(out, params)
+    torch.cuda.synchronize()
+    assert torch.equal(fp, up) and torch.equal(fs, us)
+    rp2, rs2 = oracle.compress(ref, block=B)
+    same = np.all(got.reshape(-1, B) == ref.reshape(-1, B), axis=1)
+    gp2 = gather_tiles(fp.cpu().numpy(), tiles, TILE).reshape(-1, B)
+    gs2 = gather_tiles(fs.cpu().numpy().reshape(-1), tiles, 2 * per_tile).reshape(-1, 2)
+    assert same.mean() >= 0.5
+    P.check_scales(gs2[same], rs2[same], f"{name}/B{B} fused")
+    m2 = P.check_codes(gp2[same], rp2.reshape(-1, B)[same], rs2[same], B, f"{name}/B{B} fused")
+    print(f"[{name}/B{B}] fused sum->compress: identical to the two calls; {same.mean():.3f} of sampled blocks "
+          f"have the oracle's intermediate, {m2:.6f} of their codes identical", flush=True)
+    del fp, fs, up, us
     # --- properties that hold at any size, over the whole tensor
     sc_all = scales[0]
     assert torch.isfinite(sc_all).all() and (sc_all[:, 0] > 0).all() and (sc_all[:, 1] >= 0).all()

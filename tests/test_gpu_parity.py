@@ -334,3 +334,61 @@ def test_runs_on_a_side_stream(oracle):
     rp, rs = oracle.compress(x)
     P.check_codes(payload.cpu().numpy(), rp, rs, 128, "stream")
     assert out.shape == x.shape
+
+
+# ---- decompress_sum followed by compress, fused ----------------------------------------------
+
+def _payloads_for_fused(oracle, k, n, block, seed):
+    rng = np.random.default_rng(seed)
+    ps, ss = [], []
+    for i in range(k):
+        x = rng.standard_normal(n) * 0.02
+        x[rng.integers(0, n, max(n // 200, 1))] *= 30.0
+        rp, rs = oracle.compress(W.float32_to_bf16_bits(x.astype(np.float32)), block=block)
+        ps.append(rp)
+        ss.append(rs)
+    return ps, ss
+
+
+@pytest.mark.parametrize("block,k,n", [(128, 1, 2048 * 6), (128, 8, 2048 * 9), (128, 3, 2048 * 3 + 128 * 5 + 17), (128, 2, 700),
+                                       (256, 8, 2048 * 8), (256, 2, 2048 * 2 + 300), (512, 4, 2048 * 5), (64, 8, 2048 * 4 + 70),
+                                       (32, 2, 2048 * 7), (128, 16, 2048 * 4)])
+@pytest.mark.parametrize("impl", ["auto", "butterfly"])
+def test_fused_sum_compress(oracle, block, k, n, impl):
+    ps, ss = _payloads_for_fused(oracle, k, n, block, seed=block + k + n)
+    dps = [torch.from_numpy(a).to(DEV) for a in ps]
+    dss = [torch.from_numpy(a).to(DEV) for a in ss]
+    p = taco.taco_default_params(block=block, impl=IMPLS[impl])
+    fp, fs = taco.taco_decompress_sum_compress(dps, dss, (n,), p)
+    # (1) the fused call changes no bit with respect to the two separate calls
+    buf = torch.zeros(n + ((-n) % 8), dtype=torch.bfloat16, device=DEV)
+    mid = taco.taco_decompress_sum(dps, dss, (n,), p, out=buf[:n])
+    up, us = taco.taco_compress(mid, p)
+    torch.cuda.synchronize()
+    assert torch.equal(fp, up) and torch.equal(fs, us)
+    # (2) against the oracle's composition.  The GPU sums in fp32, the oracle in double, so a few
+    # bf16 values of the intermediate differ by one ulp; blocks whose intermediate is identical are
+    # held to the usual bar, the others to what one flipped input can do to a block.
+    ref_mid = oracle.decompress_sum(ps, ss, n, block=block)
+    rp, rs = oracle.compress(ref_mid, block=block)
+    pad = (-n) % block
+    gm = np.concatenate([bits_of(mid), np.zeros(pad, dtype=np.uint16)]).reshape(-1, block)
+    rm = np.concatenate([ref_mid, np.zeros(pad, dtype=np.uint16)]).reshape(-1, block)
+    same = np.all(gm == rm, axis=1)
+    assert same.mean() >= 0.5
+    gp = fp.cpu().numpy().reshape(-1, block)
+    gs = fs.cpu().numpy().reshape(-1, 2)
+    P.check_scales(gs[same], rs[same], f"fused B={block} k={k}")
+    P.check_codes(gp[same], rp.reshape(-1, block)[same], rs[same], block, f"fused B={block} k={k}")
+    if (~same).any():
+        # One input off by one bf16 ulp (|dx| <= 2^-8 |x_j|) moves every rotated value of its block by
+        # |dx|, i.e. by at most 448 * 2^-8 = 1.75 in code VALUE (max|W| >= |W|_rms = |x|_2 >= |x_j|),
+        # and the block energy by at most 2 * 2^-8 of itself.
+        rel = np.abs(gs[~same] - rs[~same]) / np.maximum(np.abs(rs[~same]), 1e-30)
+        assert rel.max() <= 2e-2
+        flips = (gm != rm).sum(axis=1)[~same][:, None]
+        table = np.array([oracle.e4m3_decode(c) for c in range(256)])
+        gv, rv = table[gp[~same]], table[rp.reshape(-1, block)[~same]]
+        tol = 1.75 * flips + np.maximum(2.0 ** -9, np.abs(rv) * 2.0 ** -3)
+        assert np.all(np.abs(gv - rv) <= tol)
+        assert (gp[~same] == rp.reshape(-1, block)[~same]).mean() >= 0.9
