@@ -109,14 +109,20 @@ int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_par
     if (use_mfma(p)) {
         const int64_t n_tiles = n / taco::kTileElems;
         if (n_tiles > 0) {
-            constexpr int kTilesPerWave = 2;   // measured best on MI355X (1..4 tried)
-            const unsigned waves = static_cast<unsigned>((n_tiles + kTilesPerWave - 1) / kTilesPerWave);
+            // Tiles per wave, measured on MI355X: 2 wins on the largest tensors (98 k tiles), 1 below
+            // (finer tail, more waves to fill 256 compute units); 4 loses everywhere.
+            const bool two = n_tiles >= 65536;
+            const unsigned waves = static_cast<unsigned>(two ? (n_tiles + 1) / 2 : n_tiles);
             const auto* xin = static_cast<const taco::u32x4*>(x_bf16);
             auto* pout = static_cast<taco::u32x2*>(payload);
             auto* sout = static_cast<taco::f32x2*>(scales);
 #define TACO_LAUNCH_COMPRESS(RB, SUB)                                                                           \
-            hipLaunchKernelGGL((taco::compress_mfma_kernel<RB, SUB, kTilesPerWave, true>), dim3(waves), dim3(64), 0, st, \
-                               xin, n_tiles, p->tau, p->eps, pout, sout)
+            if (two)                                                                                            \
+                hipLaunchKernelGGL((taco::compress_mfma_kernel<RB, SUB, 2, true>), dim3(waves), dim3(64), 0, st, \
+                                   xin, n_tiles, p->tau, p->eps, pout, sout);                                   \
+            else                                                                                                \
+                hipLaunchKernelGGL((taco::compress_mfma_kernel<RB, SUB, 1, true>), dim3(waves), dim3(64), 0, st, \
+                                   xin, n_tiles, p->tau, p->eps, pout, sout)
             switch (B) {
                 case 32: TACO_LAUNCH_COMPRESS(1, 4); break;
                 case 64: TACO_LAUNCH_COMPRESS(1, 2); break;
