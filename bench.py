@@ -42,6 +42,7 @@ def parse():
     ap.add_argument("--workload", default="large_k8")
     ap.add_argument("--block", type=int, default=128)
     ap.add_argument("--impl", default="auto", choices=["auto", "butterfly", "mfma"])
+    ap.add_argument("--layout", default="split", choices=["split", "interleaved"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gen-threads", type=int, default=16)
     return ap.parse_args()
@@ -85,7 +86,8 @@ def main():
     w = W.WORKLOADS[args.workload]
     k, n, B = w.payloads, w.numel, args.block
     impl = {"auto": taco.TACO_IMPL_AUTO, "butterfly": taco.TACO_IMPL_BUTTERFLY, "mfma": taco.TACO_IMPL_MFMA}[args.impl]
-    params = taco.taco_default_params(block=B, impl=impl)
+    layout = taco.TACO_LAYOUT_INTERLEAVED if args.layout == "interleaved" else taco.TACO_LAYOUT_SPLIT
+    params = taco.taco_default_params(block=B, impl=impl, layout=layout)
 
     # ---- synthetic inputs, resident in HBM
     host = np.empty((w.tokens, w.hidden), dtype=np.uint16)
@@ -94,8 +96,13 @@ def main():
         W.generate(w, i, threads=args.gen_threads, out=host)
         xs.append(torch.from_numpy(host.view(np.int16)).to(dev).view(torch.bfloat16))
     del host
-    payloads = [torch.empty(taco.taco_payload_bytes(n, B), dtype=torch.uint8, device=dev) for _ in range(k)]
-    scales = [torch.empty((taco.taco_scales_bytes(n, B) // 8, 2), dtype=torch.float32, device=dev) for _ in range(k)]
+    if args.layout == "interleaved":
+        payloads = [torch.empty(taco.taco_payload_bytes(n, B) + taco.taco_scales_bytes(n, B), dtype=torch.uint8, device=dev)
+                    for _ in range(k)]
+        scales = [None] * k
+    else:
+        payloads = [torch.empty(taco.taco_payload_bytes(n, B), dtype=torch.uint8, device=dev) for _ in range(k)]
+        scales = [torch.empty((taco.taco_scales_bytes(n, B) // 8, 2), dtype=torch.float32, device=dev) for _ in range(k)]
     out1 = torch.empty((w.tokens, w.hidden), dtype=torch.bfloat16, device=dev)
     outk = torch.empty((w.tokens, w.hidden), dtype=torch.bfloat16, device=dev)
     stream = torch.cuda.current_stream()
@@ -142,7 +149,7 @@ def main():
     # side feeding the all-gather send side) on the same payloads
     fev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     fp = torch.empty_like(payloads[0])
-    fs = torch.empty_like(scales[0])
+    fs = torch.empty_like(scales[0]) if scales[0] is not None else None
     for _ in range(3):
         taco.taco_decompress_sum_compress(payloads, scales, outk.shape, params, fp, fs, stream)
     fev[0].record(stream)
@@ -186,7 +193,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: bf16 [{w.tokens}, {w.hidden}] x {k} payloads, block {B}, "
                                f"step = {k} compress + 1 decompress + 1 decompress_sum(k={k})",
-                   "impl": args.impl, "block": B},
+                   "impl": args.impl, "block": B, "layout": args.layout},
         "value_out_basis": round(real_bf16 / (ms_step * 1e6), 1),
         "moved_GBps": round(moved / (ms_step * 1e6), 1),
         "hbm_frac_step": round(moved / (ms_step * 1e6) / HBM_PEAK_GBPS, 4),
@@ -198,7 +205,7 @@ def main():
         "roofline": {"kernel": f"compress_mfma_kernel<{B // 128},2,true>" if (B >= 128 and args.impl != "butterfly") else f"compress_butterfly_kernel<{B}>",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, B, args.impl)),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, B, args.impl)) if args.layout == "split" else None,
                      "alg_bytes_per_launch": bytes_comp, "avg_launch_ms": round(t_comp, 4)},
     }
     if not args.no_cpu_baseline:

@@ -59,7 +59,8 @@ typedef enum taco_status {
     TACO_ERR_FORMAT = -6, /* params->format is not TACO_FORMAT_E4M3                   */
     TACO_ERR_LAUNCH = -7, /* the HIP runtime refused the launch (hipGetLastError)     */
     TACO_ERR_IMPL = -8,   /* params->impl is not one of TACO_IMPL_*                   */
-    TACO_ERR_PARAM = -9   /* tau <= 0, eps < 0, or a non-finite parameter             */
+    TACO_ERR_PARAM = -9,  /* tau <= 0, eps < 0, or a non-finite parameter             */
+    TACO_ERR_LAYOUT = -10 /* params->layout is not one of TACO_LAYOUT_*               */
 } taco_status;
 
 enum { TACO_FORMAT_E4M3 = 0 };
@@ -69,6 +70,15 @@ enum { TACO_FORMAT_E4M3 = 0 };
  * on the butterfly kernel (kept for tests and benchmarks that compare the two). */
 enum { TACO_IMPL_AUTO = 0, TACO_IMPL_BUTTERFLY = 1, TACO_IMPL_MFMA = 2 };
 
+/* Where the two scalars of a block travel (Section 4.4.2 of the paper places them directly
+ * behind the block's codes).
+ *   SPLIT        `payload` = the codes of all blocks in element order, `scales` = the records
+ *                {alpha, s} of all blocks.  The two regions may be adjacent parts of one buffer.
+ *   INTERLEAVED  `payload` = one record of B + 8 bytes per block: B codes, float alpha, float s.
+ *                Its size is taco_payload_bytes + taco_scales_bytes; every `scales` argument is
+ *                ignored and may be NULL.  Records are 8-byte but not 16-byte aligned. */
+enum { TACO_LAYOUT_SPLIT = 0, TACO_LAYOUT_INTERLEAVED = 1 };
+
 /* Hyper-parameters of Algorithm 1 ("Require" line): block size B, target energy tau,
  * stabiliser eps; Q_max follows from the format. */
 typedef struct taco_params {
@@ -77,9 +87,10 @@ typedef struct taco_params {
     float eps;      /* eps of Eq. ash_sigma, >= 0 (the paper gives no value; 1e-12f) */
     int32_t format; /* TACO_FORMAT_E4M3                                            */
     int32_t impl;   /* TACO_IMPL_*                                                 */
+    int32_t layout; /* TACO_LAYOUT_*                                               */
 } taco_params;
 
-/* Fills *p with B = 128, tau = 1, eps = 1e-12, E4M3, AUTO. */
+/* Fills *p with B = 128, tau = 1, eps = 1e-12, E4M3, AUTO, SPLIT. */
 void taco_default_params(taco_params* p);
 
 /* Sizes of the two output regions of taco_compress for n elements: ceil(n/B)*B bytes of

@@ -50,12 +50,19 @@ __device__ __forceinline__ void fwht_wave(float (&v)[ButterflyShape<B>::kRegs], 
     }
 }
 
+// Byte offset of block blk's codes in the payload buffer: blocks are B bytes apart in the split
+// layout and B + 8 bytes apart (codes, then {alpha, s}) in the interleaved one.
+template <int B>
+__device__ __forceinline__ int64_t code_offset(int64_t blk, bool interleaved) {
+    return blk * (interleaved ? B + 8 : B);
+}
+
 // Sender side of Algorithm 1 for one block whose elements are already in registers
 // (v[r] = element lane + 64 r, zeros past the end of the tensor).
 template <int B>
 __device__ __forceinline__ void compress_block_butterfly(float (&v)[ButterflyShape<B>::kRegs], int lane, int64_t blk,
                                                          float tau, float eps, uint8_t* __restrict__ payload,
-                                                         float2* __restrict__ scales) {
+                                                         float2* __restrict__ scales, bool interleaved) {
     constexpr int R = ButterflyShape<B>::kRegs;
     const float inv_root_b = 1.0f / __builtin_sqrtf(static_cast<float>(B));
     float energy = 0.0f;
@@ -78,17 +85,20 @@ __device__ __forceinline__ void compress_block_butterfly(float (&v)[ButterflySha
         const int e = lane + 64 * r;
         if (e < B) {
             const float q = v[r] * to_code;
-            payload[blk * B + e] = static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_fp8_f32(q, q, 0, false) & 0xFF);
+            payload[code_offset<B>(blk, interleaved) + e] = static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_fp8_f32(q, q, 0, false) & 0xFF);
         }
     }
-    if (lane == 0) scales[blk] = make_float2(alpha, s);
+    if (lane == 0) {
+        if (interleaved) *reinterpret_cast<float2*>(payload + code_offset<B>(blk, true) + B) = make_float2(alpha, s);
+        else scales[blk] = make_float2(alpha, s);
+    }
 }
 
 // Sender side of Algorithm 1 for blocks [first_block, first_block + n_blocks).
 template <int B>
 __global__ __launch_bounds__(64) void compress_butterfly_kernel(
     const uint16_t* __restrict__ x, int64_t n, int64_t first_block, int64_t n_blocks, float tau,
-    float eps, uint8_t* __restrict__ payload, float2* __restrict__ scales) {
+    float eps, uint8_t* __restrict__ payload, float2* __restrict__ scales, bool interleaved) {
     constexpr int R = ButterflyShape<B>::kRegs;
     const int lane = threadIdx.x;
     for (int64_t blk = first_block + blockIdx.x; blk < first_block + n_blocks; blk += gridDim.x) {
@@ -99,7 +109,7 @@ __global__ __launch_bounds__(64) void compress_butterfly_kernel(
             const int64_t idx = blk * B + e;
             v[r] = (e < B && idx < n) ? bf16_bits_to_f32(x[idx]) : 0.0f;   // zero padding
         }
-        compress_block_butterfly<B>(v, lane, blk, tau, eps, payload, scales);
+        compress_block_butterfly<B>(v, lane, blk, tau, eps, payload, scales, interleaved);
     }
 }
 
@@ -115,15 +125,16 @@ struct PayloadTable {
 // afterwards.
 template <int B>
 __device__ __forceinline__ void decode_sum_block_butterfly(const PayloadTable& tab, int k, int64_t blk, int lane,
-                                                           float (&v)[ButterflyShape<B>::kRegs]) {
+                                                           float (&v)[ButterflyShape<B>::kRegs], bool interleaved) {
     constexpr int R = ButterflyShape<B>::kRegs;
     const float inv_root_b = 1.0f / __builtin_sqrtf(static_cast<float>(B));
 #pragma unroll
     for (int r = 0; r < R; ++r) v[r] = 0.0f;
     float single = 1.0f;
     for (int i = 0; i < k; ++i) {
-        const uint8_t* codes = static_cast<const uint8_t*>(tab.payload[i]);
-        const float2 sc = static_cast<const float2*>(tab.scales[i])[blk];
+        const uint8_t* codes = static_cast<const uint8_t*>(tab.payload[i]) + code_offset<B>(blk, interleaved);
+        const float2 sc = interleaved ? *reinterpret_cast<const float2*>(codes + B)
+                                      : static_cast<const float2*>(tab.scales[i])[blk];
         const float factor = sc.y * __builtin_amdgcn_rcpf(sc.x) * inv_root_b;   // s / (alpha sqrt(B))
         const float w = (k == 1) ? 1.0f : factor;
         single = factor;
@@ -131,7 +142,7 @@ __device__ __forceinline__ void decode_sum_block_butterfly(const PayloadTable& t
         for (int r = 0; r < R; ++r) {
             const int e = lane + 64 * r;
             if (e < B) {
-                const float q = __builtin_amdgcn_cvt_f32_fp8(codes[blk * B + e], 0);
+                const float q = __builtin_amdgcn_cvt_f32_fp8(codes[e], 0);
                 v[r] = __builtin_fmaf(q, w, v[r]);
             }
         }
@@ -145,12 +156,12 @@ __device__ __forceinline__ void decode_sum_block_butterfly(const PayloadTable& t
 template <int B>
 __global__ __launch_bounds__(64) void decompress_sum_butterfly_kernel(
     PayloadTable tab, int k, int64_t n, int64_t first_block, int64_t n_blocks,
-    uint16_t* __restrict__ out) {
+    uint16_t* __restrict__ out, bool interleaved) {
     constexpr int R = ButterflyShape<B>::kRegs;
     const int lane = threadIdx.x;
     for (int64_t blk = first_block + blockIdx.x; blk < first_block + n_blocks; blk += gridDim.x) {
         float v[R];
-        decode_sum_block_butterfly<B>(tab, k, blk, lane, v);
+        decode_sum_block_butterfly<B>(tab, k, blk, lane, v, interleaved);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int e = lane + 64 * r;
@@ -165,19 +176,19 @@ __global__ __launch_bounds__(64) void decompress_sum_butterfly_kernel(
 template <int B>
 __global__ __launch_bounds__(64) void decompress_sum_compress_butterfly_kernel(
     PayloadTable tab, int k, int64_t n, int64_t first_block, int64_t n_blocks, float tau, float eps,
-    uint8_t* __restrict__ payload_out, float2* __restrict__ scales_out) {
+    uint8_t* __restrict__ payload_out, float2* __restrict__ scales_out, bool interleaved) {
     constexpr int R = ButterflyShape<B>::kRegs;
     const int lane = threadIdx.x;
     for (int64_t blk = first_block + blockIdx.x; blk < first_block + n_blocks; blk += gridDim.x) {
         float v[R];
-        decode_sum_block_butterfly<B>(tab, k, blk, lane, v);
+        decode_sum_block_butterfly<B>(tab, k, blk, lane, v, interleaved);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int e = lane + 64 * r;
             const int64_t idx = blk * B + e;
             v[r] = (e < B && idx < n) ? bf16_bits_to_f32(pack_bf16x2(v[r], 0.0f) & 0xFFFF) : 0.0f;
         }
-        compress_block_butterfly<B>(v, lane, blk, tau, eps, payload_out, scales_out);
+        compress_block_butterfly<B>(v, lane, blk, tau, eps, payload_out, scales_out, interleaved);
     }
 }
 

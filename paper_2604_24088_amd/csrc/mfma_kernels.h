@@ -52,6 +52,31 @@ __device__ __forceinline__ int unit_of_row(int i) {
     return kRB == 1 ? 4 * (i & 3) + (i >> 2) : i;
 }
 
+// Where codes and {alpha, s} records live.  Split layout: `payload` holds the codes in element
+// order and `scales` the records.  Interleaved layout (the paper's placement, Section 4.4.2:
+// the two scalars directly behind their block's codes): `payload` holds records of B + 8 bytes,
+// B codes then {float alpha; float s;}, and `scales` is unused.  B + 8 is a multiple of 8 but not
+// of 16, so the interleaved form is addressed in 8-byte words; a tile of 2048 elements still
+// starts on a 16-byte boundary for every block size.
+template <int kBlock, bool kInterleaved>
+struct PayloadLayout {
+    static constexpr int kBlocksPerTile = 2048 / kBlock;
+    static constexpr int kRecordWords = kBlock / 8 + (kInterleaved ? 1 : 0);   // 8-byte words per block
+    static constexpr int kTileWords = kBlocksPerTile * kRecordWords;           // 8-byte words per tile
+    static constexpr int kTileChunks = kTileWords / 2;                         // 16-byte chunks per tile
+    static constexpr int kRecordBytes = 8 * kRecordWords;
+    static_assert(kTileWords % 2 == 0, "a tile must be a whole number of 16-byte chunks");
+
+    // 8-byte word index, in the payload buffer, of codes 8 w .. 8 w + 7 of tile-local block blk.
+    static __device__ __forceinline__ int64_t code_word(int64_t tile, int blk, int w) {
+        return tile * kTileWords + blk * kRecordWords + w;
+    }
+    // Interleaved only: word index of the {alpha, s} record of tile-local block blk.
+    static __device__ __forceinline__ int64_t scale_word(int64_t tile, int blk) {
+        return tile * kTileWords + blk * kRecordWords + kBlock / 8;
+    }
+};
+
 // In-register butterfly across the kRB units of a block: v[r] -> sum_h (-1)^popcount(h & r) v[h]
 // within each aligned group of kRB registers (natural order, H_kRB).
 template <int kRB>
@@ -203,9 +228,16 @@ struct CompressLane {
 
     // Sender side of Algorithm 1 for the tile that sits in LDS.  Ends with the wave past its last
     // LDS read (a barrier follows the reads), so the caller may overwrite the buffer afterwards.
-    template <bool kStream>
-    __device__ __forceinline__ void tile_from_lds(const uint32_t* lds, int64_t tile, float tau, float eps,
+    // In the interleaved layout the records (B + 8 bytes) do not line up with cache lines, and
+    // storing codes and scalars straight from the lanes leaves every line written in pieces
+    // (measured: 142 us instead of 99 us per compress of the bench tensor).  The tile's records are
+    // therefore assembled in LDS (the input buffer is free once the A operands are read) and
+    // leave as contiguous 16-byte chunks.
+    template <bool kInterleaved>
+    __device__ __forceinline__ void tile_from_lds(uint32_t* lds, int64_t tile, float tau, float eps,
                                                   u32x2* __restrict__ payload, f32x2* __restrict__ scales) const {
+        using Layout = PayloadLayout<kBlock, kInterleaved>;
+        u32x2* records = reinterpret_cast<u32x2*>(lds);     // interleaved: the tile's records, 8-byte words
         u32x4 a[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) a[c] = *reinterpret_cast<const u32x4*>(&lds[rd_base + 4 * c]);
@@ -271,33 +303,53 @@ struct CompressLane {
         if (owns_scales) {
             const float alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / kBlock) + eps);   // Eq. ash_sigma, ash_alpha
             const float s = (wmax * alpha) * (inv_sqrt_block<kBlock>() / kQmax);               // max|Z| / Q_max
-            store_stream<kStream>(&scales[tile * kBlocksPerTile + my_block], f32x2{alpha, s});
+            if (kInterleaved)
+                records[Layout::scale_word(0, my_block)] = __builtin_bit_cast(u32x2, f32x2{alpha, s});
+            else
+                store_stream<true>(&scales[tile * kBlocksPerTile + my_block], f32x2{alpha, s});
         }
 
         // 8 consecutive codes per lane and row.  The factor of row R's block comes from the quad
         // lane that holds it (kRB = 1: lane R; kRB = 2: lane R / 2; kRB = 4: any).
+        // Codes 8 n16 .. 8 n16 + 7 of unit u belong to block u / kRB (word 16 (u % kRB) + n16 of it) when
+        // a block is one or more units, and to block u kSub + n16 / (16 / kSub) when it is part of a unit.
 #define TACO_STORE_ROW(R)                                                                      \
         {                                                                                      \
             const float f = dpp_f32<kDppQuadBcast(kRB == 1 ? R : kRB == 2 ? R / 2 : 0)>(to_code); \
             u32x2 w;                                                                           \
             w.x = pack_e4m3x4(acc[0][R] * f, acc[1][R] * f, acc[2][R] * f, acc[3][R] * f);     \
             w.y = pack_e4m3x4(acc[4][R] * f, acc[5][R] * f, acc[6][R] * f, acc[7][R] * f);     \
-            store_stream<kStream>(&payload[tile * 256 + unit_of_row<kRB>(4 * g + R) * 16 + n16], w); \
+            const int unit = unit_of_row<kRB>(4 * g + R);                                      \
+            const int blk = kSub == 1 ? unit / kRB : unit * kSub + n16 / (16 / kSub);          \
+            const int word = kSub == 1 ? 16 * (unit % kRB) + n16 : n16 % (16 / kSub);          \
+            if (kInterleaved) records[Layout::code_word(0, blk, word)] = w;                    \
+            else store_stream<true>(&payload[Layout::code_word(tile, blk, word)], w);         \
         }
         TACO_STORE_ROW(0)
         TACO_STORE_ROW(1)
         TACO_STORE_ROW(2)
         TACO_STORE_ROW(3)
 #undef TACO_STORE_ROW
+        if (kInterleaved) {
+            __syncthreads();
+            const u32x4* chunks = reinterpret_cast<const u32x4*>(lds);
+            u32x4* dst = reinterpret_cast<u32x4*>(payload) + tile * Layout::kTileChunks;
+            const int lane = 16 * g + n16;
+#pragma unroll
+            for (int c = 0; c < (Layout::kTileChunks + 63) / 64; ++c) {
+                const int chunk = 64 * c + lane;
+                if (chunk < Layout::kTileChunks) store_stream<true>(&dst[chunk], chunks[chunk]);
+            }
+            __syncthreads();
+        }
     }
 };
 
-// x: n_tiles * 2048 bf16 (as 16-byte words); payload: n_tiles * 2048 codes (as 8-byte
-// words); scales: n_tiles * (2048 / B) records {alpha, s}.  Block size B = 128 kRB / kSub
-// (at most one of kRB, kSub differs from 1).
+// x: n_tiles * 2048 bf16 (as 16-byte words); payload, scales: see PayloadLayout (payload as 8-byte
+// words).  Block size B = 128 kRB / kSub (at most one of kRB, kSub differs from 1).
 // Workgroup w (one wave) handles the kTiles consecutive tiles starting at w * kTiles; all its
 // loads are issued before the first tile is processed.
-template <int kRB, int kSub, int kTiles, bool kStream>
+template <int kRB, int kSub, int kTiles, bool kInterleaved>
 __global__ __launch_bounds__(64) void compress_mfma_kernel(
     const u32x4* __restrict__ x, int64_t n_tiles, float tau, float eps,
     u32x2* __restrict__ payload, f32x2* __restrict__ scales) {
@@ -311,7 +363,7 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
         int64_t t = first_tile + p;
         if (t >= n_tiles) t = n_tiles - 1;      // ragged last wave: re-read a valid tile, result unused
 #pragma unroll
-        for (int c = 0; c < 4; ++c) stage[p][c] = load16<kStream>(&x[t * 256 + 64 * c + lane]);
+        for (int c = 0; c < 4; ++c) stage[p][c] = load16<true>(&x[t * 256 + 64 * c + lane]);
     }
 
     const CompressLane<kRB, kSub> cl(lane);
@@ -329,7 +381,7 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
             for (int c = 0; c < 4; ++c) lds[wr_base + cp * 528 + 4 * c] = stage[p][cp][c];
         }
         __syncthreads();
-        cl.template tile_from_lds<kStream>(lds, tile, tau, eps, payload, scales);
+        cl.template tile_from_lds<kInterleaved>(lds, tile, tau, eps, payload, scales);
     }
 }
 
@@ -338,7 +390,7 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
 // ------------------------------------------------------------------------------------------
 
 // out = bf16( sum_i  H_B (codes_i) * s_i / (alpha_i sqrt(B)) ), fp32 accumulation, i ascending.
-// payloads: n_tiles * 2048 codes each; scales: n_tiles * (16 / kRB) records; out: n_tiles * 2048 bf16.
+// payloads, scales: see PayloadLayout; out: n_tiles * 2048 bf16.
 // Workgroup w (one wave) handles output tiles [w * tiles_per_wave, (w+1) * tiles_per_wave) and
 // exits.  Its work is the flattened list of (tile, payload) items, payload fastest; a ring of
 // kRing items is kept in flight in registers.  For blocks of several units the per-payload work
@@ -349,7 +401,7 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
 // bf16-rounded sum (the receive side of the reduce-scatter feeding the send side of the
 // all-gather, Section 4.4.2): the finished tile goes to LDS in the compress stage's layout
 // instead of HBM, and `out` is unused.
-template <int kRB, int kSub, int kRing, bool kStream, bool kRecompress>
+template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress>
 __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
     PayloadTable tab, int k, int64_t n_tiles, int tiles_per_wave, u32x4* __restrict__ out,
     float tau, float eps, u32x2* __restrict__ payload_out, f32x2* __restrict__ scales_out) {
@@ -357,7 +409,10 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
                   "block size must be 32, 64, 128, 256 or 512");
     constexpr int kBlock = 128 * kRB / kSub;
     constexpr int kBlocksPerTile = 2048 / kBlock;
-    __shared__ u32x4 lds[128];   // one tile of codes: 16 unit rows x 8 chunks of 16 bytes
+    using Layout = PayloadLayout<kBlock, kInterleaved>;
+    constexpr int kLoads = kInterleaved ? 3 : 2;                 // 16-byte loads per lane and item
+    constexpr int kExtraChunks = Layout::kTileChunks - 128;      // interleaved: chunks left for the third load
+    __shared__ u32x4 lds[Layout::kTileChunks];   // one tile of the payload: split layout swizzled, interleaved as it is
     __shared__ uint32_t lds_c[kRecompress ? kCompressLdsDwords : 1];   // the bf16 tile for the compress stage
     const int lane = threadIdx.x;
     const int g = lane >> 4;
@@ -374,19 +429,24 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
     const int n_items = static_cast<int>(tile_end - tile_begin) * k;
 
     // Ring fill.  (pf_tile, pf_i) walks the item list ahead of the consumer.
-    u32x4 stage[kRing][2];
+    u32x4 stage[kRing][kLoads];
     f32x2 stage_sc[kRing];
     int64_t pf_tile = tile_begin;
     int pf_i = 0;
+    auto fetch = [&](int p) {
+        const u32x4* src = static_cast<const u32x4*>(tab.payload[pf_i]) + pf_tile * Layout::kTileChunks;
+        stage[p][0] = load16<true>(&src[lane]);
+        stage[p][1] = load16<true>(&src[64 + lane]);
+        if (kInterleaved) {
+            if (lane < kExtraChunks) stage[p][kLoads - 1] = load16<true>(&src[128 + lane]);
+        } else {
+            stage_sc[p] = static_cast<const f32x2*>(tab.scales[pf_i])[pf_tile * kBlocksPerTile + my_block];
+        }
+        if (++pf_i == k) { pf_i = 0; ++pf_tile; }
+    };
 #pragma unroll
     for (int p = 0; p < kRing; ++p) {
-        if (p < n_items) {
-            const u32x4* src = static_cast<const u32x4*>(tab.payload[pf_i]);
-            stage[p][0] = load16<kStream>(&src[pf_tile * 128 + lane]);
-            stage[p][1] = load16<kStream>(&src[pf_tile * 128 + 64 + lane]);
-            stage_sc[p] = static_cast<const f32x2*>(tab.scales[pf_i])[pf_tile * kBlocksPerTile + my_block];
-            if (++pf_i == k) { pf_i = 0; ++pf_tile; }
-        }
+        if (p < n_items) fetch(p);
     }
 
     // B operand: 8 column tiles of H_128 in E4M3 (+1 = 0x38, -1 = 0xB8), 32 bytes per lane each.
@@ -416,17 +476,31 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
         }
     }
 
-    // LDS slots (16-byte units, 8 per unit row).  Writer: load m covers tile units 8m .. 8m+7,
-    // this lane holds chunk lane%8 of unit 8m + lane/8.  Reader: row i = n16 is unit u(i),
-    // half m wants chunk 4m + g.  The XOR swizzle keeps both sides bank-conflict free.
-    int wr_slot[2], rd_slot[2];
+    // LDS addressing.
+    // Split layout (16-byte slots, 8 per unit row): writer load m covers tile units 8m .. 8m+7, this
+    // lane holds chunk lane%8 of unit 8m + lane/8; reader row i = n16 is unit u(i), half m wants chunk
+    // 4m + g.  The XOR swizzle keeps both sides bank-conflict free.
+    // Interleaved layout: the tile is copied as it is; the reader computes the byte offset of its
+    // 16 codes inside the records (8-byte aligned), and the block's {alpha, s} is read from LDS too.
+    int wr_slot[2], rd_slot[2];     // split: 16-byte slot indices; interleaved: rd_slot = byte offsets
+    int sc_byte = 0;
     const int rd_unit = unit_of_row<kRB>(n16);
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
-        const int wb = 8 * m + (lane >> 3);
-        wr_slot[m] = wb * 8 + ((lane & 7) ^ ((wb >> 1) & 7));
-        rd_slot[m] = rd_unit * 8 + ((4 * m + g) ^ ((rd_unit >> 1) & 7));
+        if (kInterleaved) {
+            wr_slot[m] = 64 * m + lane;
+            const int c = 4 * m + g;                         // 16-byte chunk of the unit
+            constexpr int kChunksPerBlock = kBlock >= 128 ? 8 : kBlock / 16;
+            const int blk = kSub == 1 ? rd_unit / kRB : rd_unit * kSub + c / kChunksPerBlock;
+            const int in_block = kSub == 1 ? 128 * (rd_unit % kRB) + 16 * c : 16 * (c % kChunksPerBlock);
+            rd_slot[m] = blk * Layout::kRecordBytes + in_block;
+        } else {
+            const int wb = 8 * m + (lane >> 3);
+            wr_slot[m] = wb * 8 + ((lane & 7) ^ ((wb >> 1) & 7));
+            rd_slot[m] = rd_unit * 8 + ((4 * m + g) ^ ((rd_unit >> 1) & 7));
+        }
     }
+    if (kInterleaved) sc_byte = my_block * Layout::kRecordBytes + kBlock;
     const float inv_root_b = inv_sqrt_block<kBlock>();
     const CompressLane<kRB, kSub> cl(lane);    // used by the recompress form only
 
@@ -440,18 +514,24 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
             if (q >= n_items) break;
             lds[wr_slot[0]] = stage[p][0];
             lds[wr_slot[1]] = stage[p][1];
-            const f32x2 sc = stage_sc[p];
+            if (kInterleaved && lane < kExtraChunks) lds[128 + lane] = stage[p][kLoads - 1];
+            f32x2 sc = stage_sc[p];
             __syncthreads();
-            const u32x4 a0 = lds[rd_slot[0]];
-            const u32x4 a1 = lds[rd_slot[1]];
-            __syncthreads();
-            if (q + kRing < n_items) {      // refill this ring slot
-                const u32x4* src = static_cast<const u32x4*>(tab.payload[pf_i]);
-                stage[p][0] = load16<kStream>(&src[pf_tile * 128 + lane]);
-                stage[p][1] = load16<kStream>(&src[pf_tile * 128 + 64 + lane]);
-                stage_sc[p] = static_cast<const f32x2*>(tab.scales[pf_i])[pf_tile * kBlocksPerTile + my_block];
-                if (++pf_i == k) { pf_i = 0; ++pf_tile; }
+            u32x4 a0, a1;
+            if (kInterleaved) {
+                const unsigned char* bytes = reinterpret_cast<const unsigned char*>(lds);
+                const u32x2* p0 = reinterpret_cast<const u32x2*>(bytes + rd_slot[0]);
+                const u32x2* p1 = reinterpret_cast<const u32x2*>(bytes + rd_slot[1]);
+                const u32x2 lo0 = p0[0], hi0 = p0[1], lo1 = p1[0], hi1 = p1[1];
+                a0 = u32x4{lo0.x, lo0.y, hi0.x, hi0.y};
+                a1 = u32x4{lo1.x, lo1.y, hi1.x, hi1.y};
+                sc = *reinterpret_cast<const f32x2*>(bytes + sc_byte);
+            } else {
+                a0 = lds[rd_slot[0]];
+                a1 = lds[rd_slot[1]];
             }
+            __syncthreads();
+            if (q + kRing < n_items) fetch(p);      // refill this ring slot
             i32x8 av;
             av[0] = a0.x; av[1] = a0.y; av[2] = a0.z; av[3] = a0.w;
             av[4] = a1.x; av[5] = a1.y; av[6] = a1.z; av[7] = a1.w;
@@ -501,12 +581,12 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
                         lds_c[slot + 8] = w.z;
                         lds_c[slot + 12] = w.w;
                     } else {
-                        store_stream<kStream>(&out[tile * 256 + unit * 16 + n16], w);
+                        store_stream<true>(&out[tile * 256 + unit * 16 + n16], w);
                     }
                 }
                 if (kRecompress) {
                     __syncthreads();
-                    cl.template tile_from_lds<kStream>(lds_c, tile, tau, eps, payload_out, scales_out);
+                    cl.template tile_from_lds<kInterleaved>(lds_c, tile, tau, eps, payload_out, scales_out);
                 }
                 i = 0;
                 ++tile;

@@ -45,6 +45,7 @@ int check_common(int64_t rows, int64_t cols, const taco_params* p, int64_t* n_ou
     if (!block_ok(p->block)) return TACO_ERR_BLOCK;
     if (p->format != TACO_FORMAT_E4M3) return TACO_ERR_FORMAT;
     if (p->impl != TACO_IMPL_AUTO && p->impl != TACO_IMPL_BUTTERFLY && p->impl != TACO_IMPL_MFMA) return TACO_ERR_IMPL;
+    if (p->layout != TACO_LAYOUT_SPLIT && p->layout != TACO_LAYOUT_INTERLEAVED) return TACO_ERR_LAYOUT;
     *n_out = rows * cols;
     return TACO_OK;
 }
@@ -72,6 +73,89 @@ int dispatch_block(int32_t block, F&& f) {
 
 int launch_status() { return hipGetLastError() == hipSuccess ? TACO_OK : TACO_ERR_LAUNCH; }
 
+bool params_ok_for_compress(const taco_params* p) {
+    return p->tau > 0.0f && p->eps >= 0.0f && std::isfinite(p->tau) && std::isfinite(p->eps);
+}
+
+// Calls f(kRB, kSub, kInterleaved) with the three as compile-time constants.
+template <typename F>
+void dispatch_shape(int block, bool interleaved, F&& f) {
+    auto with_layout = [&](auto rb, auto sub) {
+        if (interleaved) f(rb, sub, std::true_type{});
+        else f(rb, sub, std::false_type{});
+    };
+    using std::integral_constant;
+    switch (block) {
+        case 32: with_layout(integral_constant<int, 1>{}, integral_constant<int, 4>{}); break;
+        case 64: with_layout(integral_constant<int, 1>{}, integral_constant<int, 2>{}); break;
+        case 128: with_layout(integral_constant<int, 1>{}, integral_constant<int, 1>{}); break;
+        case 256: with_layout(integral_constant<int, 2>{}, integral_constant<int, 1>{}); break;
+        default: with_layout(integral_constant<int, 4>{}, integral_constant<int, 1>{}); break;
+    }
+}
+
+// Fills the kernel-side table from the caller's host arrays.  In the interleaved layout the
+// scales live inside the payload and `scales` (the array or its entries) may be NULL.
+int fill_table(const void* const* payloads, const void* const* scales, int k, bool interleaved, taco::PayloadTable* tab) {
+    if (!payloads || (!interleaved && !scales)) return TACO_ERR_NULL;
+    for (int i = 0; i < k; ++i) {
+        if (!payloads[i] || (!interleaved && !scales[i])) return TACO_ERR_NULL;
+        if (!aligned16(payloads[i]) || (!interleaved && !aligned16(scales[i]))) return TACO_ERR_ALIGN;
+        tab->payload[i] = payloads[i];
+        tab->scales[i] = interleaved ? nullptr : scales[i];
+    }
+    return TACO_OK;
+}
+
+// Decode (and optionally re-compress) whole tiles on the matrix cores, the rest on the butterfly kernel.
+int launch_decode(const taco::PayloadTable& tab, int k, int64_t n, const taco_params* p, bool recompress,
+                  void* out_bf16, void* payload_out, void* scales_out, hipStream_t st) {
+    const int B = p->block;
+    const bool il = p->layout == TACO_LAYOUT_INTERLEAVED;
+    const int64_t n_blocks = (n + B - 1) / B;
+    int64_t first_block = 0;
+    if (use_mfma(p)) {
+        const int64_t n_tiles = n / taco::kTileElems;
+        if (n_tiles > 0) {
+            // Two output tiles per wave and a ring of four (tile, payload) items in flight: measured
+            // best on MI355X for k = 1 and k = 8 (1..16 tiles, rings of 2..8 tried).
+            const int tiles_per_wave = 2;
+            const unsigned waves = static_cast<unsigned>((n_tiles + tiles_per_wave - 1) / tiles_per_wave);
+            dispatch_shape(B, il, [&](auto rb, auto sub, auto layout) {
+                constexpr int kRB = decltype(rb)::value, kSub = decltype(sub)::value;
+                constexpr bool kIl = decltype(layout)::value;
+                if (recompress)
+                    hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, true>), dim3(waves), dim3(64), 0, st,
+                                       tab, k, n_tiles, tiles_per_wave, static_cast<taco::u32x4*>(nullptr), p->tau, p->eps,
+                                       static_cast<taco::u32x2*>(payload_out), static_cast<taco::f32x2*>(scales_out));
+                else
+                    hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false>), dim3(waves), dim3(64), 0, st,
+                                       tab, k, n_tiles, tiles_per_wave, static_cast<taco::u32x4*>(out_bf16), 0.0f, 0.0f,
+                                       static_cast<taco::u32x2*>(nullptr), static_cast<taco::f32x2*>(nullptr));
+            });
+            if (int rc = launch_status()) return rc;
+        }
+        first_block = n_tiles * (taco::kTileElems / B);
+    }
+    const int64_t rest = n_blocks - first_block;
+    if (rest > 0) {
+        const float tau = p->tau, eps = p->eps;
+        int rc = dispatch_block(B, [&](auto bc) {
+            constexpr int kB = decltype(bc)::value;
+            if (recompress)
+                hipLaunchKernelGGL(taco::decompress_sum_compress_butterfly_kernel<kB>, dim3(grid_for(rest, 32)), dim3(64), 0, st,
+                                   tab, k, n, first_block, rest, tau, eps, static_cast<uint8_t*>(payload_out),
+                                   static_cast<float2*>(scales_out), il);
+            else
+                hipLaunchKernelGGL(taco::decompress_sum_butterfly_kernel<kB>, dim3(grid_for(rest, 32)), dim3(64), 0, st,
+                                   tab, k, n, first_block, rest, static_cast<uint16_t*>(out_bf16), il);
+        });
+        if (rc) return rc;
+        if (int rc2 = launch_status()) return rc2;
+    }
+    return TACO_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -83,6 +167,7 @@ void taco_default_params(taco_params* p) {
     p->eps = 1e-12f;
     p->format = TACO_FORMAT_E4M3;
     p->impl = TACO_IMPL_AUTO;
+    p->layout = TACO_LAYOUT_SPLIT;
 }
 
 size_t taco_payload_bytes(int64_t n, int32_t block) {
@@ -97,11 +182,13 @@ size_t taco_scales_bytes(int64_t n, int32_t block) {
 
 int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_params* p,
                   void* payload, void* scales, void* stream) {
-    if (!x_bf16 || !payload || !scales) return TACO_ERR_NULL;
+    if (!x_bf16 || !payload) return TACO_ERR_NULL;
     int64_t n = 0;
     if (int rc = check_common(rows, cols, p, &n)) return rc;
-    if (!(p->tau > 0.0f) || !(p->eps >= 0.0f) || !std::isfinite(p->tau) || !std::isfinite(p->eps)) return TACO_ERR_PARAM;
-    if (!aligned16(x_bf16) || !aligned16(payload) || !aligned16(scales)) return TACO_ERR_ALIGN;
+    const bool il = p->layout == TACO_LAYOUT_INTERLEAVED;
+    if (!il && !scales) return TACO_ERR_NULL;
+    if (!params_ok_for_compress(p)) return TACO_ERR_PARAM;
+    if (!aligned16(x_bf16) || !aligned16(payload) || (!il && !aligned16(scales))) return TACO_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int B = p->block;
     const int64_t n_blocks = (n + B - 1) / B;
@@ -116,21 +203,16 @@ int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_par
             const auto* xin = static_cast<const taco::u32x4*>(x_bf16);
             auto* pout = static_cast<taco::u32x2*>(payload);
             auto* sout = static_cast<taco::f32x2*>(scales);
-#define TACO_LAUNCH_COMPRESS(RB, SUB)                                                                           \
-            if (two)                                                                                            \
-                hipLaunchKernelGGL((taco::compress_mfma_kernel<RB, SUB, 2, true>), dim3(waves), dim3(64), 0, st, \
-                                   xin, n_tiles, p->tau, p->eps, pout, sout);                                   \
-            else                                                                                                \
-                hipLaunchKernelGGL((taco::compress_mfma_kernel<RB, SUB, 1, true>), dim3(waves), dim3(64), 0, st, \
-                                   xin, n_tiles, p->tau, p->eps, pout, sout)
-            switch (B) {
-                case 32: TACO_LAUNCH_COMPRESS(1, 4); break;
-                case 64: TACO_LAUNCH_COMPRESS(1, 2); break;
-                case 128: TACO_LAUNCH_COMPRESS(1, 1); break;
-                case 256: TACO_LAUNCH_COMPRESS(2, 1); break;
-                default: TACO_LAUNCH_COMPRESS(4, 1); break;
-            }
-#undef TACO_LAUNCH_COMPRESS
+            dispatch_shape(B, il, [&](auto rb, auto sub, auto layout) {
+                constexpr int kRB = decltype(rb)::value, kSub = decltype(sub)::value;
+                constexpr bool kIl = decltype(layout)::value;
+                if (two)
+                    hipLaunchKernelGGL((taco::compress_mfma_kernel<kRB, kSub, 2, kIl>), dim3(waves), dim3(64), 0, st,
+                                       xin, n_tiles, p->tau, p->eps, pout, sout);
+                else
+                    hipLaunchKernelGGL((taco::compress_mfma_kernel<kRB, kSub, 1, kIl>), dim3(waves), dim3(64), 0, st,
+                                       xin, n_tiles, p->tau, p->eps, pout, sout);
+            });
             if (int rc = launch_status()) return rc;
         }
         first_block = n_tiles * (taco::kTileElems / B);
@@ -142,7 +224,7 @@ int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_par
             constexpr int kB = decltype(bc)::value;
             hipLaunchKernelGGL(taco::compress_butterfly_kernel<kB>, dim3(grid_for(rest, 32)), dim3(64), 0, st,
                                static_cast<const uint16_t*>(x_bf16), n, first_block, rest, tau, eps,
-                               static_cast<uint8_t*>(payload), static_cast<float2*>(scales));
+                               static_cast<uint8_t*>(payload), static_cast<float2*>(scales), il);
         });
         if (rc) return rc;
         if (int rc2 = launch_status()) return rc2;
@@ -153,120 +235,36 @@ int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_par
 int taco_decompress_sum(const void* const* payloads, const void* const* scales, int32_t k,
                         int64_t rows, int64_t cols, const taco_params* p, void* out_bf16,
                         void* stream) {
-    if (!payloads || !scales || !out_bf16) return TACO_ERR_NULL;
+    if (!out_bf16) return TACO_ERR_NULL;
     if (k < 1 || k > TACO_MAX_K) return TACO_ERR_K;
     int64_t n = 0;
     if (int rc = check_common(rows, cols, p, &n)) return rc;
     taco::PayloadTable tab{};
-    for (int i = 0; i < k; ++i) {
-        if (!payloads[i] || !scales[i]) return TACO_ERR_NULL;
-        if (!aligned16(payloads[i]) || !aligned16(scales[i])) return TACO_ERR_ALIGN;
-        tab.payload[i] = payloads[i];
-        tab.scales[i] = scales[i];
-    }
+    if (int rc = fill_table(payloads, scales, k, p->layout == TACO_LAYOUT_INTERLEAVED, &tab)) return rc;
     if (!aligned16(out_bf16)) return TACO_ERR_ALIGN;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int B = p->block;
-    const int64_t n_blocks = (n + B - 1) / B;
-    int64_t first_block = 0;
-    if (use_mfma(p)) {
-        const int64_t n_tiles = n / taco::kTileElems;
-        if (n_tiles > 0) {
-            // Two output tiles per wave and a ring of four (tile, payload) items in flight: measured
-            // best on MI355X for k = 1 and k = 8 (1..16 tiles, rings of 2..8 tried).
-            const int tiles_per_wave = 2;
-            const unsigned waves = static_cast<unsigned>((n_tiles + tiles_per_wave - 1) / tiles_per_wave);
-            auto* o = static_cast<taco::u32x4*>(out_bf16);
-#define TACO_LAUNCH_DECODE(RB, SUB)                                                                            \
-            hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<RB, SUB, 4, true, false>), dim3(waves), dim3(64), 0, st, \
-                               tab, static_cast<int>(k), n_tiles, tiles_per_wave, o, 0.0f, 0.0f, nullptr, nullptr)
-            switch (B) {
-                case 32: TACO_LAUNCH_DECODE(1, 4); break;
-                case 64: TACO_LAUNCH_DECODE(1, 2); break;
-                case 128: TACO_LAUNCH_DECODE(1, 1); break;
-                case 256: TACO_LAUNCH_DECODE(2, 1); break;
-                default: TACO_LAUNCH_DECODE(4, 1); break;
-            }
-#undef TACO_LAUNCH_DECODE
-            if (int rc = launch_status()) return rc;
-        }
-        first_block = n_tiles * (taco::kTileElems / B);
-    }
-    const int64_t rest = n_blocks - first_block;
-    if (rest > 0) {
-        int rc = dispatch_block(B, [&](auto bc) {
-            constexpr int kB = decltype(bc)::value;
-            hipLaunchKernelGGL(taco::decompress_sum_butterfly_kernel<kB>, dim3(grid_for(rest, 32)), dim3(64), 0, st,
-                               tab, static_cast<int>(k), n, first_block, rest, static_cast<uint16_t*>(out_bf16));
-        });
-        if (rc) return rc;
-        if (int rc2 = launch_status()) return rc2;
-    }
-    return TACO_OK;
+    return launch_decode(tab, k, n, p, false, out_bf16, nullptr, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int taco_decompress_sum_compress(const void* const* payloads, const void* const* scales, int32_t k,
                                  int64_t rows, int64_t cols, const taco_params* p, void* payload_out,
                                  void* scales_out, void* stream) {
-    if (!payloads || !scales || !payload_out || !scales_out) return TACO_ERR_NULL;
+    if (!payload_out) return TACO_ERR_NULL;
     if (k < 1 || k > TACO_MAX_K) return TACO_ERR_K;
     int64_t n = 0;
     if (int rc = check_common(rows, cols, p, &n)) return rc;
-    if (!(p->tau > 0.0f) || !(p->eps >= 0.0f) || !std::isfinite(p->tau) || !std::isfinite(p->eps)) return TACO_ERR_PARAM;
+    const bool il = p->layout == TACO_LAYOUT_INTERLEAVED;
+    if (!il && !scales_out) return TACO_ERR_NULL;
+    if (!params_ok_for_compress(p)) return TACO_ERR_PARAM;
     taco::PayloadTable tab{};
-    for (int i = 0; i < k; ++i) {
-        if (!payloads[i] || !scales[i]) return TACO_ERR_NULL;
-        if (!aligned16(payloads[i]) || !aligned16(scales[i])) return TACO_ERR_ALIGN;
-        tab.payload[i] = payloads[i];
-        tab.scales[i] = scales[i];
-    }
-    if (!aligned16(payload_out) || !aligned16(scales_out)) return TACO_ERR_ALIGN;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int B = p->block;
-    const int64_t n_blocks = (n + B - 1) / B;
-    int64_t first_block = 0;
-    if (use_mfma(p)) {
-        const int64_t n_tiles = n / taco::kTileElems;
-        if (n_tiles > 0) {
-            const int tiles_per_wave = 2;
-            const unsigned waves = static_cast<unsigned>((n_tiles + tiles_per_wave - 1) / tiles_per_wave);
-            auto* pout = static_cast<taco::u32x2*>(payload_out);
-            auto* sout = static_cast<taco::f32x2*>(scales_out);
-#define TACO_LAUNCH_FUSED(RB, SUB)                                                                             \
-            hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<RB, SUB, 4, true, true>), dim3(waves), dim3(64), 0, st,  \
-                               tab, static_cast<int>(k), n_tiles, tiles_per_wave, nullptr, p->tau, p->eps, pout, sout)
-            switch (B) {
-                case 32: TACO_LAUNCH_FUSED(1, 4); break;
-                case 64: TACO_LAUNCH_FUSED(1, 2); break;
-                case 128: TACO_LAUNCH_FUSED(1, 1); break;
-                case 256: TACO_LAUNCH_FUSED(2, 1); break;
-                default: TACO_LAUNCH_FUSED(4, 1); break;
-            }
-#undef TACO_LAUNCH_FUSED
-            if (int rc = launch_status()) return rc;
-        }
-        first_block = n_tiles * (taco::kTileElems / B);
-    }
-    const int64_t rest = n_blocks - first_block;
-    if (rest > 0) {
-        const float tau = p->tau, eps = p->eps;
-        int rc = dispatch_block(B, [&](auto bc) {
-            constexpr int kB = decltype(bc)::value;
-            hipLaunchKernelGGL(taco::decompress_sum_compress_butterfly_kernel<kB>, dim3(grid_for(rest, 32)), dim3(64), 0, st,
-                               tab, static_cast<int>(k), n, first_block, rest, tau, eps,
-                               static_cast<uint8_t*>(payload_out), static_cast<float2*>(scales_out));
-        });
-        if (rc) return rc;
-        if (int rc2 = launch_status()) return rc2;
-    }
-    return TACO_OK;
+    if (int rc = fill_table(payloads, scales, k, il, &tab)) return rc;
+    if (!aligned16(payload_out) || (!il && !aligned16(scales_out))) return TACO_ERR_ALIGN;
+    return launch_decode(tab, k, n, p, true, nullptr, payload_out, scales_out, static_cast<hipStream_t>(stream));
 }
 
 int taco_decompress(const void* payload, const void* scales, int64_t rows, int64_t cols,
                     const taco_params* p, void* out_bf16, void* stream) {
     const void* pl[1] = {payload};
     const void* sc[1] = {scales};
-    if (!payload || !scales) return TACO_ERR_NULL;
     return taco_decompress_sum(pl, sc, 1, rows, cols, p, out_bf16, stream);
 }
 
@@ -305,12 +303,13 @@ const char* taco_strerror(int status) {
         case TACO_ERR_K: return "k must be between 1 and 16";
         case TACO_ERR_FORMAT: return "unsupported format: only FP8 E4M3";
         case TACO_ERR_LAUNCH: return "kernel launch failed";
-        case TACO_ERR_IMPL: return "requested kernel does not exist for this block size";
+        case TACO_ERR_IMPL: return "bad kernel selection";
         case TACO_ERR_PARAM: return "bad parameter: tau must be positive and eps non-negative, both finite";
+        case TACO_ERR_LAYOUT: return "bad layout: must be split or interleaved";
         default: return "unknown status";
     }
 }
 
-const char* taco_version(void) { return "0.1"; }
+const char* taco_version(void) { return "0.2"; }
 
 }  // extern "C"

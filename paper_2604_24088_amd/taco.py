@@ -19,6 +19,7 @@ from . import build as _build
 TACO_MAX_K = 16
 TACO_FORMAT_E4M3 = 0
 TACO_IMPL_AUTO, TACO_IMPL_BUTTERFLY, TACO_IMPL_MFMA = 0, 1, 2
+TACO_LAYOUT_SPLIT, TACO_LAYOUT_INTERLEAVED = 0, 1
 
 EXPORTS = ("taco_default_params", "taco_payload_bytes", "taco_scales_bytes", "taco_compress",
            "taco_decompress", "taco_decompress_sum", "taco_decompress_sum_compress", "taco_debug_cvt_e4m3", "taco_debug_copy", "taco_strerror",
@@ -27,7 +28,7 @@ EXPORTS = ("taco_default_params", "taco_payload_bytes", "taco_scales_bytes", "ta
 
 class taco_params(ctypes.Structure):
     _fields_ = [("block", ctypes.c_int32), ("tau", ctypes.c_float), ("eps", ctypes.c_float),
-                ("format", ctypes.c_int32), ("impl", ctypes.c_int32)]
+                ("format", ctypes.c_int32), ("impl", ctypes.c_int32), ("layout", ctypes.c_int32)]
 
 
 class TacoError(RuntimeError):
@@ -90,10 +91,10 @@ def taco_version() -> str:
 
 
 def taco_default_params(block: int = 128, tau: float = 1.0, eps: float = 1e-12,
-                        impl: int = TACO_IMPL_AUTO) -> taco_params:
+                        impl: int = TACO_IMPL_AUTO, layout: int = TACO_LAYOUT_SPLIT) -> taco_params:
     p = taco_params()
     lib().taco_default_params(ctypes.byref(p))
-    p.block, p.tau, p.eps, p.impl = block, tau, eps, impl
+    p.block, p.tau, p.eps, p.impl, p.layout = block, tau, eps, impl, layout
     return p
 
 
@@ -116,6 +117,28 @@ def _check(status: int, where: str):
         raise TacoError(status, where)
 
 
+def _ptr_or_null(t):
+    return None if t is None else t.data_ptr()
+
+
+def _alloc_outputs(n: int, p: taco_params, device, payload, scales):
+    """Split layout: (codes, scales[n_blocks, 2]).  Interleaved: (one buffer of B + 8 byte records, None)."""
+    if p.layout == TACO_LAYOUT_INTERLEAVED:
+        if payload is None:
+            payload = torch.empty(taco_payload_bytes(n, p.block) + taco_scales_bytes(n, p.block),
+                                  dtype=torch.uint8, device=device)
+        return payload, None
+    if payload is None:
+        payload = torch.empty(taco_payload_bytes(n, p.block), dtype=torch.uint8, device=device)
+    if scales is None:
+        scales = torch.empty((taco_scales_bytes(n, p.block) // 8, 2), dtype=torch.float32, device=device)
+    return payload, scales
+
+
+def _pointer_array(tensors, k):
+    return (ctypes.c_void_p * max(k, 1))(*[_ptr_or_null(t) for t in tensors])
+
+
 def _rows_cols(shape) -> tuple:
     if len(shape) == 1:
         return 1, int(shape[0])
@@ -133,12 +156,9 @@ def taco_compress(x: torch.Tensor, params: Optional[taco_params] = None,
     assert x.is_cuda and x.dtype == torch.bfloat16 and x.is_contiguous()
     rows, cols = _rows_cols(x.shape)
     n = rows * cols
-    if payload is None:
-        payload = torch.empty(taco_payload_bytes(n, p.block), dtype=torch.uint8, device=x.device)
-    if scales is None:
-        scales = torch.empty((taco_scales_bytes(n, p.block) // 8, 2), dtype=torch.float32, device=x.device)
+    payload, scales = _alloc_outputs(n, p, x.device, payload, scales)
     st = lib().taco_compress(x.data_ptr(), rows, cols, ctypes.byref(p), payload.data_ptr(),
-                             scales.data_ptr(), _stream_handle(stream))
+                             _ptr_or_null(scales), _stream_handle(stream))
     _check(st, "taco_compress")
     return payload, scales
 
@@ -151,7 +171,7 @@ def taco_decompress(payload: torch.Tensor, scales: torch.Tensor, shape,
     rows, cols = _rows_cols(tuple(shape))
     if out is None:
         out = torch.empty(tuple(shape), dtype=torch.bfloat16, device=payload.device)
-    st = lib().taco_decompress(payload.data_ptr(), scales.data_ptr(), rows, cols, ctypes.byref(p),
+    st = lib().taco_decompress(payload.data_ptr(), _ptr_or_null(scales), rows, cols, ctypes.byref(p),
                                out.data_ptr(), _stream_handle(stream))
     _check(st, "taco_decompress")
     return out
@@ -163,12 +183,13 @@ def taco_decompress_sum(payloads: Sequence[torch.Tensor], scales: Sequence[torch
     """Decode k payloads and add them (fp32 accumulation, one bf16 rounding)."""
     p = params or taco_default_params()
     k = len(payloads)
+    scales = list(scales) if scales is not None else [None] * k
     assert k == len(scales)
     rows, cols = _rows_cols(tuple(shape))
     if out is None:
         out = torch.empty(tuple(shape), dtype=torch.bfloat16, device=payloads[0].device)
-    parr = (ctypes.c_void_p * max(k, 1))(*[t.data_ptr() for t in payloads])
-    sarr = (ctypes.c_void_p * max(k, 1))(*[t.data_ptr() for t in scales])
+    parr = _pointer_array(payloads, k)
+    sarr = _pointer_array(scales, k)
     st = lib().taco_decompress_sum(parr, sarr, k, rows, cols, ctypes.byref(p), out.data_ptr(),
                                    _stream_handle(stream))
     _check(st, "taco_decompress_sum")
@@ -182,18 +203,15 @@ def taco_decompress_sum_compress(payloads: Sequence[torch.Tensor], scales: Seque
     """Decode and add k payloads, round the sum to bf16 and compress it again, in one pass."""
     p = params or taco_default_params()
     k = len(payloads)
+    scales = list(scales) if scales is not None else [None] * k
     assert k == len(scales)
     rows, cols = _rows_cols(tuple(shape))
     n = rows * cols
-    dev = payloads[0].device
-    if payload_out is None:
-        payload_out = torch.empty(taco_payload_bytes(n, p.block), dtype=torch.uint8, device=dev)
-    if scales_out is None:
-        scales_out = torch.empty((taco_scales_bytes(n, p.block) // 8, 2), dtype=torch.float32, device=dev)
-    parr = (ctypes.c_void_p * max(k, 1))(*[t.data_ptr() for t in payloads])
-    sarr = (ctypes.c_void_p * max(k, 1))(*[t.data_ptr() for t in scales])
+    payload_out, scales_out = _alloc_outputs(n, p, payloads[0].device, payload_out, scales_out)
+    parr = _pointer_array(payloads, k)
+    sarr = _pointer_array(scales, k)
     st = lib().taco_decompress_sum_compress(parr, sarr, k, rows, cols, ctypes.byref(p), payload_out.data_ptr(),
-                                            scales_out.data_ptr(), _stream_handle(stream))
+                                            _ptr_or_null(scales_out), _stream_handle(stream))
     _check(st, "taco_decompress_sum_compress")
     return payload_out, scales_out
 

@@ -90,3 +90,19 @@ def check_recon(gpu_bits: np.ndarray, ref_bits: np.ndarray, block: int, what: st
     exact = float((err == 0).mean())
     assert exact >= min_exact, f"{what}: only {exact:.6f} of outputs identical"
     return exact
+
+
+# ---- the interleaved payload layout: pure data movement, no arithmetic ---------------------------
+
+def interleave(payload: np.ndarray, scales: np.ndarray, block: int) -> np.ndarray:
+    """codes[M*B] + scales[M,2] -> M records of B + 8 bytes (B codes, float alpha, float s)."""
+    m = payload.size // block
+    rec = np.empty((m, block + 8), dtype=np.uint8)
+    rec[:, :block] = payload.reshape(m, block)
+    rec[:, block:] = np.ascontiguousarray(scales, dtype=np.float32).reshape(m, 2).view(np.uint8)
+    return rec.reshape(-1)
+
+
+def deinterleave(buf: np.ndarray, block: int):
+    rec = buf.reshape(-1, block + 8)
+    return np.ascontiguousarray(rec[:, :block]).reshape(-1), np.ascontiguousarray(rec[:, block:]).view(np.float32).reshape(-1, 2)

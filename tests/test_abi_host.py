@@ -29,14 +29,14 @@ def test_library_exports_every_declared_symbol():
 def test_version_and_strerror():
     assert re.fullmatch(r"\d+\.\d+", taco.taco_version())
     assert taco.taco_strerror(0) == "ok"
-    for st in range(-9, 0):
+    for st in range(-10, 0):
         assert taco.taco_strerror(st) not in ("ok", "unknown status")
     assert taco.taco_strerror(-100) == "unknown status"
 
 
 def test_default_params():
     p = taco.taco_default_params()
-    assert (p.block, p.format, p.impl) == (128, 0, 0)
+    assert (p.block, p.format, p.impl, p.layout) == (128, 0, 0, 0)
     assert p.tau == 1.0 and abs(p.eps - 1e-12) < 1e-18
 
 
@@ -65,6 +65,7 @@ A = 0x1000  # a fake, 16-byte aligned, non-null "device pointer": never derefere
     (dict(x=A + 2), -4), (dict(payload=A + 8), -4), (dict(scales=A + 4), -4),
     (dict(p=_params(format=1)), -6),
     (dict(p=_params(impl=7)), -8), (dict(p=_params(impl=-1)), -8),
+    (dict(p=_params(layout=2)), -10), (dict(p=_params(layout=-1)), -10),
     (dict(p=_params(tau=0.0)), -9), (dict(p=_params(eps=-1.0)), -9), (dict(p=_params(tau=float("nan"))), -9),
 ])
 def test_compress_rejects_bad_arguments(args, status):
@@ -81,6 +82,19 @@ def test_decompress_sum_rejects_bad_k(k, status):
     arr = (ctypes.c_void_p * 17)(*([A] * 17))
     p = _params()
     assert L.taco_decompress_sum(arr, arr, k, 4, 512, ctypes.byref(p), A, None) == status
+
+
+def test_interleaved_layout_needs_no_scales_pointer():
+    """With records of codes + scalars the scales arguments are ignored; the calls below stop at the
+    NEXT check (a misaligned payload), which shows the NULL scales pointers were accepted."""
+    L = taco.lib()
+    p = _params(layout=1)
+    assert L.taco_compress(A, 4, 512, ctypes.byref(p), A + 8, None, None) == -4
+    arr = (ctypes.c_void_p * 2)(A, A + 8)
+    assert L.taco_decompress_sum(arr, None, 2, 4, 512, ctypes.byref(p), A, None) == -4
+    assert L.taco_decompress_sum_compress(arr, None, 2, 4, 512, ctypes.byref(p), A, None, None) == -4
+    split = _params(layout=0)
+    assert L.taco_decompress_sum(arr, None, 2, 4, 512, ctypes.byref(split), A, None) == -1
 
 
 def test_fused_rejects_bad_arguments():

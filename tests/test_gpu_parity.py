@@ -392,3 +392,50 @@ def test_fused_sum_compress(oracle, block, k, n, impl):
         tol = 1.75 * flips + np.maximum(2.0 ** -9, np.abs(rv) * 2.0 ** -3)
         assert np.all(np.abs(gv - rv) <= tol)
         assert (gp[~same] == rp.reshape(-1, block)[~same]).mean() >= 0.9
+
+
+# ---- interleaved payload layout (records of B codes + {alpha, s}) ------------------------------------
+
+@pytest.mark.parametrize("block,impl", [(128, "mfma"), (128, "butterfly"), (256, "mfma"), (512, "mfma"), (64, "mfma"),
+                                        (32, "mfma"), (32, "butterfly")])
+@pytest.mark.parametrize("n", [2048 * 12, 2048 * 3 + 700, 300])
+def test_interleaved_layout(oracle, block, impl, n):
+    rng = np.random.default_rng(block * 7 + n)
+    x = rng.standard_normal(n) * 0.02
+    x[rng.integers(0, n, max(n // 300, 1))] *= 30.0
+    xb = W.float32_to_bf16_bits(x.astype(np.float32))
+    rp, rs = oracle.compress(xb, block=block)
+    il = taco.taco_default_params(block=block, impl=IMPLS[impl], layout=taco.TACO_LAYOUT_INTERLEAVED)
+    padded = np.concatenate([xb, np.zeros((-n) % 8, dtype=np.uint16)])
+    # compress: same codes and scales as the oracle, found at the record positions
+    buf, none = taco.taco_compress(to_dev(padded)[:n], il)
+    torch.cuda.synchronize()
+    assert none is None and buf.numel() == rp.size + rs.size * 4
+    gp, gs = P.deinterleave(buf.cpu().numpy(), block)
+    P.check_scales(gs, rs, f"interleaved B={block}")
+    P.check_codes(gp, rp, rs, block, f"interleaved B={block}")
+    # ... and bit-identical to the split layout of the same kernels
+    sp, ss = taco.taco_compress(to_dev(padded)[:n], taco.taco_default_params(block=block, impl=IMPLS[impl]))
+    torch.cuda.synchronize()
+    assert np.array_equal(gp, sp.cpu().numpy()) and np.array_equal(gs, ss.cpu().numpy())
+    # decompress / decompress_sum of the oracle's payload in record form
+    ref = oracle.decompress(rp, rs, n, block=block)
+    rec = torch.from_numpy(P.interleave(rp, rs, block)).to(DEV)
+    out = taco.taco_decompress(rec, None, (n,), il)
+    torch.cuda.synchronize()
+    P.check_recon(bits_of(out), ref, block, f"interleaved B={block}")
+    x2 = W.float32_to_bf16_bits((rng.standard_normal(n) * 0.05).astype(np.float32))
+    rp2, rs2 = oracle.compress(x2, block=block)
+    rec2 = torch.from_numpy(P.interleave(rp2, rs2, block)).to(DEV)
+    ref2 = oracle.decompress_sum([rp, rp2, rp], [rs, rs2, rs], n, block=block)
+    out2 = taco.taco_decompress_sum([rec, rec2, rec], None, (n,), il)
+    torch.cuda.synchronize()
+    P.check_recon(bits_of(out2), ref2, block, f"interleaved sum B={block}", min_exact=P.RECON_EXACT_MIN_SUM)
+    # fused sum -> compress in record form equals the split-layout result
+    fbuf, _ = taco.taco_decompress_sum_compress([rec, rec2, rec], None, (n,), il)
+    sp3, ss3 = taco.taco_decompress_sum_compress(
+        [torch.from_numpy(a).to(DEV) for a in (rp, rp2, rp)], [torch.from_numpy(a).to(DEV) for a in (rs, rs2, rs)], (n,),
+        taco.taco_default_params(block=block, impl=IMPLS[impl]))
+    torch.cuda.synchronize()
+    fp3, fs3 = P.deinterleave(fbuf.cpu().numpy(), block)
+    assert np.array_equal(fp3, sp3.cpu().numpy()) and np.array_equal(fs3, ss3.cpu().numpy())
