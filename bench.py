@@ -81,7 +81,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
-    taco.lib()   # fail loudly if the HIP library is missing
+    from paper_2604_24088_amd import build as hip_build
+    hip_build.ensure_built()   # load what is built; build only if nothing is
+    taco.lib()                 # fails loudly if the HIP library cannot be loaded
     dev = torch.device("cuda:0")
     w = W.WORKLOADS[args.workload]
     k, n, B = w.payloads, w.numel, args.block

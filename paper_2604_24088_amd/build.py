@@ -48,5 +48,10 @@ def build(force: bool = True, extra=()) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Build only when no library is there (tests, smoke and bench call this; the binding itself never builds)."""
+    return LIB if os.path.exists(LIB) else build(force=True)
+
+
 if __name__ == "__main__":
     print(build(force=True))

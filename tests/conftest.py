@@ -10,6 +10,9 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # Load what is built; build only if nothing is (hipcc cross-compiles without a GPU).
+    from paper_2604_24088_amd import build as hip_build
+    hip_build.ensure_built()
 
 
 @pytest.fixture(scope="session")
