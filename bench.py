@@ -204,7 +204,9 @@ def main():
                   "decompress": call(t_dec, bytes_dec, 2.0 * n),
                   f"decompress_sum_k{k}": call(t_sum, bytes_sum, k * 2.0 * n),
                   f"decompress_sum_compress_k{k} (not in the step)": call(t_fused, (k + 1) * per_elem * n, k * 2.0 * n)},
-        "roofline": {"kernel": f"compress_mfma_kernel<{B // 128},2,true>" if (B >= 128 and args.impl != "butterfly") else f"compress_butterfly_kernel<{B}>",
+        "roofline": {"kernel": (f"compress_mfma_kernel<{max(B // 128, 1)},{max(128 // B, 1)},{2 if n // 2048 >= 65536 else 1},"
+                                f"{'true' if args.layout == 'interleaved' else 'false'}>") if args.impl != "butterfly"
+                     else f"compress_butterfly_kernel<{B}>",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, B, args.impl)) if args.layout == "split" else None,

@@ -24,7 +24,7 @@
  *   - A tensor of `rows` x `cols` bf16 values is row-major and is treated as the flat
  *     vector of n = rows*cols elements; blocks may straddle rows.  When n is not a
  *     multiple of B the last block is zero padded (sigma still divides by B).
- *   - FP8 is E4M3 in the OCP 8-bit layout (1 sign, 4 exponent bits with bias 7, 3
+ *   - FP8 is (unless params->format says otherwise) E4M3 in the OCP 8-bit layout (1 sign, 4 exponent bits with bias 7, 3
  *     mantissa bits, subnormals, no infinities, Q_max = 448), round to nearest even.
  *   - Hadamard matrix: natural (Sylvester) order, H[i][j] = (-1)^popcount(i & j).
  *   - Payload layout: ceil(n/B)*B one-byte codes, code i of block k at byte k*B + i.
@@ -56,14 +56,26 @@ typedef enum taco_status {
     TACO_ERR_BLOCK = -3,  /* block is not one of 32, 64, 128, 256, 512                */
     TACO_ERR_ALIGN = -4,  /* a data pointer is not 16-byte aligned                    */
     TACO_ERR_K = -5,      /* k outside 1..TACO_MAX_K                                  */
-    TACO_ERR_FORMAT = -6, /* params->format is not TACO_FORMAT_E4M3                   */
+    TACO_ERR_FORMAT = -6, /* params->format is not one of TACO_FORMAT_*               */
     TACO_ERR_LAUNCH = -7, /* the HIP runtime refused the launch (hipGetLastError)     */
-    TACO_ERR_IMPL = -8,   /* params->impl is not one of TACO_IMPL_*                   */
+    TACO_ERR_IMPL = -8,   /* params->impl is not one of TACO_IMPL_*, or MFMA was forced
+                             for an ablation variant                                  */
     TACO_ERR_PARAM = -9,  /* tau <= 0, eps < 0, or a non-finite parameter             */
-    TACO_ERR_LAYOUT = -10 /* params->layout is not one of TACO_LAYOUT_*               */
+    TACO_ERR_LAYOUT = -10,/* params->layout is not one of TACO_LAYOUT_*               */
+    TACO_ERR_MODE = -11   /* params->mode is outside 0..TACO_MODE_FULL                */
 } taco_status;
 
-enum { TACO_FORMAT_E4M3 = 0 };
+/* Code book.  E4M3 is the method's (chosen by the paper's format ablation, Section 5.3); E5M2
+ * (OCP: bias 15, Q_max 57344) and INT8 (round(x / Delta), Delta = max|x| / 127, Section 2.3) are the
+ * two alternatives that ablation compares against. */
+enum { TACO_FORMAT_E4M3 = 0, TACO_FORMAT_E5M2 = 1, TACO_FORMAT_INT8 = 2 };
+
+/* Stages of the method, for the paper's component ablations (Section 5.2.2, Section 5.3): a bit
+ * mask.  Without RESCALE alpha_k = 1; without ROTATE Z_k = alpha_k G_k; without POSTSCALE s_k = 1
+ * and Z_k itself is converted, saturating at +-Q_max.  FULL (7) is the method; 0 is the direct
+ * cast, 4 "DS only", 2 the standard Hadamard transform, 3 ASH without DS.  Every variant other
+ * than FULL + E4M3 runs on the butterfly kernels: they are there for numerical studies. */
+enum { TACO_MODE_RESCALE = 1, TACO_MODE_ROTATE = 2, TACO_MODE_POSTSCALE = 4, TACO_MODE_FULL = 7 };
 
 /* Kernel selection.  AUTO and MFMA run whole tiles of 2048 elements on the matrix-core
  * kernel and the rest of the tensor on the plain butterfly kernel; BUTTERFLY runs everything
@@ -85,12 +97,13 @@ typedef struct taco_params {
     int32_t block;  /* B: 32, 64, 128, 256 or 512                                  */
     float tau;      /* tau of Eq. ash_alpha, > 0 (the paper gives no value; 1.0f)  */
     float eps;      /* eps of Eq. ash_sigma, >= 0 (the paper gives no value; 1e-12f) */
-    int32_t format; /* TACO_FORMAT_E4M3                                            */
+    int32_t format; /* TACO_FORMAT_*                                               */
     int32_t impl;   /* TACO_IMPL_*                                                 */
     int32_t layout; /* TACO_LAYOUT_*                                               */
+    int32_t mode;   /* TACO_MODE_* bit mask, TACO_MODE_FULL for the method         */
 } taco_params;
 
-/* Fills *p with B = 128, tau = 1, eps = 1e-12, E4M3, AUTO, SPLIT. */
+/* Fills *p with B = 128, tau = 1, eps = 1e-12, E4M3, AUTO, SPLIT, FULL. */
 void taco_default_params(taco_params* p);
 
 /* Sizes of the two output regions of taco_compress for n elements: ceil(n/B)*B bytes of

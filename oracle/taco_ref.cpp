@@ -32,6 +32,15 @@
 //   * The reduction of k decoded payloads accumulates in double, payload index ascending,
 //     and rounds once to bf16 (via binary32), Section 4.4.2 "single local reduction".
 //
+// Ablation variants (Section 5.3 "Ablation Study", Section 5.2.2 "Component-wise Analysis"): the
+// same pipeline with a stage switched off or another code book.  `mode` is a bit mask
+//   1 rescale    alpha_k = tau / sigma_k, else alpha_k = 1           (Adaptive Scale)
+//   2 rotate     Z_k = H (alpha G) / sqrt(B), else Z_k = alpha G     (Hadamard)
+//   4 postscale  s_k = max|Z_k| / Q_max, else s_k = 1                (Dual-Scale)
+// and `format` selects E4M3 (Q_max 448), E5M2 (Q_max 57344) or INT8 (round(x / Delta),
+// Delta = max|x| / 127, Section 2.3).  mode 7 + E4M3 is the method itself; 0 is the direct cast,
+// 4 "DS only", 2 the standard Hadamard transform, 3 ASH without DS.
+//
 // Pins: see tests/test_oracle_*.py (exhaustive E4M3 table against an independent
 // library decode, H H^T = B I and a library Hadamard matrix, closed forms for the
 // all-zero, single-outlier and constant blocks, brute-force scales, error bound).
@@ -121,6 +130,64 @@ uint8_t e4m3_encode(double v) {
     return sign | static_cast<uint8_t>(code);
 }
 
+// ---- FP8 E5M2 (OCP): s eeeee mm, bias 15, subnormals (m/4) 2^-14, e = 31: infinity (m = 0) or NaN ----
+
+constexpr double kQmaxE5M2 = 57344.0;   // 1.75 * 2^15
+
+double e5m2_decode(uint8_t code) {
+    int sign = code >> 7;
+    int e = (code >> 2) & 0x1f;
+    int m = code & 0x3;
+    double mag;
+    if (e == 0x1f) mag = (m == 0) ? INFINITY : std::nan("");
+    else if (e == 0) mag = std::ldexp(static_cast<double>(m), -16);
+    else mag = std::ldexp(4.0 + static_cast<double>(m), e - 17);
+    return sign ? -mag : mag;
+}
+
+// Nearest E5M2 code, ties to even, saturating at +-57344, sign kept on underflow.
+uint8_t e5m2_encode(double v) {
+    if (std::isnan(v)) return 0x7f;
+    uint8_t sign = std::signbit(v) ? 0x80 : 0x00;
+    double a = std::fabs(v);
+    if (a >= kQmaxE5M2) return sign | 0x7b;
+    int ex;
+    std::frexp(a, &ex);
+    int p = (a < std::ldexp(1.0, -14)) ? -14 : ex - 1;
+    double steps = round_half_even(std::ldexp(a, 2 - p));   // in units of the local step 2^(p-2)
+    int code;
+    if (p == -14 && steps < 4.0) {
+        code = static_cast<int>(steps);
+    } else {
+        if (steps == 8.0) { steps = 4.0; p += 1; }
+        code = ((p + 15) << 2) | (static_cast<int>(steps) - 4);
+    }
+    if (code > 0x7b) code = 0x7b;
+    return sign | static_cast<uint8_t>(code);
+}
+
+// INT8 of Section 2.3: round to the nearest integer (ties to even), clamp to [-127, 127], two's complement byte.
+uint8_t int8_encode(double v) {
+    if (std::isnan(v)) return 0;
+    double a = std::fabs(v);
+    double r = a >= 127.0 ? 127.0 : round_half_even(a);
+    int q = static_cast<int>(r);
+    if (std::signbit(v)) q = -q;
+    return static_cast<uint8_t>(static_cast<int8_t>(q));
+}
+double int8_decode(uint8_t code) { return static_cast<double>(static_cast<int8_t>(code)); }
+
+enum { FORMAT_E4M3 = 0, FORMAT_E5M2 = 1, FORMAT_INT8 = 2 };
+enum { MODE_RESCALE = 1, MODE_ROTATE = 2, MODE_POSTSCALE = 4, MODE_FULL = 7 };
+
+double format_qmax(int format) { return format == FORMAT_E4M3 ? kQmax : format == FORMAT_E5M2 ? kQmaxE5M2 : 127.0; }
+uint8_t format_encode(int format, double v) {
+    return format == FORMAT_E4M3 ? e4m3_encode(v) : format == FORMAT_E5M2 ? e5m2_encode(v) : int8_encode(v);
+}
+double format_decode(int format, uint8_t c) {
+    return format == FORMAT_E4M3 ? e4m3_decode(c) : format == FORMAT_E5M2 ? e5m2_decode(c) : int8_decode(c);
+}
+
 // ---- Hadamard matrix -----------------------------------------------------------------------
 
 bool is_pow2(int64_t b) { return b >= 1 && (b & (b - 1)) == 0; }
@@ -151,13 +218,17 @@ void matvec(const std::vector<double>& H, int B, const double* x, double* y) {
 
 // Decode one block of one payload into g'[0..B): Eqs. recon_dequant, recon_ifwht, recon_rescale.
 void decode_block(const std::vector<double>& H, int B, const uint8_t* codes, float alpha_f,
-                  float s_f, double* zhat, double* gprime) {
+                  float s_f, double* zhat, double* gprime, int mode = MODE_FULL, int format = FORMAT_E4M3) {
     const double alpha = static_cast<double>(alpha_f);
     const double s = static_cast<double>(s_f);
     const double root_b = std::sqrt(static_cast<double>(B));
-    for (int i = 0; i < B; ++i) zhat[i] = e4m3_decode(codes[i]) * s;
-    matvec(H, B, zhat, gprime);
-    for (int j = 0; j < B; ++j) gprime[j] = (gprime[j] / root_b) / alpha;
+    for (int i = 0; i < B; ++i) zhat[i] = format_decode(format, codes[i]) * s;
+    if (mode & MODE_ROTATE) {
+        matvec(H, B, zhat, gprime);
+        for (int j = 0; j < B; ++j) gprime[j] = (gprime[j] / root_b) / alpha;
+    } else {
+        for (int j = 0; j < B; ++j) gprime[j] = zhat[j] / alpha;
+    }
 }
 
 }  // namespace
@@ -176,6 +247,8 @@ int taco_ref_threads(void) {
 }
 
 double taco_ref_e4m3_decode(uint8_t code) { return e4m3_decode(code); }
+double taco_ref_format_decode(int32_t format, uint8_t code) { return format_decode(format, code); }
+uint8_t taco_ref_format_encode(int32_t format, double v) { return format_encode(format, v); }
 uint8_t taco_ref_e4m3_encode(double v) { return e4m3_encode(v); }
 uint16_t taco_ref_float_to_bf16(float f) { return float_to_bf16(f); }
 
@@ -202,14 +275,17 @@ int taco_ref_rotate(const double* x, int32_t block, double* y) {
 // Sender side of Algorithm 1.  x: n bf16 values (host).  payload: ceil(n/B)*B codes.
 // scales: ceil(n/B) pairs {alpha_k, s_k} as fp32.  z_out (optional, may be null):
 // ceil(n/B)*B doubles receiving the rotated values Z_k before quantisation.
-int taco_ref_compress(const uint16_t* x, int64_t n, int32_t block, float tau_f, float eps_f,
-                      uint8_t* payload, float* scales, double* z_out) {
+// mode / format: ablation variants (see the header); MODE_FULL and FORMAT_E4M3 give the method.
+int taco_ref_compress_ex(const uint16_t* x, int64_t n, int32_t block, float tau_f, float eps_f, int32_t mode,
+                         int32_t format, uint8_t* payload, float* scales, double* z_out) {
     if (!x || !payload || !scales || n <= 0 || !is_pow2(block) || block < 2) return TACO_REF_ERR_ARG;
+    if (mode < 0 || mode > MODE_FULL || format < FORMAT_E4M3 || format > FORMAT_INT8) return TACO_REF_ERR_ARG;
     const int B = block;
     const int64_t M = (n + B - 1) / B;
     const double tau = static_cast<double>(tau_f);
     const double eps = static_cast<double>(eps_f);
     const double root_b = std::sqrt(static_cast<double>(B));
+    const double qmax = format_qmax(format);
     std::vector<double> H;
     fill_hadamard(B, H);
 
@@ -224,24 +300,29 @@ int taco_ref_compress(const uint16_t* x, int64_t n, int32_t block, float tau_f, 
                 g[j] = idx < n ? bf16_to_double(x[idx]) : 0.0;
             }
             // Eq. ash_sigma, Eq. ash_alpha.
-            double energy = 0.0;
-            for (int j = 0; j < B; ++j) energy += g[j] * g[j];
-            const double sigma = std::sqrt(energy / B + eps);
-            const float alpha_f = static_cast<float>(tau / sigma);
+            float alpha_f = 1.0f;
+            if (mode & MODE_RESCALE) {
+                double energy = 0.0;
+                for (int j = 0; j < B; ++j) energy += g[j] * g[j];
+                const double sigma = std::sqrt(energy / B + eps);
+                alpha_f = static_cast<float>(tau / sigma);
+            }
             const double alpha = static_cast<double>(alpha_f);
             // Rescale, then Eq. ash_rotation.
             for (int j = 0; j < B; ++j) g[j] = alpha * g[j];
-            matvec(H, B, g.data(), w.data());
             double amax = 0.0;
-            for (int i = 0; i < B; ++i) {
-                z[i] = w[i] / root_b;
-                amax = std::fmax(amax, std::fabs(z[i]));
+            if (mode & MODE_ROTATE) {
+                matvec(H, B, g.data(), w.data());
+                for (int i = 0; i < B; ++i) z[i] = w[i] / root_b;
+            } else {
+                for (int i = 0; i < B; ++i) z[i] = g[i];
             }
+            for (int i = 0; i < B; ++i) amax = std::fmax(amax, std::fabs(z[i]));
             // Eq. post_scale, Eq. quantization.
-            const float s_f = static_cast<float>(amax / kQmax);
+            const float s_f = (mode & MODE_POSTSCALE) ? static_cast<float>(amax / qmax) : 1.0f;
             const double s = static_cast<double>(s_f);
             uint8_t* q = payload + k * B;
-            for (int i = 0; i < B; ++i) q[i] = (s_f == 0.0f) ? 0x00 : e4m3_encode(z[i] / s);
+            for (int i = 0; i < B; ++i) q[i] = (s_f == 0.0f) ? 0x00 : format_encode(format, z[i] / s);
             scales[2 * k + 0] = alpha_f;
             scales[2 * k + 1] = s_f;
             if (z_out) std::memcpy(z_out + k * B, z.data(), sizeof(double) * B);
@@ -250,13 +331,20 @@ int taco_ref_compress(const uint16_t* x, int64_t n, int32_t block, float tau_f, 
     return TACO_REF_OK;
 }
 
+int taco_ref_compress(const uint16_t* x, int64_t n, int32_t block, float tau_f, float eps_f,
+                      uint8_t* payload, float* scales, double* z_out) {
+    return taco_ref_compress_ex(x, n, block, tau_f, eps_f, MODE_FULL, FORMAT_E4M3, payload, scales, z_out);
+}
+
 // Receiver side of Algorithm 1 followed by the local reduction over k payloads:
 // out[j] = bf16( fp32( sum_i G'^(i)_j ) ).  k = 1 is plain decompression.
 // sum_out (optional): n doubles receiving the unrounded sum.
-int taco_ref_decompress_sum(const uint8_t* const* payloads, const float* const* scales, int32_t k,
-                            int64_t n, int32_t block, uint16_t* out, double* sum_out) {
+int taco_ref_decompress_sum_ex(const uint8_t* const* payloads, const float* const* scales, int32_t k,
+                               int64_t n, int32_t block, int32_t mode, int32_t format, uint16_t* out,
+                               double* sum_out) {
     if (!payloads || !scales || !out || k < 1 || n <= 0 || !is_pow2(block) || block < 2)
         return TACO_REF_ERR_ARG;
+    if (mode < 0 || mode > MODE_FULL || format < FORMAT_E4M3 || format > FORMAT_INT8) return TACO_REF_ERR_ARG;
     for (int i = 0; i < k; ++i)
         if (!payloads[i] || !scales[i]) return TACO_REF_ERR_ARG;
     const int B = block;
@@ -272,7 +360,7 @@ int taco_ref_decompress_sum(const uint8_t* const* payloads, const float* const* 
             for (int j = 0; j < B; ++j) acc[j] = 0.0;
             for (int i = 0; i < k; ++i) {
                 decode_block(H, B, payloads[i] + b * B, scales[i][2 * b], scales[i][2 * b + 1],
-                             zhat.data(), gp.data());
+                             zhat.data(), gp.data(), mode, format);
                 for (int j = 0; j < B; ++j) acc[j] += gp[j];
             }
             for (int j = 0; j < B; ++j) {
@@ -284,6 +372,11 @@ int taco_ref_decompress_sum(const uint8_t* const* payloads, const float* const* 
         }
     }
     return TACO_REF_OK;
+}
+
+int taco_ref_decompress_sum(const uint8_t* const* payloads, const float* const* scales, int32_t k,
+                            int64_t n, int32_t block, uint16_t* out, double* sum_out) {
+    return taco_ref_decompress_sum_ex(payloads, scales, k, n, block, MODE_FULL, FORMAT_E4M3, out, sum_out);
 }
 
 int taco_ref_decompress(const uint8_t* payload, const float* scales, int64_t n, int32_t block,

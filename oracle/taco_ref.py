@@ -29,6 +29,10 @@ def lib():
         L.taco_ref_e4m3_decode.argtypes = [c.c_uint8]
         L.taco_ref_e4m3_encode.restype = c.c_uint8
         L.taco_ref_e4m3_encode.argtypes = [c.c_double]
+        L.taco_ref_format_decode.restype = c.c_double
+        L.taco_ref_format_decode.argtypes = [c.c_int32, c.c_uint8]
+        L.taco_ref_format_encode.restype = c.c_uint8
+        L.taco_ref_format_encode.argtypes = [c.c_int32, c.c_double]
         L.taco_ref_float_to_bf16.restype = c.c_uint16
         L.taco_ref_float_to_bf16.argtypes = [c.c_float]
         L.taco_ref_hadamard_matrix.restype = c.c_int
@@ -38,6 +42,12 @@ def lib():
         L.taco_ref_compress.restype = c.c_int
         L.taco_ref_compress.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_float, c.c_float,
                                         c.c_void_p, c.c_void_p, c.c_void_p]
+        L.taco_ref_compress_ex.restype = c.c_int
+        L.taco_ref_compress_ex.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_float, c.c_float, c.c_int32, c.c_int32,
+                                           c.c_void_p, c.c_void_p, c.c_void_p]
+        L.taco_ref_decompress_sum_ex.restype = c.c_int
+        L.taco_ref_decompress_sum_ex.argtypes = [c.c_void_p, c.c_void_p, c.c_int32, c.c_int64, c.c_int32, c.c_int32,
+                                                 c.c_int32, c.c_void_p, c.c_void_p]
         L.taco_ref_decompress_sum.restype = c.c_int
         L.taco_ref_decompress_sum.argtypes = [c.c_void_p, c.c_void_p, c.c_int32, c.c_int64,
                                               c.c_int32, c.c_void_p, c.c_void_p]
@@ -62,6 +72,18 @@ def e4m3_decode(code: int) -> float:
 
 def e4m3_encode(v: float) -> int:
     return int(lib().taco_ref_e4m3_encode(float(v)))
+
+
+FORMAT_E4M3, FORMAT_E5M2, FORMAT_INT8 = 0, 1, 2
+MODE_RESCALE, MODE_ROTATE, MODE_POSTSCALE, MODE_FULL = 1, 2, 4, 7
+
+
+def format_decode(fmt: int, code: int) -> float:
+    return lib().taco_ref_format_decode(int(fmt), int(code) & 0xFF)
+
+
+def format_encode(fmt: int, v: float) -> int:
+    return int(lib().taco_ref_format_encode(int(fmt), float(v)))
 
 
 def float_to_bf16(f: float) -> int:
@@ -91,7 +113,7 @@ def n_blocks(n: int, block: int) -> int:
 
 
 def compress(x_bf16: np.ndarray, block: int = 128, tau: float = 1.0, eps: float = 1e-12,
-             want_z: bool = False):
+             want_z: bool = False, mode: int = MODE_FULL, fmt: int = FORMAT_E4M3):
     """x_bf16: uint16 array (any shape, flattened row-major).
     Returns (payload uint8[M*B], scales float32[M,2] = {alpha, s}) and, if want_z,
     the rotated values Z (float64[M*B]) before quantisation."""
@@ -101,14 +123,15 @@ def compress(x_bf16: np.ndarray, block: int = 128, tau: float = 1.0, eps: float 
     payload = np.empty(M * block, dtype=np.uint8)
     scales = np.empty((M, 2), dtype=np.float32)
     z = np.empty(M * block, dtype=np.float64) if want_z else None
-    rc = lib().taco_ref_compress(_ptr(x), n, block, float(np.float32(tau)), float(np.float32(eps)),
-                                 _ptr(payload), _ptr(scales), _ptr(z) if want_z else None)
+    rc = lib().taco_ref_compress_ex(_ptr(x), n, block, float(np.float32(tau)), float(np.float32(eps)), mode, fmt,
+                                    _ptr(payload), _ptr(scales), _ptr(z) if want_z else None)
     if rc != 0:
         raise ValueError(f"taco_ref_compress(n={n}, B={block}) -> {rc}")
     return (payload, scales, z) if want_z else (payload, scales)
 
 
-def decompress_sum(payloads, scales, n: int, block: int = 128, want_sum: bool = False):
+def decompress_sum(payloads, scales, n: int, block: int = 128, want_sum: bool = False,
+                   mode: int = MODE_FULL, fmt: int = FORMAT_E4M3):
     """payloads: list of k uint8[M*B]; scales: list of k float32[M,2].
     Returns bf16 bits (uint16[n]) of the sum of the k decoded tensors, and the unrounded
     float64 sum if want_sum."""
@@ -124,12 +147,13 @@ def decompress_sum(payloads, scales, n: int, block: int = 128, want_sum: bool = 
     sarr = (ctypes.c_void_p * k)(*[s.ctypes.data for s in ss])
     out = np.empty(n, dtype=np.uint16)
     acc = np.empty(n, dtype=np.float64) if want_sum else None
-    rc = lib().taco_ref_decompress_sum(parr, sarr, k, n, block, _ptr(out),
-                                       _ptr(acc) if want_sum else None)
+    rc = lib().taco_ref_decompress_sum_ex(parr, sarr, k, n, block, mode, fmt, _ptr(out),
+                                          _ptr(acc) if want_sum else None)
     if rc != 0:
         raise ValueError(f"taco_ref_decompress_sum(k={k}, n={n}, B={block}) -> {rc}")
     return (out, acc) if want_sum else out
 
 
-def decompress(payload, scales, n: int, block: int = 128, want_sum: bool = False):
-    return decompress_sum([payload], [scales], n, block, want_sum)
+def decompress(payload, scales, n: int, block: int = 128, want_sum: bool = False,
+               mode: int = MODE_FULL, fmt: int = FORMAT_E4M3):
+    return decompress_sum([payload], [scales], n, block, want_sum, mode, fmt)

@@ -50,6 +50,30 @@ __device__ __forceinline__ void fwht_wave(float (&v)[ButterflyShape<B>::kRegs], 
     }
 }
 
+// Ablation variants (the paper's component and format ablations): a stage switched off or another
+// code book.  mode bits: 1 adaptive rescaling, 2 Hadamard rotation, 4 post-rotation scale; formats:
+// 0 E4M3, 1 E5M2, 2 INT8 (round(x / Delta), Delta = max|x| / 127).  7 and 0 are the method itself.
+struct Variant {
+    int mode;
+    int format;
+    __device__ __forceinline__ bool rescale() const { return (mode & 1) != 0; }
+    __device__ __forceinline__ bool rotate() const { return (mode & 2) != 0; }
+    __device__ __forceinline__ bool postscale() const { return (mode & 4) != 0; }
+    __device__ __forceinline__ float qmax() const { return format == 0 ? 448.0f : format == 1 ? 57344.0f : 127.0f; }
+};
+
+__device__ __forceinline__ uint8_t encode_value(float q, const Variant& var) {
+    if (var.format == 0) return static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_fp8_f32(q, q, 0, false) & 0xFF);
+    if (var.format == 1) return static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_bf8_f32(q, q, 0, false) & 0xFF);
+    return static_cast<uint8_t>(static_cast<int8_t>(static_cast<int>(__builtin_rintf(q))));
+}
+
+__device__ __forceinline__ float decode_value(uint8_t code, const Variant& var) {
+    if (var.format == 0) return __builtin_amdgcn_cvt_f32_fp8(code, 0);
+    if (var.format == 1) return __builtin_amdgcn_cvt_f32_bf8(code, 0);
+    return static_cast<float>(static_cast<int8_t>(code));
+}
+
 // Byte offset of block blk's codes in the payload buffer: blocks are B bytes apart in the split
 // layout and B + 8 bytes apart (codes, then {alpha, s}) in the interleaved one.
 template <int B>
@@ -62,30 +86,41 @@ __device__ __forceinline__ int64_t code_offset(int64_t blk, bool interleaved) {
 template <int B>
 __device__ __forceinline__ void compress_block_butterfly(float (&v)[ButterflyShape<B>::kRegs], int lane, int64_t blk,
                                                          float tau, float eps, uint8_t* __restrict__ payload,
-                                                         float2* __restrict__ scales, bool interleaved) {
+                                                         float2* __restrict__ scales, bool interleaved, Variant var) {
     constexpr int R = ButterflyShape<B>::kRegs;
-    const float inv_root_b = 1.0f / __builtin_sqrtf(static_cast<float>(B));
-    float energy = 0.0f;
+    float alpha = 1.0f;
+    if (var.rescale()) {
+        float energy = 0.0f;
 #pragma unroll
-    for (int r = 0; r < R; ++r) energy = __builtin_fmaf(v[r], v[r], energy);
-    energy = wave_allreduce_sum(energy);                 // sum_j G_kj^2
-    fwht_wave<B>(v, lane);                               // W = H G_k (unnormalised)
+        for (int r = 0; r < R; ++r) energy = __builtin_fmaf(v[r], v[r], energy);
+        energy = wave_allreduce_sum(energy);                          // sum_j G_kj^2
+        alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / B) + eps);   // Eq. ash_sigma, Eq. ash_alpha
+    }
+    float norm = 1.0f;
+    if (var.rotate()) {
+        fwht_wave<B>(v, lane);                                        // W = H G_k (unnormalised)
+        norm = 1.0f / __builtin_sqrtf(static_cast<float>(B));
+    }
     float wmax = 0.0f;
 #pragma unroll
     for (int r = 0; r < R; ++r) wmax = fmaxf(wmax, __builtin_fabsf(v[r]));
     wmax = wave_allreduce_max(wmax);
-    // Eq. ash_sigma, Eq. ash_alpha; Z = alpha W / sqrt(B); Eq. post_scale.
-    const float alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / B) + eps);
-    const float zmax = wmax * alpha * inv_root_b;
-    const float s = zmax * (1.0f / kQmax);
-    // Z / s = Q_max W / max|W| in exact arithmetic; zero blocks map to zero codes.
-    const float to_code = wmax > 0.0f ? kQmax * __builtin_amdgcn_rcpf(wmax) : 0.0f;
+    const float qmax = var.qmax();
+    // Z = alpha W / sqrt(B); with the post-rotation scale, s = max|Z| / Q_max (Eq. post_scale) and
+    // Z / s = Q_max W / max|W| in exact arithmetic (zero blocks map to zero codes); without it s = 1
+    // and Z itself is converted, saturating at +-Q_max.
+    float s = 1.0f, to_code = alpha * norm;
+    if (var.postscale()) {
+        s = (wmax * alpha * norm) * (1.0f / qmax);
+        to_code = wmax > 0.0f ? qmax * __builtin_amdgcn_rcpf(wmax) : 0.0f;
+    }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int e = lane + 64 * r;
         if (e < B) {
-            const float q = v[r] * to_code;
-            payload[code_offset<B>(blk, interleaved) + e] = static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_fp8_f32(q, q, 0, false) & 0xFF);
+            float q = v[r] * to_code;
+            if (!var.postscale() || var.format == 2) q = __builtin_amdgcn_fmed3f(q, -qmax, qmax);
+            payload[code_offset<B>(blk, interleaved) + e] = encode_value(q, var);
         }
     }
     if (lane == 0) {
@@ -98,7 +133,7 @@ __device__ __forceinline__ void compress_block_butterfly(float (&v)[ButterflySha
 template <int B>
 __global__ __launch_bounds__(64) void compress_butterfly_kernel(
     const uint16_t* __restrict__ x, int64_t n, int64_t first_block, int64_t n_blocks, float tau,
-    float eps, uint8_t* __restrict__ payload, float2* __restrict__ scales, bool interleaved) {
+    float eps, uint8_t* __restrict__ payload, float2* __restrict__ scales, bool interleaved, Variant var) {
     constexpr int R = ButterflyShape<B>::kRegs;
     const int lane = threadIdx.x;
     for (int64_t blk = first_block + blockIdx.x; blk < first_block + n_blocks; blk += gridDim.x) {
@@ -109,7 +144,7 @@ __global__ __launch_bounds__(64) void compress_butterfly_kernel(
             const int64_t idx = blk * B + e;
             v[r] = (e < B && idx < n) ? bf16_bits_to_f32(x[idx]) : 0.0f;   // zero padding
         }
-        compress_block_butterfly<B>(v, lane, blk, tau, eps, payload, scales, interleaved);
+        compress_block_butterfly<B>(v, lane, blk, tau, eps, payload, scales, interleaved, var);
     }
 }
 
@@ -125,9 +160,10 @@ struct PayloadTable {
 // afterwards.
 template <int B>
 __device__ __forceinline__ void decode_sum_block_butterfly(const PayloadTable& tab, int k, int64_t blk, int lane,
-                                                           float (&v)[ButterflyShape<B>::kRegs], bool interleaved) {
+                                                           float (&v)[ButterflyShape<B>::kRegs], bool interleaved,
+                                                           Variant var) {
     constexpr int R = ButterflyShape<B>::kRegs;
-    const float inv_root_b = 1.0f / __builtin_sqrtf(static_cast<float>(B));
+    const float inv_root_b = var.rotate() ? 1.0f / __builtin_sqrtf(static_cast<float>(B)) : 1.0f;
 #pragma unroll
     for (int r = 0; r < R; ++r) v[r] = 0.0f;
     float single = 1.0f;
@@ -142,12 +178,12 @@ __device__ __forceinline__ void decode_sum_block_butterfly(const PayloadTable& t
         for (int r = 0; r < R; ++r) {
             const int e = lane + 64 * r;
             if (e < B) {
-                const float q = __builtin_amdgcn_cvt_f32_fp8(codes[e], 0);
+                const float q = decode_value(codes[e], var);
                 v[r] = __builtin_fmaf(q, w, v[r]);
             }
         }
     }
-    fwht_wave<B>(v, lane);
+    if (var.rotate()) fwht_wave<B>(v, lane);
     const float post = (k == 1) ? single : 1.0f;
 #pragma unroll
     for (int r = 0; r < R; ++r) v[r] *= post;
@@ -156,12 +192,12 @@ __device__ __forceinline__ void decode_sum_block_butterfly(const PayloadTable& t
 template <int B>
 __global__ __launch_bounds__(64) void decompress_sum_butterfly_kernel(
     PayloadTable tab, int k, int64_t n, int64_t first_block, int64_t n_blocks,
-    uint16_t* __restrict__ out, bool interleaved) {
+    uint16_t* __restrict__ out, bool interleaved, Variant var) {
     constexpr int R = ButterflyShape<B>::kRegs;
     const int lane = threadIdx.x;
     for (int64_t blk = first_block + blockIdx.x; blk < first_block + n_blocks; blk += gridDim.x) {
         float v[R];
-        decode_sum_block_butterfly<B>(tab, k, blk, lane, v, interleaved);
+        decode_sum_block_butterfly<B>(tab, k, blk, lane, v, interleaved, var);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int e = lane + 64 * r;
@@ -176,19 +212,19 @@ __global__ __launch_bounds__(64) void decompress_sum_butterfly_kernel(
 template <int B>
 __global__ __launch_bounds__(64) void decompress_sum_compress_butterfly_kernel(
     PayloadTable tab, int k, int64_t n, int64_t first_block, int64_t n_blocks, float tau, float eps,
-    uint8_t* __restrict__ payload_out, float2* __restrict__ scales_out, bool interleaved) {
+    uint8_t* __restrict__ payload_out, float2* __restrict__ scales_out, bool interleaved, Variant var) {
     constexpr int R = ButterflyShape<B>::kRegs;
     const int lane = threadIdx.x;
     for (int64_t blk = first_block + blockIdx.x; blk < first_block + n_blocks; blk += gridDim.x) {
         float v[R];
-        decode_sum_block_butterfly<B>(tab, k, blk, lane, v, interleaved);
+        decode_sum_block_butterfly<B>(tab, k, blk, lane, v, interleaved, var);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int e = lane + 64 * r;
             const int64_t idx = blk * B + e;
             v[r] = (e < B && idx < n) ? bf16_bits_to_f32(pack_bf16x2(v[r], 0.0f) & 0xFFFF) : 0.0f;
         }
-        compress_block_butterfly<B>(v, lane, blk, tau, eps, payload_out, scales_out, interleaved);
+        compress_block_butterfly<B>(v, lane, blk, tau, eps, payload_out, scales_out, interleaved, var);
     }
 }
 

@@ -43,14 +43,21 @@ int check_common(int64_t rows, int64_t cols, const taco_params* p, int64_t* n_ou
     if (rows <= 0 || cols <= 0) return TACO_ERR_SHAPE;
     if (rows > kMaxElems || cols > kMaxElems || rows > kMaxElems / cols) return TACO_ERR_SHAPE;
     if (!block_ok(p->block)) return TACO_ERR_BLOCK;
-    if (p->format != TACO_FORMAT_E4M3) return TACO_ERR_FORMAT;
+    if (p->format != TACO_FORMAT_E4M3 && p->format != TACO_FORMAT_E5M2 && p->format != TACO_FORMAT_INT8) return TACO_ERR_FORMAT;
+    if (p->mode < 0 || p->mode > TACO_MODE_FULL) return TACO_ERR_MODE;
     if (p->impl != TACO_IMPL_AUTO && p->impl != TACO_IMPL_BUTTERFLY && p->impl != TACO_IMPL_MFMA) return TACO_ERR_IMPL;
     if (p->layout != TACO_LAYOUT_SPLIT && p->layout != TACO_LAYOUT_INTERLEAVED) return TACO_ERR_LAYOUT;
+    // The matrix-core kernels implement the method itself; the ablation variants run on the butterfly kernels.
+    if (p->impl == TACO_IMPL_MFMA && !(p->mode == TACO_MODE_FULL && p->format == TACO_FORMAT_E4M3)) return TACO_ERR_IMPL;
     *n_out = rows * cols;
     return TACO_OK;
 }
 
-bool use_mfma(const taco_params* p) { return p->impl != TACO_IMPL_BUTTERFLY; }
+bool use_mfma(const taco_params* p) {
+    return p->impl != TACO_IMPL_BUTTERFLY && p->mode == TACO_MODE_FULL && p->format == TACO_FORMAT_E4M3;
+}
+
+taco::Variant variant_of(const taco_params* p) { return taco::Variant{p->mode, p->format}; }
 
 // Persistent grids: enough single-wave workgroups to fill every SIMD several times over.
 int grid_for(int64_t work_items, int waves_per_cu) {
@@ -145,10 +152,10 @@ int launch_decode(const taco::PayloadTable& tab, int k, int64_t n, const taco_pa
             if (recompress)
                 hipLaunchKernelGGL(taco::decompress_sum_compress_butterfly_kernel<kB>, dim3(grid_for(rest, 32)), dim3(64), 0, st,
                                    tab, k, n, first_block, rest, tau, eps, static_cast<uint8_t*>(payload_out),
-                                   static_cast<float2*>(scales_out), il);
+                                   static_cast<float2*>(scales_out), il, variant_of(p));
             else
                 hipLaunchKernelGGL(taco::decompress_sum_butterfly_kernel<kB>, dim3(grid_for(rest, 32)), dim3(64), 0, st,
-                                   tab, k, n, first_block, rest, static_cast<uint16_t*>(out_bf16), il);
+                                   tab, k, n, first_block, rest, static_cast<uint16_t*>(out_bf16), il, variant_of(p));
         });
         if (rc) return rc;
         if (int rc2 = launch_status()) return rc2;
@@ -168,6 +175,7 @@ void taco_default_params(taco_params* p) {
     p->format = TACO_FORMAT_E4M3;
     p->impl = TACO_IMPL_AUTO;
     p->layout = TACO_LAYOUT_SPLIT;
+    p->mode = TACO_MODE_FULL;
 }
 
 size_t taco_payload_bytes(int64_t n, int32_t block) {
@@ -224,7 +232,7 @@ int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_par
             constexpr int kB = decltype(bc)::value;
             hipLaunchKernelGGL(taco::compress_butterfly_kernel<kB>, dim3(grid_for(rest, 32)), dim3(64), 0, st,
                                static_cast<const uint16_t*>(x_bf16), n, first_block, rest, tau, eps,
-                               static_cast<uint8_t*>(payload), static_cast<float2*>(scales), il);
+                               static_cast<uint8_t*>(payload), static_cast<float2*>(scales), il, variant_of(p));
         });
         if (rc) return rc;
         if (int rc2 = launch_status()) return rc2;
@@ -301,11 +309,12 @@ const char* taco_strerror(int status) {
         case TACO_ERR_BLOCK: return "bad block size: must be 32, 64, 128, 256 or 512";
         case TACO_ERR_ALIGN: return "data pointer is not 16-byte aligned";
         case TACO_ERR_K: return "k must be between 1 and 16";
-        case TACO_ERR_FORMAT: return "unsupported format: only FP8 E4M3";
+        case TACO_ERR_FORMAT: return "bad format: must be E4M3, E5M2 or INT8";
         case TACO_ERR_LAUNCH: return "kernel launch failed";
-        case TACO_ERR_IMPL: return "bad kernel selection";
+        case TACO_ERR_IMPL: return "bad kernel selection (the matrix-core kernels run the full method in E4M3 only)";
         case TACO_ERR_PARAM: return "bad parameter: tau must be positive and eps non-negative, both finite";
         case TACO_ERR_LAYOUT: return "bad layout: must be split or interleaved";
+        case TACO_ERR_MODE: return "bad mode: must be a combination of the three TACO_MODE_* bits";
         default: return "unknown status";
     }
 }

@@ -17,7 +17,8 @@ import torch
 from . import build as _build
 
 TACO_MAX_K = 16
-TACO_FORMAT_E4M3 = 0
+TACO_FORMAT_E4M3, TACO_FORMAT_E5M2, TACO_FORMAT_INT8 = 0, 1, 2
+TACO_MODE_RESCALE, TACO_MODE_ROTATE, TACO_MODE_POSTSCALE, TACO_MODE_FULL = 1, 2, 4, 7
 TACO_IMPL_AUTO, TACO_IMPL_BUTTERFLY, TACO_IMPL_MFMA = 0, 1, 2
 TACO_LAYOUT_SPLIT, TACO_LAYOUT_INTERLEAVED = 0, 1
 
@@ -28,7 +29,8 @@ EXPORTS = ("taco_default_params", "taco_payload_bytes", "taco_scales_bytes", "ta
 
 class taco_params(ctypes.Structure):
     _fields_ = [("block", ctypes.c_int32), ("tau", ctypes.c_float), ("eps", ctypes.c_float),
-                ("format", ctypes.c_int32), ("impl", ctypes.c_int32), ("layout", ctypes.c_int32)]
+                ("format", ctypes.c_int32), ("impl", ctypes.c_int32), ("layout", ctypes.c_int32),
+                ("mode", ctypes.c_int32)]
 
 
 class TacoError(RuntimeError):
@@ -91,10 +93,11 @@ def taco_version() -> str:
 
 
 def taco_default_params(block: int = 128, tau: float = 1.0, eps: float = 1e-12,
-                        impl: int = TACO_IMPL_AUTO, layout: int = TACO_LAYOUT_SPLIT) -> taco_params:
+                        impl: int = TACO_IMPL_AUTO, layout: int = TACO_LAYOUT_SPLIT,
+                        mode: int = TACO_MODE_FULL, fmt: int = TACO_FORMAT_E4M3) -> taco_params:
     p = taco_params()
     lib().taco_default_params(ctypes.byref(p))
-    p.block, p.tau, p.eps, p.impl, p.layout = block, tau, eps, impl, layout
+    p.block, p.tau, p.eps, p.impl, p.layout, p.mode, p.format = block, tau, eps, impl, layout, mode, fmt
     return p
 
 

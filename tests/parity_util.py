@@ -22,12 +22,20 @@ import numpy as np
 CODE_MATCH_MIN = 0.9999
 SCALE_RTOL = 1e-6
 RECON_RTOL = 1e-3
+# Variants without the rotation quantise ratios of bf16 numbers, 448 g / max|g|: a large share of them sits
+# EXACTLY on a rounding tie, which the last bit of the fp32 reciprocal (GPU) or of the stored fp32 scale
+# (oracle) then breaks either way.  Both are one code apart; the identical share is lower.
+CODE_MATCH_MIN_UNROTATED = 0.99
 RECON_EXACT_MIN = 0.995
 RECON_EXACT_MIN_SUM = 0.99
 RECON_EXACT_MIN_RANDOM = 0.90
 
 
-def code_rank(codes: np.ndarray) -> np.ndarray:
+def code_rank(codes: np.ndarray, fmt: int = 0) -> np.ndarray:
+    """Position of a code on its format's value axis: sign-magnitude order for the two FP8 formats
+    (0 = E4M3, 1 = E5M2), the integer itself for INT8 (2)."""
+    if fmt == 2:
+        return codes.view(np.int8).astype(np.int32)
     c = codes.astype(np.int32)
     mag = c & 0x7F
     return np.where(c & 0x80, -mag, mag)
@@ -52,18 +60,22 @@ def check_scales(gpu: np.ndarray, ref: np.ndarray, what: str = ""):
     return True
 
 
-def check_codes(gpu: np.ndarray, ref: np.ndarray, ref_scales: np.ndarray, block: int, what: str = ""):
+def check_codes(gpu: np.ndarray, ref: np.ndarray, ref_scales: np.ndarray, block: int, what: str = "", fmt: int = 0,
+                min_match: float = CODE_MATCH_MIN):
     gpu = gpu.reshape(-1, block)
     ref = ref.reshape(-1, block)
     assert gpu.shape == ref.shape, (gpu.shape, ref.shape)
-    assert not np.any((gpu & 0x7F) == 0x7F), f"{what}: NaN code produced"
-    dist = np.abs(code_rank(gpu) - code_rank(ref))
+    if fmt == 0:
+        assert not np.any((gpu & 0x7F) == 0x7F), f"{what}: NaN code produced"
+    elif fmt == 1:
+        assert not np.any((gpu & 0x7F) >= 0x7C), f"{what}: infinity or NaN code produced"
+    dist = np.abs(code_rank(gpu, fmt) - code_rank(ref, fmt))
     zero_blocks = ref_scales.reshape(-1, 2)[:, 1] == 0.0
-    assert np.all((gpu[zero_blocks] & 0x7F) == 0), f"{what}: non-zero code in an all-zero block"
+    assert np.all(code_rank(gpu[zero_blocks], fmt) == 0), f"{what}: non-zero code in an all-zero block"
     match = float((dist == 0).mean())
     assert dist.max() <= 1, f"{what}: a code is {dist.max()} steps from the oracle's"
     # A sample of fewer than 10^4 codes cannot resolve 99.99 %: there a single off-by-one code is let through.
-    allowed = max(1, int((1.0 - CODE_MATCH_MIN) * dist.size))
+    allowed = max(1, int((1.0 - min_match) * dist.size))
     assert int((dist != 0).sum()) <= allowed, f"{what}: only {match:.6f} of codes identical"
     return match
 

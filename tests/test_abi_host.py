@@ -29,14 +29,14 @@ def test_library_exports_every_declared_symbol():
 def test_version_and_strerror():
     assert re.fullmatch(r"\d+\.\d+", taco.taco_version())
     assert taco.taco_strerror(0) == "ok"
-    for st in range(-10, 0):
+    for st in range(-11, 0):
         assert taco.taco_strerror(st) not in ("ok", "unknown status")
     assert taco.taco_strerror(-100) == "unknown status"
 
 
 def test_default_params():
     p = taco.taco_default_params()
-    assert (p.block, p.format, p.impl, p.layout) == (128, 0, 0, 0)
+    assert (p.block, p.format, p.impl, p.layout, p.mode) == (128, 0, 0, 0, 7)
     assert p.tau == 1.0 and abs(p.eps - 1e-12) < 1e-18
 
 
@@ -63,7 +63,9 @@ A = 0x1000  # a fake, 16-byte aligned, non-null "device pointer": never derefere
     (dict(rows=0), -2), (dict(cols=-4), -2), (dict(rows=1 << 30, cols=1 << 30), -2),
     (dict(p=_params(block=96)), -3), (dict(p=_params(block=1024)), -3),
     (dict(x=A + 2), -4), (dict(payload=A + 8), -4), (dict(scales=A + 4), -4),
-    (dict(p=_params(format=1)), -6),
+    (dict(p=_params(format=3)), -6), (dict(p=_params(format=-1)), -6),
+    (dict(p=_params(mode=8)), -11), (dict(p=_params(mode=-1)), -11),
+    (dict(p=_params(impl=2, mode=6)), -8), (dict(p=_params(impl=2, format=1)), -8),
     (dict(p=_params(impl=7)), -8), (dict(p=_params(impl=-1)), -8),
     (dict(p=_params(layout=2)), -10), (dict(p=_params(layout=-1)), -10),
     (dict(p=_params(tau=0.0)), -9), (dict(p=_params(eps=-1.0)), -9), (dict(p=_params(tau=float("nan"))), -9),
