@@ -7,7 +7,7 @@ on the `large_k8` workload (bf16 [16384, 12288], k = 8 payloads, block 128): the
 single-GPU configuration, and the one whose buffers (3 GiB of inputs) cannot sit in the
 256 MB last-level cache.  Inputs are resident in HBM before the timed region.
 
-Prints ONE JSON line (see the design doc for every field).  `value` counts bf16-equivalent
+Prints ONE JSON line.  `value` counts bf16-equivalent
 bytes: 2N per compressed tensor, 2N per decompressed tensor, k*2N for decompress_sum
 (k tensors decoded); `value_out_basis` counts only bf16 bytes that really cross HBM.
 The roofline object prices the dominant kernel (compress) by its ALGORITHMIC bytes
@@ -70,8 +70,8 @@ def cpu_baseline(w, block, rows):
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (the operator is block-local; see DESIGN.md on sharding); "
-              "run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (the operator is block-local, so it shards on any block "
+              "boundary without an exchange, and nothing here uses a second device); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
@@ -191,7 +191,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16->fp8_e4m3 (fp32 arithmetic)",
+        "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: bf16 [{w.tokens}, {w.hidden}] x {k} payloads, block {B}, "
                                f"step = {k} compress + 1 decompress + 1 decompress_sum(k={k})",

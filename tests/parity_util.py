@@ -50,6 +50,7 @@ def check_scales(gpu: np.ndarray, ref: np.ndarray, what: str = ""):
     ref = ref.reshape(-1, 2).astype(np.float64)
     assert gpu.shape == ref.shape, (gpu.shape, ref.shape)
     assert np.all(np.isfinite(gpu)), f"{what}: non-finite scale"
+    worst_of = []
     for col, name in ((0, "alpha"), (1, "s")):
         g, r = gpu[:, col], ref[:, col]
         zero = r == 0.0
@@ -57,7 +58,8 @@ def check_scales(gpu: np.ndarray, ref: np.ndarray, what: str = ""):
         rel = np.abs(g[~zero] - r[~zero]) / np.abs(r[~zero])
         worst = rel.max() if rel.size else 0.0
         assert worst <= SCALE_RTOL, f"{what}: {name} relative error {worst:.3e} > {SCALE_RTOL}"
-    return True
+        worst_of.append(worst)
+    return tuple(worst_of)
 
 
 def check_codes(gpu: np.ndarray, ref: np.ndarray, ref_scales: np.ndarray, block: int, what: str = "", fmt: int = 0,

@@ -68,9 +68,10 @@ def test_full_size_workload(oracle, name, B):
         rp, rs = oracle.compress(x_s, block=B)
         gp = gather_tiles(pl.cpu().numpy(), tiles, TILE)
         gs = gather_tiles(sc.cpu().numpy().reshape(-1), tiles, 2 * per_tile).reshape(-1, 2)
-        P.check_scales(gs, rs, f"{name}/B{B}[{i}]")
+        worst_alpha, worst_s = P.check_scales(gs, rs, f"{name}/B{B}[{i}]")
         match = P.check_codes(gp, rp, rs, B, f"{name}/B{B}[{i}]")
-        print(f"[{name}/B{B}] payload {i}: compress parity ok, {match:.6f} of sampled codes identical", flush=True)
+        print(f"[{name}/B{B}] payload {i}: compress parity ok, {match:.6f} of sampled codes identical, "
+              f"worst relative error alpha {worst_alpha:.2e}, s {worst_s:.2e}", flush=True)
         # --- patch the oracle's payload into the sampled tiles for the decode test
         idx_c = torch.from_numpy((tiles[:, None] * TILE + np.arange(TILE)[None, :]).reshape(-1)).to(DEV)
         idx_s = torch.from_numpy((tiles[:, None] * per_tile + np.arange(per_tile)[None, :]).reshape(-1)).to(DEV)
