@@ -8,15 +8,16 @@ and by the smoke check).  Tolerances:
                       is zero the sign bit is unspecified.
   reconstruction      per element |gpu - ref| <= max(one bf16 ulp of ref, 1e-3 * max|ref| of
                       its block); max|gpu - ref| / max|ref| over the tensor at most one bf16 ulp
-                      (2^-8); and a minimum share of bit-identical elements: 99.5 % for one
+                      of the largest element (between 2^-8 and 2^-7 of it); and a minimum share of
+                      bit-identical elements: 99.5 % for one
                       decoded payload, 99 % for sums of k payloads (k fp32 additions, with
                       cancellation), 90 % for synthetic random codes (18 binades inside a block).
 
 The code rule follows from the arithmetic: the kernels compute Z/s in fp32 (relative error a
 few 2^-24) while the oracle works in double, so only values within ~1e-7 relative of a
 rounding boundary (spacing 2^-4 relative) can land on the neighbouring code: ~1e-5 of the
-elements at most.  The reconstruction rule allows the one legal bf16 rounding flip (2^-8
-relative to the element) that the same fp32-vs-double difference can cause."""
+elements at most.  The reconstruction rule allows the one legal bf16 rounding flip (one ulp,
+2^-8 to 2^-7 of the element) that the same fp32-vs-double difference can cause."""
 import numpy as np
 
 CODE_MATCH_MIN = 0.9999
@@ -99,8 +100,9 @@ def check_recon(gpu_bits: np.ndarray, ref_bits: np.ndarray, block: int, what: st
     err = np.abs(g - r)
     bad = err > tol
     assert not bad.any(), f"{what}: {int(bad.sum())} elements off by more than one bf16 ulp / 1e-3 of block max"
+    # one ulp is 2^(e-7) for an element in [2^e, 2^(e+1)): up to 2^-7 of it at the low end of a binade
     overall = err.max() / max(np.abs(r).max(), 1e-300)
-    assert overall <= 2.0 ** -8, f"{what}: max error {overall:.3e} of the tensor's max"
+    assert overall <= 2.0 ** -7, f"{what}: max error {overall:.3e} of the tensor's max"
     exact = float((err == 0).mean())
     assert exact >= min_exact, f"{what}: only {exact:.6f} of outputs identical"
     return exact
