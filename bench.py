@@ -29,8 +29,8 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
 # WRITE_SIZE runs, scaled by a copy kernel of known size); None until measured.  The summary
 # the number comes from is committed under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    # fetch 393267 KiB + write 208896 KiB per compress launch: profiles/mfma_kernels_large_k8.txt
-    ("large_k8", 128, "auto"): 616615206,
+    # fetch 393250 KiB + write 208896 KiB per compress launch: profiles/mfma_kernels_large_k8.txt
+    ("large_k8", 128, "auto"): 616597093,
 }
 
 
@@ -204,7 +204,7 @@ def main():
                   "decompress": call(t_dec, bytes_dec, 2.0 * n),
                   f"decompress_sum_k{k}": call(t_sum, bytes_sum, k * 2.0 * n),
                   f"decompress_sum_compress_k{k} (not in the step)": call(t_fused, (k + 1) * per_elem * n, k * 2.0 * n)},
-        "roofline": {"kernel": (f"compress_mfma_kernel<{max(B // 128, 1)},{max(128 // B, 1)},{2 if n // 2048 >= 65536 else 1},"
+        "roofline": {"kernel": (f"compress_mfma_kernel<{max(B // 128, 1)},{max(128 // B, 1)},1,"
                                 f"{'true' if args.layout == 'interleaved' else 'false'}>") if args.impl != "butterfly"
                      else f"compress_butterfly_kernel<{B}>",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -96,4 +96,15 @@ __device__ __forceinline__ float wave_allreduce_max(float v) {
     return v;
 }
 
+// Orders one wave's LDS accesses: what its lanes wrote before is visible to what they read after.
+// LDS instructions of a wave execute in issue order, so no instruction is needed: the fences only
+// stop the compiler from moving LDS accesses across this point.  Every wave of the matrix-core
+// kernels works in an LDS region of its own, so no workgroup barrier is ever needed (and waves of
+// one workgroup may run different numbers of loop iterations).
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 }  // namespace taco

@@ -241,7 +241,7 @@ struct CompressLane {
         u32x4 a[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) a[c] = *reinterpret_cast<const u32x4*>(&lds[rd_base + 4 * c]);
-        __syncthreads();
+        wave_lds_sync();
 
         // V = X H_128 (unnormalised rotation of Eq. ash_rotation, per unit) and the Gram diagonal
         // sum_j x_j^2 of every unit (Eq. ash_sigma), all on the matrix cores.
@@ -331,7 +331,7 @@ struct CompressLane {
         TACO_STORE_ROW(3)
 #undef TACO_STORE_ROW
         if (kInterleaved) {
-            __syncthreads();
+            wave_lds_sync();
             const u32x4* chunks = reinterpret_cast<const u32x4*>(lds);
             u32x4* dst = reinterpret_cast<u32x4*>(payload) + tile * Layout::kTileChunks;
             const int lane = 16 * g + n16;
@@ -340,7 +340,7 @@ struct CompressLane {
                 const int chunk = 64 * c + lane;
                 if (chunk < Layout::kTileChunks) store_stream<true>(&dst[chunk], chunks[chunk]);
             }
-            __syncthreads();
+            wave_lds_sync();
         }
     }
 };
@@ -380,7 +380,7 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
 #pragma unroll
             for (int c = 0; c < 4; ++c) lds[wr_base + cp * 528 + 4 * c] = stage[p][cp][c];
         }
-        __syncthreads();
+        wave_lds_sync();
         cl.template tile_from_lds<kInterleaved>(lds, tile, tau, eps, payload, scales);
     }
 }
@@ -391,8 +391,9 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
 
 // out = bf16( sum_i  H_B (codes_i) * s_i / (alpha_i sqrt(B)) ), fp32 accumulation, i ascending.
 // payloads, scales: see PayloadLayout; out: n_tiles * 2048 bf16.
-// Workgroup w (one wave) handles output tiles [w * tiles_per_wave, (w+1) * tiles_per_wave) and
-// exits.  Its work is the flattened list of (tile, payload) items, payload fastest; a ring of
+// Wave v = blockIdx.x * kWaves + wave-in-workgroup handles output tiles
+// [v * tiles_per_wave, (v+1) * tiles_per_wave) and exits; the waves of a workgroup share nothing
+// (each has its own LDS region, there is no workgroup barrier).  A wave's work is the flattened list of (tile, payload) items, payload fastest; a ring of
 // kRing items is kept in flight in registers.  For blocks of several units the per-payload work
 // is the 128-point product of every unit times the block factor; the butterfly across units is
 // linear, so it runs once on the accumulated sums.
@@ -401,8 +402,8 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
 // bf16-rounded sum (the receive side of the reduce-scatter feeding the send side of the
 // all-gather, Section 4.4.2): the finished tile goes to LDS in the compress stage's layout
 // instead of HBM, and `out` is unused.
-template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress>
-__global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
+template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kWaves = 1>
+__global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
     PayloadTable tab, int k, int64_t n_tiles, int tiles_per_wave, u32x4* __restrict__ out,
     float tau, float eps, u32x2* __restrict__ payload_out, f32x2* __restrict__ scales_out) {
     static_assert((kRB == 1 || kRB == 2 || kRB == 4) && (kSub == 1 || kSub == 2 || kSub == 4) && (kRB == 1 || kSub == 1),
@@ -412,9 +413,14 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
     using Layout = PayloadLayout<kBlock, kInterleaved>;
     constexpr int kLoads = kInterleaved ? 3 : 2;                 // 16-byte loads per lane and item
     constexpr int kExtraChunks = Layout::kTileChunks - 128;      // interleaved: chunks left for the third load
-    __shared__ u32x4 lds[Layout::kTileChunks];   // one tile of the payload: split layout swizzled, interleaved as it is
-    __shared__ uint32_t lds_c[kRecompress ? kCompressLdsDwords : 1];   // the bf16 tile for the compress stage
-    const int lane = threadIdx.x;
+    // Per wave: one tile of the payload (split layout swizzled, interleaved as it is) and, for the
+    // recompress form, the bf16 tile for the compress stage.
+    __shared__ u32x4 lds_all[kWaves][Layout::kTileChunks];
+    __shared__ uint32_t lds_c_all[kWaves][kRecompress ? kCompressLdsDwords : 1];
+    const int wave = kWaves == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    u32x4* lds = lds_all[wave];
+    uint32_t* lds_c = lds_c_all[wave];
+    const int lane = threadIdx.x & 63;
     const int g = lane >> 4;
     const int n16 = lane & 15;
     // Block whose factor this lane computes: the one that contains this lane's outputs of row
@@ -423,9 +429,10 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
     const int my_block = kSub == 1 ? unit_of_row<kRB>(4 * g + (n16 & 3)) / kRB
                                    : unit_of_row<kRB>(4 * g + (n16 & 3)) * kSub + ph;
 
-    const int64_t tile_begin = static_cast<int64_t>(blockIdx.x) * tiles_per_wave;
+    const int64_t tile_begin = (static_cast<int64_t>(blockIdx.x) * kWaves + wave) * tiles_per_wave;
     int64_t tile_end = tile_begin + tiles_per_wave;
     if (tile_end > n_tiles) tile_end = n_tiles;
+    if (tile_end <= tile_begin) return;      // a wave past the end (last workgroup only)
     const int n_items = static_cast<int>(tile_end - tile_begin) * k;
 
     // Ring fill.  (pf_tile, pf_i) walks the item list ahead of the consumer.
@@ -516,7 +523,7 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
             lds[wr_slot[1]] = stage[p][1];
             if (kInterleaved && lane < kExtraChunks) lds[128 + lane] = stage[p][kLoads - 1];
             f32x2 sc = stage_sc[p];
-            __syncthreads();
+            wave_lds_sync();
             u32x4 a0, a1;
             if (kInterleaved) {
                 const unsigned char* bytes = reinterpret_cast<const unsigned char*>(lds);
@@ -530,7 +537,7 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
                 a0 = lds[rd_slot[0]];
                 a1 = lds[rd_slot[1]];
             }
-            __syncthreads();
+            wave_lds_sync();
             if (q + kRing < n_items) fetch(p);      // refill this ring slot
             i32x8 av;
             av[0] = a0.x; av[1] = a0.y; av[2] = a0.z; av[3] = a0.w;
@@ -585,7 +592,7 @@ __global__ __launch_bounds__(64) void decompress_sum_mfma_kernel(
                     }
                 }
                 if (kRecompress) {
-                    __syncthreads();
+                    wave_lds_sync();
                     cl.template tile_from_lds<kInterleaved>(lds_c, tile, tau, eps, payload_out, scales_out);
                 }
                 i = 0;

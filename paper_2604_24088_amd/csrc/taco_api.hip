@@ -124,19 +124,28 @@ int launch_decode(const taco::PayloadTable& tab, int k, int64_t n, const taco_pa
     if (use_mfma(p)) {
         const int64_t n_tiles = n / taco::kTileElems;
         if (n_tiles > 0) {
-            // Two output tiles per wave and a ring of four (tile, payload) items in flight: measured
-            // best on MI355X for k = 1 and k = 8 (1..16 tiles, rings of 2..8 tried).
-            const int tiles_per_wave = 2;
-            const unsigned waves = static_cast<unsigned>((n_tiles + tiles_per_wave - 1) / tiles_per_wave);
+            // Launch shape, measured on MI355X (1..16 tiles per wave, rings of 2..8 items, 1..8 waves
+            // per workgroup tried, all block sizes and both layouts): a ring of four (tile, payload)
+            // items in flight; up to five payloads, and for the recompress form, two output tiles per
+            // wave and one wave per workgroup; from six payloads on, one tile per wave and two waves
+            // per workgroup (3-10 % faster at k = 8..16, 5-10 % slower at k <= 4).
+            const bool wide = !recompress && k >= 6;
+            const int tiles_per_wave = wide ? 1 : 2;
+            const int64_t tiles_per_group = 2;      // either 1 wave x 2 tiles or 2 waves x 1 tile
+            const unsigned groups = static_cast<unsigned>((n_tiles + tiles_per_group - 1) / tiles_per_group);
             dispatch_shape(B, il, [&](auto rb, auto sub, auto layout) {
                 constexpr int kRB = decltype(rb)::value, kSub = decltype(sub)::value;
                 constexpr bool kIl = decltype(layout)::value;
                 if (recompress)
-                    hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, true>), dim3(waves), dim3(64), 0, st,
+                    hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, true, 1>), dim3(groups), dim3(64), 0, st,
                                        tab, k, n_tiles, tiles_per_wave, static_cast<taco::u32x4*>(nullptr), p->tau, p->eps,
                                        static_cast<taco::u32x2*>(payload_out), static_cast<taco::f32x2*>(scales_out));
+                else if (wide)
+                    hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 2>), dim3(groups), dim3(128), 0, st,
+                                       tab, k, n_tiles, tiles_per_wave, static_cast<taco::u32x4*>(out_bf16), 0.0f, 0.0f,
+                                       static_cast<taco::u32x2*>(nullptr), static_cast<taco::f32x2*>(nullptr));
                 else
-                    hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false>), dim3(waves), dim3(64), 0, st,
+                    hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 1>), dim3(groups), dim3(64), 0, st,
                                        tab, k, n_tiles, tiles_per_wave, static_cast<taco::u32x4*>(out_bf16), 0.0f, 0.0f,
                                        static_cast<taco::u32x2*>(nullptr), static_cast<taco::f32x2*>(nullptr));
             });
@@ -204,22 +213,17 @@ int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_par
     if (use_mfma(p)) {
         const int64_t n_tiles = n / taco::kTileElems;
         if (n_tiles > 0) {
-            // Tiles per wave, measured on MI355X: 2 wins on the largest tensors (98 k tiles), 1 below
-            // (finer tail, more waves to fill 256 compute units); 4 loses everywhere.
-            const bool two = n_tiles >= 65536;
-            const unsigned waves = static_cast<unsigned>(two ? (n_tiles + 1) / 2 : n_tiles);
+            // One tile per wave, one wave per workgroup: measured best on MI355X at every block size
+            // and in both layouts (2 tiles per wave cost 4-5 % on the largest tensors, 4 more).
+            const unsigned waves = static_cast<unsigned>(n_tiles);
             const auto* xin = static_cast<const taco::u32x4*>(x_bf16);
             auto* pout = static_cast<taco::u32x2*>(payload);
             auto* sout = static_cast<taco::f32x2*>(scales);
             dispatch_shape(B, il, [&](auto rb, auto sub, auto layout) {
                 constexpr int kRB = decltype(rb)::value, kSub = decltype(sub)::value;
                 constexpr bool kIl = decltype(layout)::value;
-                if (two)
-                    hipLaunchKernelGGL((taco::compress_mfma_kernel<kRB, kSub, 2, kIl>), dim3(waves), dim3(64), 0, st,
-                                       xin, n_tiles, p->tau, p->eps, pout, sout);
-                else
-                    hipLaunchKernelGGL((taco::compress_mfma_kernel<kRB, kSub, 1, kIl>), dim3(waves), dim3(64), 0, st,
-                                       xin, n_tiles, p->tau, p->eps, pout, sout);
+                hipLaunchKernelGGL((taco::compress_mfma_kernel<kRB, kSub, 1, kIl>), dim3(waves), dim3(64), 0, st,
+                                   xin, n_tiles, p->tau, p->eps, pout, sout);
             });
             if (int rc = launch_status()) return rc;
         }
