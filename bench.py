@@ -10,6 +10,8 @@ single-GPU configuration, and the one whose buffers (3 GiB of inputs) cannot sit
 Prints ONE JSON line.  `value` counts bf16-equivalent
 bytes: 2N per compressed tensor, 2N per decompressed tensor, k*2N for decompress_sum
 (k tensors decoded); `value_out_basis` counts only bf16 bytes that really cross HBM.
+`mix_yardstick` times memory-only kernels (taco_debug_traffic) that move exactly the bytes of a
+compress and of a decompress_sum call and compute nothing: what the memory system gives that mix.
 The roofline object prices the dominant kernel (compress) by its ALGORITHMIC bytes
 (3.0625 B per element at block 128) over its average launch duration, measured with
 HIP events on the launch stream inside the timed region.
@@ -147,6 +149,32 @@ def main():
     copy_gbps = 2.0 * src.numel() * 10 / (cev[0].elapsed_time(cev[1]) * 1e6)
     del dst
 
+    # ---- yardsticks outside the timed region: memory-only kernels with the traffic of compress (reads one
+    # bf16 tensor, writes one payload) and of decompress_sum (reads k payloads, writes one bf16 tensor)
+    chunks = (2048 + 8 * (2048 // B)) // 16           # 16-byte words of one tile's payload
+    n_tiles = n // 2048
+    ybuf = torch.empty(n_tiles * chunks * 16, dtype=torch.uint8, device=dev)
+
+    def yardstick(fn, alg_bytes):
+        yev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        for _ in range(3):
+            fn(0)
+        yev[0].record(stream)
+        for r in range(16):
+            fn(r)
+        yev[1].record(stream)
+        torch.cuda.synchronize()
+        ms = yev[0].elapsed_time(yev[1]) / 16
+        return {"ms": round(ms, 4), "moved_GBps": round(alg_bytes / ms / 1e6, 1),
+                "hbm_frac": round(alg_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+
+    per_elem_y = 1.0 + 8.0 / B
+    mix = {"compress": yardstick(lambda r: taco.taco_debug_traffic([xs[r % k]], 256, ybuf, chunks, n_tiles, stream),
+                                 (2.0 + per_elem_y) * n_tiles * 2048),
+           f"decompress_sum_k{k}": yardstick(lambda r: taco.taco_debug_traffic(xs, chunks, out1, 256, n_tiles, stream),
+                                             (k * per_elem_y + 2.0) * n_tiles * 2048)}
+    del ybuf
+
     # ---- outside the timed region: the fused decompress_sum -> compress call (reduce-scatter receive
     # side feeding the all-gather send side) on the same payloads
     fev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
@@ -200,6 +228,7 @@ def main():
         "moved_GBps": round(moved / (ms_step * 1e6), 1),
         "hbm_frac_step": round(moved / (ms_step * 1e6) / HBM_PEAK_GBPS, 4),
         "copy_yardstick_GBps": round(copy_gbps, 1),
+        "mix_yardstick": mix,
         "calls": {"compress": call(t_comp, bytes_comp, 2.0 * n),
                   "decompress": call(t_dec, bytes_dec, 2.0 * n),
                   f"decompress_sum_k{k}": call(t_sum, bytes_sum, k * 2.0 * n),

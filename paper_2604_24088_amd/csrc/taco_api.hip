@@ -305,6 +305,30 @@ int taco_debug_copy(const void* src, void* dst, int64_t bytes, void* stream) {
     return launch_status();
 }
 
+int taco_debug_traffic(const void* const* srcs, int32_t k, int32_t src_chunks, void* dst,
+                       int32_t dst_chunks, int64_t n_tiles, void* stream) {
+    if (!srcs || !dst) return TACO_ERR_NULL;
+    if (k < 1 || k > TACO_MAX_K) return TACO_ERR_K;
+    if (src_chunks < 1 || src_chunks > 256 || dst_chunks < 1 || dst_chunks > 256) return TACO_ERR_SHAPE;
+    if (n_tiles < 1 || n_tiles > kMaxElems / taco::kTileElems) return TACO_ERR_SHAPE;
+    taco::PayloadTable tab{};
+    for (int i = 0; i < k; ++i) {
+        if (!srcs[i]) return TACO_ERR_NULL;
+        if (!aligned16(srcs[i])) return TACO_ERR_ALIGN;
+        tab.payload[i] = srcs[i];
+    }
+    if (!aligned16(dst)) return TACO_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // The launch shapes of the kernels it stands in for: two waves per workgroup from six sources on.
+    if (k >= 6)
+        hipLaunchKernelGGL(taco::traffic_kernel<2>, dim3(static_cast<unsigned>((n_tiles + 1) / 2)), dim3(128), 0, st,
+                           tab, k, src_chunks, static_cast<taco::u32x4*>(dst), dst_chunks, n_tiles);
+    else
+        hipLaunchKernelGGL(taco::traffic_kernel<1>, dim3(static_cast<unsigned>(n_tiles)), dim3(64), 0, st,
+                           tab, k, src_chunks, static_cast<taco::u32x4*>(dst), dst_chunks, n_tiles);
+    return launch_status();
+}
+
 const char* taco_strerror(int status) {
     switch (status) {
         case TACO_OK: return "ok";

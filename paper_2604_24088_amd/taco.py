@@ -23,7 +23,7 @@ TACO_IMPL_AUTO, TACO_IMPL_BUTTERFLY, TACO_IMPL_MFMA = 0, 1, 2
 TACO_LAYOUT_SPLIT, TACO_LAYOUT_INTERLEAVED = 0, 1
 
 EXPORTS = ("taco_default_params", "taco_payload_bytes", "taco_scales_bytes", "taco_compress",
-           "taco_decompress", "taco_decompress_sum", "taco_decompress_sum_compress", "taco_debug_cvt_e4m3", "taco_debug_copy", "taco_strerror",
+           "taco_decompress", "taco_decompress_sum", "taco_decompress_sum_compress", "taco_debug_cvt_e4m3", "taco_debug_copy", "taco_debug_traffic", "taco_strerror",
            "taco_version")
 
 
@@ -76,6 +76,9 @@ def lib() -> ctypes.CDLL:
         L.taco_debug_cvt_e4m3.argtypes = [c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p]
         L.taco_debug_copy.restype = c.c_int
         L.taco_debug_copy.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p]
+        L.taco_debug_traffic.restype = c.c_int
+        L.taco_debug_traffic.argtypes = [c.POINTER(c.c_void_p), c.c_int32, c.c_int32, c.c_void_p, c.c_int32,
+                                         c.c_int64, c.c_void_p]
         L.taco_strerror.restype = c.c_char_p
         L.taco_strerror.argtypes = [c.c_int]
         L.taco_version.restype = c.c_char_p
@@ -235,4 +238,18 @@ def taco_debug_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> torch.
     assert src.is_cuda and dst.is_cuda and nbytes == dst.numel() * dst.element_size()
     st = lib().taco_debug_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_handle(stream))
     _check(st, "taco_debug_copy")
+    return dst
+
+
+def taco_debug_traffic(srcs: Sequence[torch.Tensor], src_chunks: int, dst: torch.Tensor, dst_chunks: int,
+                       n_tiles: int, stream=None) -> torch.Tensor:
+    """Memory-only stand-in for the operator: per tile reads src_chunks 16-byte words from every source and
+    writes dst_chunks words to dst (bandwidth yardstick for that mix of reads and writes)."""
+    k = len(srcs)
+    for t in srcs:
+        assert t.is_cuda and t.numel() * t.element_size() >= n_tiles * src_chunks * 16
+    assert dst.is_cuda and dst.numel() * dst.element_size() >= n_tiles * dst_chunks * 16
+    st = lib().taco_debug_traffic(_pointer_array(srcs, k), k, src_chunks, dst.data_ptr(), dst_chunks, n_tiles,
+                                  _stream_handle(stream))
+    _check(st, "taco_debug_traffic")
     return dst

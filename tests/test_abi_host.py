@@ -112,6 +112,24 @@ def test_fused_rejects_bad_arguments():
     assert L.taco_decompress_sum_compress(arr, arr, 2, 4, 512, ctypes.byref(bad), A, A, None) == -9
 
 
+def test_debug_traffic_rejects_bad_arguments():
+    L = taco.lib()
+    arr = (ctypes.c_void_p * 2)(A, A)
+    assert L.taco_debug_traffic(None, 1, 256, A, 136, 4, None) == -1
+    assert L.taco_debug_traffic(arr, 1, 256, 0, 136, 4, None) == -1
+    assert L.taco_debug_traffic(arr, 0, 256, A, 136, 4, None) == -5
+    assert L.taco_debug_traffic(arr, 17, 256, A, 136, 4, None) == -5
+    assert L.taco_debug_traffic(arr, 1, 0, A, 136, 4, None) == -2
+    assert L.taco_debug_traffic(arr, 1, 257, A, 136, 4, None) == -2
+    assert L.taco_debug_traffic(arr, 1, 256, A, 300, 4, None) == -2
+    assert L.taco_debug_traffic(arr, 1, 256, A, 136, 0, None) == -2
+    assert L.taco_debug_traffic(arr, 2, 256, A + 8, 136, 4, None) == -4
+    bad = (ctypes.c_void_p * 2)(A, A + 4)
+    assert L.taco_debug_traffic(bad, 2, 256, A, 136, 4, None) == -4
+    null = (ctypes.c_void_p * 2)(A, 0)
+    assert L.taco_debug_traffic(null, 2, 256, A, 136, 4, None) == -1
+
+
 def test_decompress_rejects_bad_arguments():
     L = taco.lib()
     p = _params()

@@ -439,3 +439,35 @@ def test_interleaved_layout(oracle, block, impl, n):
     torch.cuda.synchronize()
     fp3, fs3 = P.deinterleave(fbuf.cpu().numpy(), block)
     assert np.array_equal(fp3, sp3.cpu().numpy()) and np.array_equal(fs3, ss3.cpu().numpy())
+
+
+# ---- diagnostic entry points: data movement only, checked bit for bit ------------------------------
+
+def test_debug_copy_is_a_copy():
+    rng = np.random.default_rng(5)
+    src = torch.from_numpy(rng.integers(0, 256, size=(1 << 20) + 48, dtype=np.uint8)).to(DEV)
+    dst = torch.zeros_like(src)
+    taco.taco_debug_copy(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+
+
+@pytest.mark.parametrize("k,src_chunks,dst_chunks,n_tiles", [(1, 256, 136, 37), (8, 136, 256, 37), (2, 40, 40, 5),
+                                                             (16, 136, 256, 3), (5, 256, 256, 11), (6, 64, 200, 9)])
+def test_debug_traffic_writes_the_xor_of_what_it_reads(k, src_chunks, dst_chunks, n_tiles):
+    """Written word 64 c + lane of a tile is a fixed XOR of the loaded words 64 c' + lane of all sources
+    (loaded word = 0 past src_chunks): acc0 = v0^v2, acc1 = v1^v3, acc2 = v1^v2^v3, acc3 = v0^v2^v3."""
+    rng = np.random.default_rng(100 * k + src_chunks)
+    srcs = [rng.integers(0, 2 ** 32, size=(n_tiles, src_chunks, 4), dtype=np.uint32) for _ in range(k)]
+    dst = torch.full((n_tiles * dst_chunks * 4 + 4,), 0x5A5A5A5A, dtype=torch.int64, device=DEV).to(torch.int32)
+    taco.taco_debug_traffic([torch.from_numpy(s.view(np.int32)).to(DEV) for s in srcs], src_chunks, dst, dst_chunks, n_tiles)
+    torch.cuda.synchronize()
+    v = np.zeros((n_tiles, 256, 4), dtype=np.uint32)
+    for s in srcs:
+        v[:, :src_chunks] ^= s
+    v = v.reshape(n_tiles, 4, 64, 4)
+    acc = np.stack([v[:, 0] ^ v[:, 2], v[:, 1] ^ v[:, 3], v[:, 1] ^ v[:, 2] ^ v[:, 3], v[:, 0] ^ v[:, 2] ^ v[:, 3]], axis=1)
+    want = acc.reshape(n_tiles, 256, 4)[:, :dst_chunks].reshape(-1)
+    got = dst.cpu().numpy().view(np.uint32)
+    assert np.array_equal(got[:want.size], want)
+    assert np.all(got[want.size:] == 0x5A5A5A5A)      # nothing written past the last tile
