@@ -45,6 +45,13 @@ def parse():
     ap.add_argument("--block", type=int, default=128)
     ap.add_argument("--impl", default="auto", choices=["auto", "butterfly", "mfma"])
     ap.add_argument("--layout", default="split", choices=["split", "interleaved"])
+    ap.add_argument("--chunk-mb", type=float, default=0.0,
+                    help="issue every call in row chunks of about this many MB of bf16 (0 = whole tensor): the overlap "
+                         "granularity of Section 4.4.2")
+    ap.add_argument("--streams", type=int, default=1, help="streams the chunks are dealt to in turn (with --chunk-mb)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the three parts of the step into HIP graphs and time their replays (takes the "
+                         "host's launch cost out of chunked runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gen-threads", type=int, default=16)
     return ap.parse_args()
@@ -111,17 +118,72 @@ def main():
     outk = torch.empty((w.tokens, w.hidden), dtype=torch.bfloat16, device=dev)
     stream = torch.cuda.current_stream()
 
-    def step(ev=None):
-        if ev:
-            ev[0].record(stream)
+    # Row chunks (whole rows, so every chunk is a whole number of blocks and tiles when hidden is a multiple of
+    # 2048) dealt to `--streams` streams in turn; each call joins them back into `stream`.
+    rows_per_chunk = w.tokens
+    if args.chunk_mb > 0:
+        rows_per_chunk = max(1, min(w.tokens, int(args.chunk_mb * (1 << 20)) // (2 * w.hidden)))
+        assert (rows_per_chunk * w.hidden) % 2048 == 0, "chunks must be whole tiles"
+    bounds = [(r, min(r + rows_per_chunk, w.tokens)) for r in range(0, w.tokens, rows_per_chunk)]
+    side = [torch.cuda.Stream() for _ in range(args.streams)] if args.chunk_mb > 0 and args.streams > 1 else []
+    rec = (B + 8) if args.layout == "interleaved" else B       # payload bytes per block
+
+    def rows_of(t, r0, r1, per_row):
+        return None if t is None else t[r0 * per_row:r1 * per_row]
+
+    def chunked(fn):
+        """fn(r0, r1, stream) for every chunk; whole-tensor calls go straight to `stream`."""
+        if len(bounds) == 1:
+            fn(0, w.tokens, stream)
+            return
+        for s_ in side:
+            s_.wait_stream(stream)
+        for c, (r0, r1) in enumerate(bounds):
+            fn(r0, r1, side[c % len(side)] if side else stream)
+        for s_ in side:
+            stream.wait_stream(s_)
+
+    bpr = w.hidden // B                                          # blocks per row
+
+    def compress_rows(i):
+        return lambda r0, r1, st: taco.taco_compress(xs[i][r0:r1], params, rows_of(payloads[i], r0, r1, bpr * rec),
+                                                     rows_of(scales[i], r0, r1, bpr), st)
+
+    def decode_rows(srcs_p, srcs_s, out):
+        return lambda r0, r1, st: taco.taco_decompress_sum([rows_of(t, r0, r1, bpr * rec) for t in srcs_p],
+                                                           [rows_of(t, r0, r1, bpr) for t in srcs_s],
+                                                           out[r0:r1].shape, params, out[r0:r1], st)
+
+    def part_compress():
         for i in range(k):
-            taco.taco_compress(xs[i], params, payloads[i], scales[i], stream)
-        if ev:
-            ev[1].record(stream)
-        taco.taco_decompress(payloads[0], scales[0], out1.shape, params, out1, stream)
-        if ev:
-            ev[2].record(stream)
-        taco.taco_decompress_sum(payloads, scales, outk.shape, params, outk, stream)
+            chunked(compress_rows(i))
+
+    def part_decompress():
+        chunked(decode_rows(payloads[:1], scales[:1], out1))
+
+    def part_sum():
+        chunked(decode_rows(payloads, scales, outk))
+
+    parts = [part_compress, part_decompress, part_sum]
+    if args.graph:
+        for part in parts:
+            part()                      # first launches (module load) outside the capture
+        torch.cuda.synchronize()
+        graphs = []
+        for part in parts:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                stream = torch.cuda.current_stream()        # the capturing stream: chunked() forks from and joins it
+                part()
+            graphs.append(g)
+        stream = torch.cuda.current_stream()
+        parts = [g.replay for g in graphs]
+
+    def step(ev=None):
+        for j, part in enumerate(parts):
+            if ev:
+                ev[j].record(stream)
+            part()
         if ev:
             ev[3].record(stream)
 
@@ -223,7 +285,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: bf16 [{w.tokens}, {w.hidden}] x {k} payloads, block {B}, "
                                f"step = {k} compress + 1 decompress + 1 decompress_sum(k={k})",
-                   "impl": args.impl, "block": B, "layout": args.layout},
+                   "impl": args.impl, "block": B, "layout": args.layout,
+                   "chunk_rows": rows_per_chunk if len(bounds) > 1 else None, "chunks_per_call": len(bounds),
+                   "streams": max(len(side), 1), "hip_graph": bool(args.graph)},
         "value_out_basis": round(real_bf16 / (ms_step * 1e6), 1),
         "moved_GBps": round(moved / (ms_step * 1e6), 1),
         "hbm_frac_step": round(moved / (ms_step * 1e6) / HBM_PEAK_GBPS, 4),
