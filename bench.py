@@ -10,6 +10,9 @@ single-GPU configuration, and the one whose buffers (3 GiB of inputs) cannot sit
 Prints ONE JSON line.  `value` counts bf16-equivalent
 bytes: 2N per compressed tensor, 2N per decompressed tensor, k*2N for decompress_sum
 (k tensors decoded); `value_out_basis` counts only bf16 bytes that really cross HBM.
+`calls` times each call inside the step (HIP events between the calls); `calls_back_to_back` times
+16 launches of one call in a row, which is what a kernel costs when the host's launch time (about 8 us
+per call through this binding) is not in the way: on the smaller workloads the two differ.
 `mix_yardstick` times memory-only kernels (taco_debug_traffic) that move exactly the bytes of a
 compress and of a decompress_sum call and compute nothing: what the memory system gives that mix.
 The roofline object prices the dominant kernel (compress) by its ALGORITHMIC bytes
@@ -49,6 +52,9 @@ def parse():
                     help="issue every call in row chunks of about this many MB of bf16 (0 = whole tensor): the overlap "
                          "granularity of Section 4.4.2")
     ap.add_argument("--streams", type=int, default=1, help="streams the chunks are dealt to in turn (with --chunk-mb)")
+    ap.add_argument("--rotate", type=int, default=0,
+                    help="buffer sets the steps rotate through (0 = as many as it takes, up to 64, for the sets to exceed "
+                         "1 GiB together, so that workloads smaller than the 256 MB last-level cache are still timed from HBM)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the three parts of the step into HIP graphs and time their replays (takes the "
                          "host's launch cost out of chunked runs)")
@@ -116,6 +122,16 @@ def main():
         scales = [torch.empty((taco.taco_scales_bytes(n, B) // 8, 2), dtype=torch.float32, device=dev) for _ in range(k)]
     out1 = torch.empty((w.tokens, w.hidden), dtype=torch.bfloat16, device=dev)
     outk = torch.empty((w.tokens, w.hidden), dtype=torch.bfloat16, device=dev)
+    # Buffer sets: copies of everything a step touches; step j works on set j mod R.
+    set_bytes = sum(t.numel() * t.element_size() for t in xs + payloads + [t for t in scales if t is not None] + [out1, outk])
+    n_sets = args.rotate if args.rotate > 0 else max(1, min(64, -(-(1 << 30) // set_bytes)))
+    if args.graph:
+        n_sets = 1                      # a captured graph replays on the buffers it was captured with
+    sets = [(xs, payloads, scales, out1, outk)]
+    for _ in range(n_sets - 1):
+        sets.append(tuple([t.clone() if t is not None else None for t in group] if isinstance(group, list) else group.clone()
+                          for group in sets[0]))
+    step_no = 0
     stream = torch.cuda.current_stream()
 
     # Row chunks (whole rows, so every chunk is a whole number of blocks and tiles when hidden is a multiple of
@@ -180,6 +196,9 @@ def main():
         parts = [g.replay for g in graphs]
 
     def step(ev=None):
+        nonlocal xs, payloads, scales, out1, outk, step_no
+        xs, payloads, scales, out1, outk = sets[step_no % n_sets]
+        step_no += 1
         for j, part in enumerate(parts):
             if ev:
                 ev[j].record(stream)
@@ -215,27 +234,35 @@ def main():
     # bf16 tensor, writes one payload) and of decompress_sum (reads k payloads, writes one bf16 tensor)
     chunks = (2048 + 8 * (2048 // B)) // 16           # 16-byte words of one tile's payload
     n_tiles = n // 2048
-    ybuf = torch.empty(n_tiles * chunks * 16, dtype=torch.uint8, device=dev)
+    per_elem_y = 1.0 + 8.0 / B
 
-    def yardstick(fn, alg_bytes):
+    def back_to_back(fn, alg_bytes):
+        """16 launches in a row (after 3 untimed), launch r on buffer set r mod R: no events or other kernels between."""
         yev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        for _ in range(3):
-            fn(0)
+        for r in range(3):
+            fn(r, sets[r % n_sets])
         yev[0].record(stream)
         for r in range(16):
-            fn(r)
+            fn(r, sets[r % n_sets])
         yev[1].record(stream)
         torch.cuda.synchronize()
         ms = yev[0].elapsed_time(yev[1]) / 16
         return {"ms": round(ms, 4), "moved_GBps": round(alg_bytes / ms / 1e6, 1),
                 "hbm_frac": round(alg_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4)}
 
-    per_elem_y = 1.0 + 8.0 / B
-    mix = {"compress": yardstick(lambda r: taco.taco_debug_traffic([xs[r % k]], 256, ybuf, chunks, n_tiles, stream),
-                                 (2.0 + per_elem_y) * n_tiles * 2048),
-           f"decompress_sum_k{k}": yardstick(lambda r: taco.taco_debug_traffic(xs, chunks, out1, 256, n_tiles, stream),
-                                             (k * per_elem_y + 2.0) * n_tiles * 2048)}
-    del ybuf
+    mix, b2b = {}, {}
+    if n_tiles > 0:
+        # set layout: (xs, payloads, scales, out1, outk); the bf16 buffers serve as sources and sinks of the right sizes
+        mix = {"compress": back_to_back(lambda r, S: taco.taco_debug_traffic([S[0][r % k]], 256, S[4], chunks, n_tiles, stream),
+                                        (2.0 + per_elem_y) * n_tiles * 2048),
+               f"decompress_sum_k{k}": back_to_back(lambda r, S: taco.taco_debug_traffic(S[0], chunks, S[3], 256, n_tiles, stream),
+                                                    (k * per_elem_y + 2.0) * n_tiles * 2048)}
+    b2b = {"compress": back_to_back(lambda r, S: taco.taco_compress(S[0][r % k], params, S[1][r % k], S[2][r % k], stream),
+                                    (2.0 + per_elem_y) * n),
+           "decompress": back_to_back(lambda r, S: taco.taco_decompress(S[1][0], S[2][0], S[3].shape, params, S[3], stream),
+                                      (2.0 + per_elem_y) * n),
+           f"decompress_sum_k{k}": back_to_back(lambda r, S: taco.taco_decompress_sum(S[1], S[2], S[4].shape, params, S[4], stream),
+                                                (k * per_elem_y + 2.0) * n)}
 
     # ---- outside the timed region: the fused decompress_sum -> compress call (reduce-scatter receive
     # side feeding the all-gather send side) on the same payloads
@@ -287,12 +314,14 @@ def main():
                                f"step = {k} compress + 1 decompress + 1 decompress_sum(k={k})",
                    "impl": args.impl, "block": B, "layout": args.layout,
                    "chunk_rows": rows_per_chunk if len(bounds) > 1 else None, "chunks_per_call": len(bounds),
-                   "streams": max(len(side), 1), "hip_graph": bool(args.graph)},
+                   "streams": max(len(side), 1), "hip_graph": bool(args.graph),
+                   "buffer_sets": n_sets},
         "value_out_basis": round(real_bf16 / (ms_step * 1e6), 1),
         "moved_GBps": round(moved / (ms_step * 1e6), 1),
         "hbm_frac_step": round(moved / (ms_step * 1e6) / HBM_PEAK_GBPS, 4),
         "copy_yardstick_GBps": round(copy_gbps, 1),
         "mix_yardstick": mix,
+        "calls_back_to_back": b2b,
         "calls": {"compress": call(t_comp, bytes_comp, 2.0 * n),
                   "decompress": call(t_dec, bytes_dec, 2.0 * n),
                   f"decompress_sum_k{k}": call(t_sum, bytes_sum, k * 2.0 * n),

@@ -538,12 +538,13 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
                 a1 = lds[rd_slot[1]];
             }
             wave_lds_sync();
+            // Eq. recon_dequant .. recon_rescale: factor s / (alpha sqrt(B)) for this lane's block.
+            // Taken before the refill below, so that the slot's old scalars are dead when it is issued.
+            const float factor = sc.y * __builtin_amdgcn_rcpf(sc.x) * inv_root_b;
             if (q + kRing < n_items) fetch(p);      // refill this ring slot
             i32x8 av;
             av[0] = a0.x; av[1] = a0.y; av[2] = a0.z; av[3] = a0.w;
             av[4] = a1.x; av[5] = a1.y; av[6] = a1.z; av[7] = a1.w;
-            // Eq. recon_dequant .. recon_rescale: factor s / (alpha sqrt(B)) for this lane's block.
-            const float factor = sc.y * __builtin_amdgcn_rcpf(sc.x) * inv_root_b;
             f32x4 d[8];
 #pragma unroll
             for (int nt = 0; nt < 8; ++nt) {
