@@ -63,8 +63,12 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(w, block, rows):
-    """The oracle, as it stands, on the first `rows` tokens of every payload, same call mix as a step."""
+def cpu_baseline(w, block, rows, gpu=None):
+    """The oracle, as it stands, on the first `rows` tokens of every payload, same call mix as a step.
+
+    With `gpu` = (payloads, scales, params, taco module) of the split layout and rows = all tokens, what the oracle
+    computed anyway is also compared with the GPU's results, over the whole benchmark tensors: every code and scale of
+    every payload, and decompress_sum of the ORACLE's payloads on the GPU against the oracle's own sum."""
     import numpy as np
     from oracle import taco_ref
     from paper_2604_24088_amd import workloads as W
@@ -73,13 +77,52 @@ def cpu_baseline(w, block, rows):
     t0 = time.perf_counter()
     enc = [taco_ref.compress(x, block=block) for x in xs]
     taco_ref.decompress(enc[0][0], enc[0][1], n, block=block)
-    taco_ref.decompress_sum([e[0] for e in enc], [e[1] for e in enc], n, block=block)
+    total = taco_ref.decompress_sum([e[0] for e in enc], [e[1] for e in enc], n, block=block)
     dt = time.perf_counter() - t0
     k = w.payloads
     bf16_bytes = (k + 1 + k) * 2 * n
-    return {"value": bf16_bytes / dt / 1e9, "unit": "GB/s", "cores": taco_ref.threads(), "kind": "oracle",
+    base = {"value": bf16_bytes / dt / 1e9, "unit": "GB/s", "cores": taco_ref.threads(), "kind": "oracle",
             "sample": f"first {rows} of {w.tokens} tokens of each of the {k} payloads, same call mix as one step "
                       f"({dt:.1f} s)"}
+    if gpu is None or rows != w.tokens:
+        return base, None
+    import torch
+    payloads, scales, params, taco = gpu
+
+    def rank(c):                       # E4M3 codes in sign-magnitude order, +0 and -0 merged
+        mag = (c & 0x7F).astype(np.int16)
+        return np.where(c & 0x80, -mag, mag)
+
+    off_one = off_more = 0
+    worst = [0.0, 0.0]
+    for i in range(k):
+        d = np.abs(rank(payloads[i].cpu().numpy()) - rank(enc[i][0]))
+        off_one += int((d == 1).sum())
+        off_more += int((d > 1).sum())
+        g, r = scales[i].cpu().numpy().astype(np.float64), enc[i][1].astype(np.float64)
+        for c in range(2):
+            nz = r[:, c] != 0
+            worst[c] = max(worst[c], float(np.max(np.abs(g[nz, c] - r[nz, c]) / np.abs(r[nz, c]))))
+    dev = payloads[0].device
+    out = taco.taco_decompress_sum([torch.from_numpy(e[0]).to(dev) for e in enc], [torch.from_numpy(e[1]).to(dev) for e in enc],
+                                   (rows, w.hidden), params)
+    torch.cuda.synchronize()
+    got = out.view(torch.int16).cpu().numpy().view(np.uint16).reshape(-1)
+    f = lambda b: (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    ref = f(total)
+    err = np.abs(f(got) - ref)
+    # the parity rule of the tests: per element at most max(one bf16 ulp of the oracle's value, 1e-3 of its block's maximum)
+    mag = np.abs(ref)
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(mag, 2.0 ** -126))) - 7)
+    block_max = np.repeat(mag.reshape(-1, block).max(axis=1), block)
+    worst_tol = float(np.max(err / np.maximum(ulp, 1e-3 * block_max + 1e-300)))
+    parity = {"scope": f"all {k} x {n} elements of the benchmark tensors, GPU against the CPU oracle",
+              "codes_identical": 1.0 - (off_one + off_more) / (k * n), "codes_one_step_apart": off_one,
+              "codes_further_apart": off_more, "alpha_max_rel_err": worst[0], "s_max_rel_err": worst[1],
+              f"decompress_sum_k{k}_outputs_identical": float((got == total).mean()),
+              f"decompress_sum_k{k}_max_err_over_tolerance": worst_tol,
+              "tolerance": "per element max(1 bf16 ulp of the oracle's value, 1e-3 of the block's max)"}
+    return base, parity
 
 
 def main():
@@ -335,7 +378,10 @@ def main():
                      "alg_bytes_per_launch": bytes_comp, "avg_launch_ms": round(t_comp, 4)},
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, B, rows=w.tokens)
+        gpu = (sets[0][1], sets[0][2], params, taco) if args.layout == "split" and impl != taco.TACO_IMPL_BUTTERFLY else None
+        result["cpu_baseline"], parity = cpu_baseline(w, B, rows=w.tokens, gpu=gpu)
+        if parity is not None:
+            result["parity_full_size"] = parity
     print(json.dumps(result))
 
 
