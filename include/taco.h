@@ -96,7 +96,8 @@ enum { TACO_LAYOUT_SPLIT = 0, TACO_LAYOUT_INTERLEAVED = 1 };
 typedef struct taco_params {
     int32_t block;  /* B: 32, 64, 128, 256 or 512                                  */
     float tau;      /* tau of Eq. ash_alpha, > 0 (the paper gives no value; 1.0f)  */
-    float eps;      /* eps of Eq. ash_sigma, >= 0 (the paper gives no value; 1e-12f) */
+    float eps;      /* eps of Eq. ash_sigma, >= 0 (the paper gives no value; 1e-12f).  With eps = 0 an
+                       all-zero block stores alpha = inf, s = 0 and still decodes to zeros */
     int32_t format; /* TACO_FORMAT_*                                               */
     int32_t impl;   /* TACO_IMPL_*                                                 */
     int32_t layout; /* TACO_LAYOUT_*                                               */

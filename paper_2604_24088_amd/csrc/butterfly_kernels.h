@@ -111,7 +111,7 @@ __device__ __forceinline__ void compress_block_butterfly(float (&v)[ButterflySha
     // and Z itself is converted, saturating at +-Q_max.
     float s = 1.0f, to_code = alpha * norm;
     if (var.postscale()) {
-        s = (wmax * alpha * norm) * (1.0f / qmax);
+        s = wmax > 0.0f ? (wmax * alpha * norm) * (1.0f / qmax) : 0.0f;   // all-zero block: s = 0 even if alpha is infinite (eps = 0)
         to_code = wmax > 0.0f ? qmax * __builtin_amdgcn_rcpf(wmax) : 0.0f;
     }
 #pragma unroll

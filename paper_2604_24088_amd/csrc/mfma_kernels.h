@@ -302,7 +302,8 @@ struct CompressLane {
         }
         if (owns_scales) {
             const float alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / kBlock) + eps);   // Eq. ash_sigma, ash_alpha
-            const float s = (wmax * alpha) * (inv_sqrt_block<kBlock>() / kQmax);               // max|Z| / Q_max
+            // max|Z| / Q_max; an all-zero block stores s = 0 whatever alpha is (with eps = 0 it is infinite)
+            const float s = wmax > 0.0f ? (wmax * alpha) * (inv_sqrt_block<kBlock>() / kQmax) : 0.0f;
             if (kInterleaved)
                 records[Layout::scale_word(0, my_block)] = __builtin_bit_cast(u32x2, f32x2{alpha, s});
             else

@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <type_traits>
@@ -19,23 +20,18 @@ constexpr int64_t kMaxElems = int64_t(1) << 40;
 bool block_ok(int32_t b) { return b == 32 || b == 64 || b == 128 || b == 256 || b == 512; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-struct DeviceInfo {
-    int cus = 0;
-};
-
-// Compute-unit count of the current device (queried once per process and device id).
+// Compute-unit count of the current device, queried once per device; safe to call from several
+// threads (the worst case is two threads asking the runtime the same question).
 int device_cus() {
-    static int cached_dev = -1;
-    static int cached_cus = 0;
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> cache[kMaxDevices];      // zero-initialised: 0 = not asked yet
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    if (dev != cached_dev) {
-        int v = 0;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
-        cached_cus = v;
-        cached_dev = dev;
-    }
-    return cached_cus;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+    int v = cache[dev].load(std::memory_order_relaxed);
+    if (v > 0) return v;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+    cache[dev].store(v, std::memory_order_relaxed);
+    return v;
 }
 
 int check_common(int64_t rows, int64_t cols, const taco_params* p, int64_t* n_out) {

@@ -471,3 +471,30 @@ def test_debug_traffic_writes_the_xor_of_what_it_reads(k, src_chunks, dst_chunks
     got = dst.cpu().numpy().view(np.uint32)
     assert np.array_equal(got[:want.size], want)
     assert np.all(got[want.size:] == 0x5A5A5A5A)      # nothing written past the last tile
+
+
+@pytest.mark.parametrize("impl", ["auto", "butterfly"])
+@pytest.mark.parametrize("block", [32, 128, 512])
+def test_eps_zero_with_all_zero_blocks(oracle, impl, block):
+    """eps = 0 makes alpha infinite on an all-zero block; s must still be 0 and the block must decode to zeros
+    (the oracle stores {inf, 0}), and the other blocks are untouched by their neighbours."""
+    x = sample_rows(W.WORKLOADS["gpt_rowpar"], rows=3).reshape(-1).copy()     # 6 tiles
+    nb = x.size // block
+    zero = np.arange(nb) % 3 == 1
+    x.reshape(nb, block)[zero] = 0
+    p = taco.taco_default_params(block=block, eps=0.0, impl=IMPLS[impl])
+    pl, sc = taco.taco_compress(to_dev(x), p)
+    out = taco.taco_decompress(pl, sc, (x.size,), p)
+    two = taco.taco_decompress_sum([pl, pl], [sc, sc], (x.size,), p)
+    torch.cuda.synchronize()
+    gp, gs = pl.cpu().numpy(), sc.cpu().numpy()
+    with np.errstate(all="ignore"):
+        rp, rs = oracle.compress(x, block=block, eps=0.0)
+    assert np.all(np.isinf(gs[zero, 0])) and np.all(gs[zero, 1] == 0.0) and np.all(np.isinf(rs[zero, 0]))
+    assert np.all((gp.reshape(nb, block)[zero] & 0x7F) == 0)
+    P.check_scales(gs[~zero], rs[~zero], "eps=0")
+    P.check_codes(gp.reshape(nb, block)[~zero], rp.reshape(nb, block)[~zero], rs[~zero], block, "eps=0", min_match=0.999)
+    for t in (out, two):
+        o = bits_of(t).reshape(nb, block)
+        assert np.all((o[zero] & 0x7FFF) == 0)
+        assert np.all(np.isfinite(P.bf16_to_f64(o.reshape(-1))))
