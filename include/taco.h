@@ -33,7 +33,9 @@
  *     metadata placement, Section 4.4.2, in structure-of-arrays form).
  *   - A block whose rotated maximum is zero stores s_k = 0 and zero codes (sign bits
  *     of the codes are unspecified) and decodes to zeros.
- *   - Non-finite inputs are outside the contract.
+ *   - Non-finite inputs are outside the contract, and so are blocks whose sum of squares
+ *     leaves the range of normal fp32 numbers (|x| up to about 2^60 and down to 2^-60 are
+ *     tested): the kernels work in fp32.
  *   - Return value: TACO_OK (0) or a negative taco_status.  Argument errors are found on
  *     the host before anything is launched.
  */

@@ -498,3 +498,25 @@ def test_eps_zero_with_all_zero_blocks(oracle, impl, block):
         o = bits_of(t).reshape(nb, block)
         assert np.all((o[zero] & 0x7FFF) == 0)
         assert np.all(np.isfinite(P.bf16_to_f64(o.reshape(-1))))
+
+
+@pytest.mark.parametrize("impl", ["auto", "butterfly"])
+@pytest.mark.parametrize("block", [64, 128, 256])
+@pytest.mark.parametrize("exp", [-60, -24, 30, 60])
+def test_extreme_magnitudes(oracle, impl, block, exp):
+    """Inputs scaled by 2^exp (exact in bf16): the block energy stays inside fp32's normal range (2^-120 .. 2^120),
+    eps = 1e-12 dominates sigma at the small end.  Same bar as everywhere else."""
+    x = sample_rows(W.WORKLOADS["qwen_act"], rows=2).reshape(-1)              # 5 tiles, heavy tails
+    xf = P.bf16_to_f64(x) * 2.0 ** exp
+    xs = W.float32_to_bf16_bits(xf.astype(np.float32))
+    assert np.array_equal(P.bf16_to_f64(xs), xf)                               # the scaling was exact
+    p = taco.taco_default_params(block=block, impl=IMPLS[impl])
+    pl, sc = taco.taco_compress(to_dev(xs), p)
+    torch.cuda.synchronize()
+    rp, rs = oracle.compress(xs, block=block)
+    P.check_scales(sc.cpu().numpy(), rs, f"2^{exp}")
+    P.check_codes(pl.cpu().numpy(), rp, rs, block, f"2^{exp}", min_match=0.999)
+    out = taco.taco_decompress(torch.from_numpy(rp).to(DEV), torch.from_numpy(rs).to(DEV), (xs.size,), p)
+    torch.cuda.synchronize()
+    P.check_recon(bits_of(out), oracle.decompress(rp, rs, xs.size, block=block), block, f"2^{exp} decompress",
+                  min_exact=0.99)
