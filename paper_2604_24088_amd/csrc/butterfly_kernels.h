@@ -1,13 +1,15 @@
-// Plain butterfly kernels: one 64-lane wavefront per block of B elements, any supported B
-// (32 .. 512), any n (ragged tails are bounds-checked).  They serve block sizes without a
-// matrix-core kernel and the tail of a tensor that does not fill a whole tile.
+// Plain butterfly kernels, any supported B (32 .. 512) and any n (ragged tails are bounds-checked).
+// They serve the part of a tensor that does not fill a whole tile of the matrix-core kernels, the
+// run-time selectable ablation variants, and impl = BUTTERFLY as a second, independent family.
 //
-// Element e of a block lives in lane (e & 63), register (e >> 6).  The fast Walsh-Hadamard
-// transform (Algorithm 1, sender and receiver sides) then splits into stages that
-// exchange values between lanes (strides 1 .. 32, a wave shuffle) and stages between
-// registers of one lane (strides 64 and up).  The in-place butterfly with stride h maps
-// (a, b) -> (a + b, a - b) for the pair whose indices differ in bit h; running all strides
-// gives y = H x with H[i][j] = (-1)^popcount(i & j), the natural ordering.
+// A wave works on a GROUP of 512 consecutive elements = 512 / B whole blocks: lane L holds the
+// eight elements 8 L .. 8 L + 7 of the group (one 16-byte load of bf16, one 8-byte load or store
+// of codes), so a block occupies B / 8 neighbouring lanes.  The fast Walsh-Hadamard transform
+// (Algorithm 1, sender and receiver sides) then splits into three stages between the registers of
+// a lane (strides 1, 2, 4) and log2(B / 8) stages that exchange values between lanes L and L ^ m.
+// The in-place butterfly with stride h maps (a, b) -> (a + b, a - b) for the pair whose indices
+// differ in bit h; running all strides gives y = H x with H[i][j] = (-1)^popcount(i & j), the
+// natural ordering.  Sums and maxima over a block are xor-shuffle reductions over the same lanes.
 //
 // The transform runs on the raw block (bf16 inputs, or decoded FP8 codes) so that most
 // partial sums are exact in fp32, and the block scalars are applied once afterwards
@@ -18,36 +20,63 @@
 
 namespace taco {
 
-template <int B>
-struct ButterflyShape {
-    static constexpr int kRegs = (B + 63) / 64;   // values per lane
-    static constexpr int kLanes = B < 64 ? B : 64;  // lanes that hold data
-};
+constexpr int kGroupElems = 512;     // elements per wave iteration of the butterfly kernels
 
-// y = H x over the wave; v[r] holds element lane + 64 r.  Lanes >= B (B = 32) carry zeros.
-template <int B>
-__device__ __forceinline__ void fwht_wave(float (&v)[ButterflyShape<B>::kRegs], int lane) {
-    constexpr int R = ButterflyShape<B>::kRegs;
+// Butterfly between lanes L and L ^ kMask (element stride 8 kMask); nothing when the block is narrower.
+template <int B, int kMask>
+__device__ __forceinline__ void cross_lane_stage(float (&v)[8], int lane) {
+    if (kMask < B / 8) {
+        const bool upper = (lane & kMask) != 0;
 #pragma unroll
-    for (int h = 1; h < 64 && h < B; h <<= 1) {
-        const bool upper = (lane & h) != 0;
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            float other = __shfl_xor(v[r], h, 64);
+        for (int r = 0; r < 8; ++r) {
+            const float other = lane_xor<kMask>(v[r]);
             v[r] = upper ? other - v[r] : v[r] + other;
         }
     }
+}
+
+// y = H_B x for every block of the group; v[r] holds element 8 lane + r.
+template <int B>
+__device__ __forceinline__ void fwht_group(float (&v)[8], int lane) {
 #pragma unroll
-    for (int hr = 1; hr < R; hr <<= 1) {
+    for (int h = 1; h < 8; h <<= 1) {
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            if ((r & hr) == 0) {
-                float a = v[r], b = v[r | hr];
+        for (int r = 0; r < 8; ++r) {
+            if ((r & h) == 0) {
+                const float a = v[r], b = v[r | h];
                 v[r] = a + b;
-                v[r | hr] = a - b;
+                v[r | h] = a - b;
             }
         }
     }
+    cross_lane_stage<B, 1>(v, lane);
+    cross_lane_stage<B, 2>(v, lane);
+    cross_lane_stage<B, 4>(v, lane);
+    cross_lane_stage<B, 8>(v, lane);
+    cross_lane_stage<B, 16>(v, lane);
+    cross_lane_stage<B, 32>(v, lane);
+}
+
+// Sum / maximum over the B / 8 lanes of the caller's block, returned in every one of them.
+template <int B>
+__device__ __forceinline__ float block_allreduce_sum(float v) {
+    if (1 < B / 8) v += lane_xor<1>(v);
+    if (2 < B / 8) v += lane_xor<2>(v);
+    if (4 < B / 8) v += lane_xor<4>(v);
+    if (8 < B / 8) v += lane_xor<8>(v);
+    if (16 < B / 8) v += lane_xor<16>(v);
+    if (32 < B / 8) v += lane_xor<32>(v);
+    return v;
+}
+template <int B>
+__device__ __forceinline__ float block_allreduce_max(float v) {
+    if (1 < B / 8) v = fmaxf(v, lane_xor<1>(v));
+    if (2 < B / 8) v = fmaxf(v, lane_xor<2>(v));
+    if (4 < B / 8) v = fmaxf(v, lane_xor<4>(v));
+    if (8 < B / 8) v = fmaxf(v, lane_xor<8>(v));
+    if (16 < B / 8) v = fmaxf(v, lane_xor<16>(v));
+    if (32 < B / 8) v = fmaxf(v, lane_xor<32>(v));
+    return v;
 }
 
 // Ablation variants (the paper's component and format ablations): a stage switched off or another
@@ -74,6 +103,28 @@ __device__ __forceinline__ float decode_value(uint8_t code, const Variant& var) 
     return static_cast<float>(static_cast<int8_t>(code));
 }
 
+// The eight codes of two dwords as floats, q[r] = value of byte r (the conversions select the byte themselves).
+__device__ __forceinline__ void decode8(u32x2 w, const Variant& var, float (&q)[8]) {
+    const int lo = static_cast<int>(w.x), hi = static_cast<int>(w.y);
+    if (var.format == 0) {
+        q[0] = __builtin_amdgcn_cvt_f32_fp8(lo, 0); q[1] = __builtin_amdgcn_cvt_f32_fp8(lo, 1);
+        q[2] = __builtin_amdgcn_cvt_f32_fp8(lo, 2); q[3] = __builtin_amdgcn_cvt_f32_fp8(lo, 3);
+        q[4] = __builtin_amdgcn_cvt_f32_fp8(hi, 0); q[5] = __builtin_amdgcn_cvt_f32_fp8(hi, 1);
+        q[6] = __builtin_amdgcn_cvt_f32_fp8(hi, 2); q[7] = __builtin_amdgcn_cvt_f32_fp8(hi, 3);
+    } else if (var.format == 1) {
+        q[0] = __builtin_amdgcn_cvt_f32_bf8(lo, 0); q[1] = __builtin_amdgcn_cvt_f32_bf8(lo, 1);
+        q[2] = __builtin_amdgcn_cvt_f32_bf8(lo, 2); q[3] = __builtin_amdgcn_cvt_f32_bf8(lo, 3);
+        q[4] = __builtin_amdgcn_cvt_f32_bf8(hi, 0); q[5] = __builtin_amdgcn_cvt_f32_bf8(hi, 1);
+        q[6] = __builtin_amdgcn_cvt_f32_bf8(hi, 2); q[7] = __builtin_amdgcn_cvt_f32_bf8(hi, 3);
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            q[r] = static_cast<float>(static_cast<int8_t>((w.x >> (8 * r)) & 0xFF));
+            q[4 + r] = static_cast<float>(static_cast<int8_t>((w.y >> (8 * r)) & 0xFF));
+        }
+    }
+}
+
 // Byte offset of block blk's codes in the payload buffer: blocks are B bytes apart in the split
 // layout and B + 8 bytes apart (codes, then {alpha, s}) in the interleaved one.
 template <int B>
@@ -81,30 +132,66 @@ __device__ __forceinline__ int64_t code_offset(int64_t blk, bool interleaved) {
     return blk * (interleaved ? B + 8 : B);
 }
 
-// Sender side of Algorithm 1 for one block whose elements are already in registers
-// (v[r] = element lane + 64 r, zeros past the end of the tensor).
+// Where a lane's eight elements sit: global block index and offset inside the block.
 template <int B>
-__device__ __forceinline__ void compress_block_butterfly(float (&v)[ButterflyShape<B>::kRegs], int lane, int64_t blk,
+struct LaneSlot {
+    int64_t blk;
+    int pos;
+    __device__ __forceinline__ LaneSlot(int64_t group, int lane)
+        : blk(group * (kGroupElems / B) + lane / (B / 8)), pos(8 * (lane % (B / 8))) {}
+};
+
+// Eight codes of one lane as two dwords, byte r = code of q[r].
+__device__ __forceinline__ u32x2 encode8(const float (&q)[8], const Variant& var) {
+    u32x2 w;
+    if (var.format == 0) {
+        w.x = pack_e4m3x4(q[0], q[1], q[2], q[3]);
+        w.y = pack_e4m3x4(q[4], q[5], q[6], q[7]);
+    } else if (var.format == 1) {
+        int lo = __builtin_amdgcn_cvt_pk_bf8_f32(q[0], q[1], 0, false);
+        lo = __builtin_amdgcn_cvt_pk_bf8_f32(q[2], q[3], lo, true);
+        int hi = __builtin_amdgcn_cvt_pk_bf8_f32(q[4], q[5], 0, false);
+        hi = __builtin_amdgcn_cvt_pk_bf8_f32(q[6], q[7], hi, true);
+        w.x = static_cast<uint32_t>(lo);
+        w.y = static_cast<uint32_t>(hi);
+    } else {
+        uint32_t lo = 0, hi = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            lo |= static_cast<uint32_t>(encode_value(q[r], var)) << (8 * r);
+            hi |= static_cast<uint32_t>(encode_value(q[4 + r], var)) << (8 * r);
+        }
+        w.x = lo;
+        w.y = hi;
+    }
+    return w;
+}
+
+// Sender side of Algorithm 1 for the group whose elements are already in registers
+// (v[r] = element 8 lane + r of the group, zeros past the end of the tensor).  Lanes whose block
+// lies past the last block of the tensor take part in the exchanges and store nothing.
+template <int B>
+__device__ __forceinline__ void compress_group_butterfly(float (&v)[8], int lane, int64_t group, int64_t n_blocks_total,
                                                          float tau, float eps, uint8_t* __restrict__ payload,
                                                          float2* __restrict__ scales, bool interleaved, Variant var) {
-    constexpr int R = ButterflyShape<B>::kRegs;
+    const LaneSlot<B> slot(group, lane);
     float alpha = 1.0f;
     if (var.rescale()) {
         float energy = 0.0f;
 #pragma unroll
-        for (int r = 0; r < R; ++r) energy = __builtin_fmaf(v[r], v[r], energy);
-        energy = wave_allreduce_sum(energy);                          // sum_j G_kj^2
+        for (int r = 0; r < 8; ++r) energy = __builtin_fmaf(v[r], v[r], energy);
+        energy = block_allreduce_sum<B>(energy);                      // sum_j G_kj^2
         alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / B) + eps);   // Eq. ash_sigma, Eq. ash_alpha
     }
     float norm = 1.0f;
     if (var.rotate()) {
-        fwht_wave<B>(v, lane);                                        // W = H G_k (unnormalised)
+        fwht_group<B>(v, lane);                                       // W = H G_k (unnormalised)
         norm = 1.0f / __builtin_sqrtf(static_cast<float>(B));
     }
     float wmax = 0.0f;
 #pragma unroll
-    for (int r = 0; r < R; ++r) wmax = fmaxf(wmax, __builtin_fabsf(v[r]));
-    wmax = wave_allreduce_max(wmax);
+    for (int r = 0; r < 8; ++r) wmax = fmaxf(wmax, __builtin_fabsf(v[r]));
+    wmax = block_allreduce_max<B>(wmax);
     const float qmax = var.qmax();
     // Z = alpha W / sqrt(B); with the post-rotation scale, s = max|Z| / Q_max (Eq. post_scale) and
     // Z / s = Q_max W / max|W| in exact arithmetic (zero blocks map to zero codes); without it s = 1
@@ -114,37 +201,46 @@ __device__ __forceinline__ void compress_block_butterfly(float (&v)[ButterflySha
         s = wmax > 0.0f ? (wmax * alpha * norm) * (1.0f / qmax) : 0.0f;   // all-zero block: s = 0 even if alpha is infinite (eps = 0)
         to_code = wmax > 0.0f ? qmax * __builtin_amdgcn_rcpf(wmax) : 0.0f;
     }
+    if (slot.blk >= n_blocks_total) return;
+    float q[8];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int e = lane + 64 * r;
-        if (e < B) {
-            float q = v[r] * to_code;
-            if (!var.postscale() || var.format == 2) q = __builtin_amdgcn_fmed3f(q, -qmax, qmax);
-            payload[code_offset<B>(blk, interleaved) + e] = encode_value(q, var);
-        }
+    for (int r = 0; r < 8; ++r) {
+        q[r] = v[r] * to_code;
+        if (!var.postscale() || var.format == 2) q[r] = __builtin_amdgcn_fmed3f(q[r], -qmax, qmax);
     }
-    if (lane == 0) {
-        if (interleaved) *reinterpret_cast<float2*>(payload + code_offset<B>(blk, true) + B) = make_float2(alpha, s);
-        else scales[blk] = make_float2(alpha, s);
+    uint8_t* dst = payload + code_offset<B>(slot.blk, interleaved);
+    *reinterpret_cast<u32x2*>(dst + slot.pos) = encode8(q, var);
+    if (slot.pos == 0) {
+        if (interleaved) *reinterpret_cast<float2*>(dst + B) = make_float2(alpha, s);
+        else scales[slot.blk] = make_float2(alpha, s);
     }
 }
 
-// Sender side of Algorithm 1 for blocks [first_block, first_block + n_blocks).
+// Eight bf16 elements of the group for this lane as floats, zeros past the end of the tensor.
+__device__ __forceinline__ void load_group_elems(const uint16_t* __restrict__ x, int64_t n, int64_t first, float (&v)[8]) {
+    if (first + 8 <= n) {
+        const u32x4 w = *reinterpret_cast<const u32x4*>(x + first);
+        v[0] = bf16_bits_to_f32(w.x & 0xFFFF); v[1] = bf16_bits_to_f32(w.x >> 16);
+        v[2] = bf16_bits_to_f32(w.y & 0xFFFF); v[3] = bf16_bits_to_f32(w.y >> 16);
+        v[4] = bf16_bits_to_f32(w.z & 0xFFFF); v[5] = bf16_bits_to_f32(w.z >> 16);
+        v[6] = bf16_bits_to_f32(w.w & 0xFFFF); v[7] = bf16_bits_to_f32(w.w >> 16);
+    } else {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) v[r] = first + r < n ? bf16_bits_to_f32(x[first + r]) : 0.0f;   // zero padding
+    }
+}
+
+// Sender side of Algorithm 1 for the groups [first_group, first_group + n_groups) of 512 elements.
 template <int B>
 __global__ __launch_bounds__(64) void compress_butterfly_kernel(
-    const uint16_t* __restrict__ x, int64_t n, int64_t first_block, int64_t n_blocks, float tau,
+    const uint16_t* __restrict__ x, int64_t n, int64_t first_group, int64_t n_groups, float tau,
     float eps, uint8_t* __restrict__ payload, float2* __restrict__ scales, bool interleaved, Variant var) {
-    constexpr int R = ButterflyShape<B>::kRegs;
     const int lane = threadIdx.x;
-    for (int64_t blk = first_block + blockIdx.x; blk < first_block + n_blocks; blk += gridDim.x) {
-        float v[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int e = lane + 64 * r;
-            const int64_t idx = blk * B + e;
-            v[r] = (e < B && idx < n) ? bf16_bits_to_f32(x[idx]) : 0.0f;   // zero padding
-        }
-        compress_block_butterfly<B>(v, lane, blk, tau, eps, payload, scales, interleaved, var);
+    const int64_t n_blocks_total = (n + B - 1) / B;
+    for (int64_t g = first_group + blockIdx.x; g < first_group + n_groups; g += gridDim.x) {
+        float v[8];
+        load_group_elems(x, n, g * kGroupElems + 8 * lane, v);
+        compress_group_butterfly<B>(v, lane, g, n_blocks_total, tau, eps, payload, scales, interleaved, var);
     }
 }
 
@@ -153,78 +249,94 @@ struct PayloadTable {
     const void* scales[16];
 };
 
-// Receiver side of Algorithm 1 plus the local reduction over k payloads for one block; the
+// Receiver side of Algorithm 1 plus the local reduction over k payloads for one group; the
 // result (before the final rounding to bf16) is left in v.  The rotation is linear, so for
 // k > 1 the codes are first combined with their block factors s / (alpha sqrt(B)) and rotated
 // once; for k = 1 the raw codes are rotated (exact partial sums) and the factor is applied
-// afterwards.
+// afterwards.  Lanes whose block lies past the end of the tensor read nothing and carry zeros.
 template <int B>
-__device__ __forceinline__ void decode_sum_block_butterfly(const PayloadTable& tab, int k, int64_t blk, int lane,
-                                                           float (&v)[ButterflyShape<B>::kRegs], bool interleaved,
+__device__ __forceinline__ void decode_sum_group_butterfly(const PayloadTable& tab, int k, int64_t group, int lane,
+                                                           int64_t n_blocks_total, float (&v)[8], bool interleaved,
                                                            Variant var) {
-    constexpr int R = ButterflyShape<B>::kRegs;
+    const LaneSlot<B> slot(group, lane);
+    const bool live = slot.blk < n_blocks_total;
     const float inv_root_b = var.rotate() ? 1.0f / __builtin_sqrtf(static_cast<float>(B)) : 1.0f;
 #pragma unroll
-    for (int r = 0; r < R; ++r) v[r] = 0.0f;
+    for (int r = 0; r < 8; ++r) v[r] = 0.0f;
     float single = 1.0f;
-    for (int i = 0; i < k; ++i) {
-        const uint8_t* codes = static_cast<const uint8_t*>(tab.payload[i]) + code_offset<B>(blk, interleaved);
-        const float2 sc = interleaved ? *reinterpret_cast<const float2*>(codes + B)
-                                      : static_cast<const float2*>(tab.scales[i])[blk];
-        const float factor = sc.y * __builtin_amdgcn_rcpf(sc.x) * inv_root_b;   // s / (alpha sqrt(B))
-        const float w = (k == 1) ? 1.0f : factor;
-        single = factor;
+    // Four payloads at a time, all their loads issued before the first is used.
+    for (int i0 = 0; i0 < k; i0 += 4) {
+        u32x2 w8[4];
+        float2 sc[4];
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int e = lane + 64 * r;
-            if (e < B) {
-                const float q = decode_value(codes[e], var);
-                v[r] = __builtin_fmaf(q, w, v[r]);
+        for (int j = 0; j < 4; ++j) {
+            w8[j] = u32x2{0, 0};
+            sc[j] = make_float2(1.0f, 0.0f);
+            if (live && i0 + j < k) {
+                const uint8_t* codes = static_cast<const uint8_t*>(tab.payload[i0 + j]) + code_offset<B>(slot.blk, interleaved);
+                sc[j] = interleaved ? *reinterpret_cast<const float2*>(codes + B)
+                                    : static_cast<const float2*>(tab.scales[i0 + j])[slot.blk];
+                w8[j] = *reinterpret_cast<const u32x2*>(codes + slot.pos);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (i0 + j < k) {
+                const float factor = sc[j].y * __builtin_amdgcn_rcpf(sc[j].x) * inv_root_b;   // s / (alpha sqrt(B))
+                const float w = (k == 1) ? 1.0f : factor;
+                single = factor;
+                float q[8];
+                decode8(w8[j], var, q);
+#pragma unroll
+                for (int r = 0; r < 8; ++r) v[r] = __builtin_fmaf(q[r], w, v[r]);
             }
         }
     }
-    if (var.rotate()) fwht_wave<B>(v, lane);
+    if (var.rotate()) fwht_group<B>(v, lane);
     const float post = (k == 1) ? single : 1.0f;
 #pragma unroll
-    for (int r = 0; r < R; ++r) v[r] *= post;
+    for (int r = 0; r < 8; ++r) v[r] *= post;
 }
 
 template <int B>
 __global__ __launch_bounds__(64) void decompress_sum_butterfly_kernel(
-    PayloadTable tab, int k, int64_t n, int64_t first_block, int64_t n_blocks,
+    PayloadTable tab, int k, int64_t n, int64_t first_group, int64_t n_groups,
     uint16_t* __restrict__ out, bool interleaved, Variant var) {
-    constexpr int R = ButterflyShape<B>::kRegs;
     const int lane = threadIdx.x;
-    for (int64_t blk = first_block + blockIdx.x; blk < first_block + n_blocks; blk += gridDim.x) {
-        float v[R];
-        decode_sum_block_butterfly<B>(tab, k, blk, lane, v, interleaved, var);
+    const int64_t n_blocks_total = (n + B - 1) / B;
+    for (int64_t g = first_group + blockIdx.x; g < first_group + n_groups; g += gridDim.x) {
+        float v[8];
+        decode_sum_group_butterfly<B>(tab, k, g, lane, n_blocks_total, v, interleaved, var);
+        const int64_t first = g * kGroupElems + 8 * lane;
+        if (first + 8 <= n) {
+            u32x4 w;
+            w.x = pack_bf16x2(v[0], v[1]); w.y = pack_bf16x2(v[2], v[3]);
+            w.z = pack_bf16x2(v[4], v[5]); w.w = pack_bf16x2(v[6], v[7]);
+            *reinterpret_cast<u32x4*>(out + first) = w;
+        } else {
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int e = lane + 64 * r;
-            const int64_t idx = blk * B + e;
-            if (e < B && idx < n) out[idx] = static_cast<uint16_t>(pack_bf16x2(v[r], 0.0f) & 0xFFFF);
+            for (int r = 0; r < 8; ++r)
+                if (first + r < n) out[first + r] = static_cast<uint16_t>(pack_bf16x2(v[r], 0.0f) & 0xFFFF);
         }
     }
 }
 
-// decompress_sum followed by compress of the bf16-rounded sum, block by block, without the
+// decompress_sum followed by compress of the bf16-rounded sum, group by group, without the
 // bf16 tensor leaving the registers.
 template <int B>
 __global__ __launch_bounds__(64) void decompress_sum_compress_butterfly_kernel(
-    PayloadTable tab, int k, int64_t n, int64_t first_block, int64_t n_blocks, float tau, float eps,
+    PayloadTable tab, int k, int64_t n, int64_t first_group, int64_t n_groups, float tau, float eps,
     uint8_t* __restrict__ payload_out, float2* __restrict__ scales_out, bool interleaved, Variant var) {
-    constexpr int R = ButterflyShape<B>::kRegs;
     const int lane = threadIdx.x;
-    for (int64_t blk = first_block + blockIdx.x; blk < first_block + n_blocks; blk += gridDim.x) {
-        float v[R];
-        decode_sum_block_butterfly<B>(tab, k, blk, lane, v, interleaved, var);
+    const int64_t n_blocks_total = (n + B - 1) / B;
+    for (int64_t g = first_group + blockIdx.x; g < first_group + n_groups; g += gridDim.x) {
+        float v[8];
+        decode_sum_group_butterfly<B>(tab, k, g, lane, n_blocks_total, v, interleaved, var);
+        const int64_t first = g * kGroupElems + 8 * lane;
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int e = lane + 64 * r;
-            const int64_t idx = blk * B + e;
-            v[r] = (e < B && idx < n) ? bf16_bits_to_f32(pack_bf16x2(v[r], 0.0f) & 0xFFFF) : 0.0f;
-        }
-        compress_block_butterfly<B>(v, lane, blk, tau, eps, payload_out, scales_out, interleaved, var);
+        for (int r = 0; r < 8; ++r)
+            v[r] = first + r < n ? bf16_bits_to_f32(pack_bf16x2(v[r], 0.0f) & 0xFFFF) : 0.0f;
+        compress_group_butterfly<B>(v, lane, g, n_blocks_total, tau, eps, payload_out, scales_out, interleaved, var);
     }
 }
 

@@ -1,5 +1,5 @@
 // Device-side helpers shared by the gfx950 kernels: type punning, bf16 / FP8 conversion
-// instructions, DPP lane exchanges inside a 16-lane row and whole-wave reductions.
+// instructions, DPP lane exchanges inside a 16-lane row, wave-local LDS ordering.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -73,27 +73,17 @@ __device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
 constexpr int kDppRowRor(int n) { return 0x120 + n; }                  // rotate right by n in the row
 constexpr int kDppQuadBcast(int q) { return q | (q << 2) | (q << 4) | (q << 6); }  // lane q of each quad
 
-// max over the 16 lanes of a row, result in every lane.
-__device__ __forceinline__ float row16_allreduce_max(float v) {
-    v = fmaxf(v, dpp_f32<kDppRowRor(8)>(v));
-    v = fmaxf(v, dpp_f32<kDppRowRor(4)>(v));
-    v = fmaxf(v, dpp_f32<kDppRowRor(2)>(v));
-    v = fmaxf(v, dpp_f32<kDppRowRor(1)>(v));
-    return v;
-}
-
-// ---- whole-wave (64 lanes) reductions, result in every lane ---------------------------
-
-__device__ __forceinline__ float wave_allreduce_sum(float v) {
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m, 64);
-    return v;
-}
-
-__device__ __forceinline__ float wave_allreduce_max(float v) {
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
-    return v;
+// The value held by lane (lane ^ kMask).  Masks inside a row of 16 lanes are DPP moves (quad
+// permutes for 1 and 2; for 4 the mirror of each half row, lane ^ 7, followed by the reversal of
+// each quad, lane ^ 3; for 8 the rotation by half a row); 16 and 32 go through the LDS crossbar.
+template <int kMask>
+__device__ __forceinline__ float lane_xor(float v) {
+    static_assert(kMask == 1 || kMask == 2 || kMask == 4 || kMask == 8 || kMask == 16 || kMask == 32, "one lane bit");
+    if (kMask == 1) return dpp_f32<0xB1>(v);                      // quad_perm [1,0,3,2]
+    if (kMask == 2) return dpp_f32<0x4E>(v);                      // quad_perm [2,3,0,1]
+    if (kMask == 4) return dpp_f32<0x1B>(dpp_f32<0x141>(v));      // row_half_mirror, then quad_perm [3,2,1,0]
+    if (kMask == 8) return dpp_f32<kDppRowRor(8)>(v);
+    return __shfl_xor(v, kMask, 64);
 }
 
 // Orders one wave's LDS accesses: what its lanes wrote before is visible to what they read after.

@@ -55,7 +55,8 @@ bool use_mfma(const taco_params* p) {
 
 taco::Variant variant_of(const taco_params* p) { return taco::Variant{p->mode, p->format}; }
 
-// Persistent grids: enough single-wave workgroups to fill every SIMD several times over.
+// Grid of the butterfly kernels: one single-wave workgroup per work item (one-shot waves, as in the
+// matrix-core kernels) up to waves_per_cu per compute unit, a stride loop beyond that.
 int grid_for(int64_t work_items, int waves_per_cu) {
     int64_t cap = static_cast<int64_t>(device_cus()) * waves_per_cu;
     int64_t g = work_items < cap ? work_items : cap;
@@ -115,8 +116,7 @@ int launch_decode(const taco::PayloadTable& tab, int k, int64_t n, const taco_pa
                   void* out_bf16, void* payload_out, void* scales_out, hipStream_t st) {
     const int B = p->block;
     const bool il = p->layout == TACO_LAYOUT_INTERLEAVED;
-    const int64_t n_blocks = (n + B - 1) / B;
-    int64_t first_block = 0;
+    int64_t first_group = 0;       // groups of 512 elements: what one wave of the butterfly kernels handles
     if (use_mfma(p)) {
         const int64_t n_tiles = n / taco::kTileElems;
         if (n_tiles > 0) {
@@ -147,20 +147,20 @@ int launch_decode(const taco::PayloadTable& tab, int k, int64_t n, const taco_pa
             });
             if (int rc = launch_status()) return rc;
         }
-        first_block = n_tiles * (taco::kTileElems / B);
+        first_group = n_tiles * (taco::kTileElems / taco::kGroupElems);
     }
-    const int64_t rest = n_blocks - first_block;
+    const int64_t rest = (n - first_group * taco::kGroupElems + taco::kGroupElems - 1) / taco::kGroupElems;
     if (rest > 0) {
         const float tau = p->tau, eps = p->eps;
         int rc = dispatch_block(B, [&](auto bc) {
             constexpr int kB = decltype(bc)::value;
             if (recompress)
-                hipLaunchKernelGGL(taco::decompress_sum_compress_butterfly_kernel<kB>, dim3(grid_for(rest, 32)), dim3(64), 0, st,
-                                   tab, k, n, first_block, rest, tau, eps, static_cast<uint8_t*>(payload_out),
+                hipLaunchKernelGGL(taco::decompress_sum_compress_butterfly_kernel<kB>, dim3(grid_for(rest, 16384)), dim3(64), 0, st,
+                                   tab, k, n, first_group, rest, tau, eps, static_cast<uint8_t*>(payload_out),
                                    static_cast<float2*>(scales_out), il, variant_of(p));
             else
-                hipLaunchKernelGGL(taco::decompress_sum_butterfly_kernel<kB>, dim3(grid_for(rest, 32)), dim3(64), 0, st,
-                                   tab, k, n, first_block, rest, static_cast<uint16_t*>(out_bf16), il, variant_of(p));
+                hipLaunchKernelGGL(taco::decompress_sum_butterfly_kernel<kB>, dim3(grid_for(rest, 16384)), dim3(64), 0, st,
+                                   tab, k, n, first_group, rest, static_cast<uint16_t*>(out_bf16), il, variant_of(p));
         });
         if (rc) return rc;
         if (int rc2 = launch_status()) return rc2;
@@ -204,8 +204,7 @@ int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_par
     if (!aligned16(x_bf16) || !aligned16(payload) || (!il && !aligned16(scales))) return TACO_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int B = p->block;
-    const int64_t n_blocks = (n + B - 1) / B;
-    int64_t first_block = 0;
+    int64_t first_group = 0;       // groups of 512 elements: what one wave of the butterfly kernels handles
     if (use_mfma(p)) {
         const int64_t n_tiles = n / taco::kTileElems;
         if (n_tiles > 0) {
@@ -223,15 +222,15 @@ int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_par
             });
             if (int rc = launch_status()) return rc;
         }
-        first_block = n_tiles * (taco::kTileElems / B);
+        first_group = n_tiles * (taco::kTileElems / taco::kGroupElems);
     }
-    const int64_t rest = n_blocks - first_block;
+    const int64_t rest = (n - first_group * taco::kGroupElems + taco::kGroupElems - 1) / taco::kGroupElems;
     if (rest > 0) {
         const float tau = p->tau, eps = p->eps;
         int rc = dispatch_block(B, [&](auto bc) {
             constexpr int kB = decltype(bc)::value;
-            hipLaunchKernelGGL(taco::compress_butterfly_kernel<kB>, dim3(grid_for(rest, 32)), dim3(64), 0, st,
-                               static_cast<const uint16_t*>(x_bf16), n, first_block, rest, tau, eps,
+            hipLaunchKernelGGL(taco::compress_butterfly_kernel<kB>, dim3(grid_for(rest, 16384)), dim3(64), 0, st,
+                               static_cast<const uint16_t*>(x_bf16), n, first_group, rest, tau, eps,
                                static_cast<uint8_t*>(payload), static_cast<float2*>(scales), il, variant_of(p));
         });
         if (rc) return rc;
