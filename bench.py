@@ -39,6 +39,11 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+# Share of time the matrix cores are busy in the dominant kernel (SQ_VALU_MFMA_BUSY_CYCLES over SIMD-cycles,
+# rocprofv3 --pmc run summarised in the same profile); the Hadamard rotation is an MFMA contraction there.
+MEASURED_MFMA_BUSY = {("large_k8", 128, "auto"): 0.205}
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -375,7 +380,8 @@ def main():
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, B, args.impl)) if args.layout == "split" else None,
-                     "alg_bytes_per_launch": bytes_comp, "avg_launch_ms": round(t_comp, 4)},
+                     "alg_bytes_per_launch": bytes_comp, "avg_launch_ms": round(t_comp, 4),
+                     "mfma_busy_frac": MEASURED_MFMA_BUSY.get((w.name, B, args.impl)) if args.layout == "split" else None},
     }
     if not args.no_cpu_baseline:
         gpu = (sets[0][1], sets[0][2], params, taco) if args.layout == "split" and impl != taco.TACO_IMPL_BUTTERFLY else None
