@@ -12,10 +12,11 @@
 // Everything else (sum of squares, max|W|, the two block scalars, conversion) rides along in
 // the same pass, so each byte of the tensor crosses HBM once.
 //
-// One 64-lane wavefront per workgroup (the workgroup barrier is then free) handles a few
-// consecutive tiles and exits: no persistent loop.  The dispatcher hands out workgroups in
-// index order, so the tiles in flight form one dense, advancing window of memory, which
-// measured ~15 % faster on HBM than a grid-stride loop over the same tiles.
+// A 64-lane wavefront handles one or two consecutive tiles and exits: no persistent loop.  The
+// dispatcher hands out workgroups in index order, so the tiles in flight form one dense,
+// advancing window of memory, which measured ~15 % faster on HBM than a grid-stride loop over the
+// same tiles.  Every wave works in an LDS region of its own (one or two waves per workgroup), so
+// there is no workgroup barrier anywhere: wave_lds_sync() orders a wave's own LDS accesses.
 //
 //   global -> registers   coalesced 16-byte non-temporal loads, 1 KiB per wave instruction
 //   registers -> LDS      the tile, unit row by unit row, swizzled
@@ -227,7 +228,7 @@ struct CompressLane {
     }
 
     // Sender side of Algorithm 1 for the tile that sits in LDS.  Ends with the wave past its last
-    // LDS read (a barrier follows the reads), so the caller may overwrite the buffer afterwards.
+    // LDS read (wave_lds_sync follows the reads), so the caller may overwrite the buffer afterwards.
     // In the interleaved layout the records (B + 8 bytes) do not line up with cache lines, and
     // storing codes and scalars straight from the lanes leaves every line written in pieces
     // (measured: 142 us instead of 99 us per compress of the bench tensor).  The tile's records are
@@ -394,8 +395,8 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
 // payloads, scales: see PayloadLayout; out: n_tiles * 2048 bf16.
 // Wave v = blockIdx.x * kWaves + wave-in-workgroup handles output tiles
 // [v * tiles_per_wave, (v+1) * tiles_per_wave) and exits; the waves of a workgroup share nothing
-// (each has its own LDS region, there is no workgroup barrier).  A wave's work is the flattened list of (tile, payload) items, payload fastest; a ring of
-// kRing items is kept in flight in registers.  For blocks of several units the per-payload work
+// (each has its own LDS region, there is no workgroup barrier).  A wave's work is the flattened
+// list of (tile, payload) items, payload fastest; a ring of kRing items is kept in flight in registers.  For blocks of several units the per-payload work
 // is the 128-point product of every unit times the block factor; the butterfly across units is
 // linear, so it runs once on the accumulated sums.
 //
