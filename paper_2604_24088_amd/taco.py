@@ -127,6 +127,32 @@ def _ptr_or_null(t):
     return None if t is None else t.data_ptr()
 
 
+def _require(cond: bool, what: str):
+    if not cond:
+        raise ValueError(what)
+
+
+def _check_buffer(t, dtype, min_bytes: int, name: str, device=None):
+    """A tensor handed to a kernel: on the GPU, contiguous, of the expected dtype and large enough.  The C entry
+    points see only a pointer, so this is where an undersized buffer is caught before a kernel writes past its end."""
+    _require(isinstance(t, torch.Tensor) and t.is_cuda, f"{name}: expected a CUDA tensor")
+    _require(t.dtype == dtype, f"{name}: expected dtype {dtype}, got {t.dtype}")
+    _require(t.is_contiguous(), f"{name}: must be contiguous")
+    _require(t.numel() * t.element_size() >= min_bytes, f"{name}: {t.numel() * t.element_size()} bytes, {min_bytes} needed")
+    _require(device is None or t.device == device, f"{name}: on {t.device}, expected {device}")
+
+
+def _check_payload_args(n: int, p: "taco_params", payloads, scales, device):
+    il = p.layout == TACO_LAYOUT_INTERLEAVED
+    codes, sc_bytes = taco_payload_bytes(n, p.block), taco_scales_bytes(n, p.block)
+    _require(codes > 0, f"bad shape or block size (n = {n}, block = {p.block})")
+    for i, t in enumerate(payloads):
+        _check_buffer(t, torch.uint8, codes + (sc_bytes if il else 0), f"payload[{i}]", device)
+    if not il:
+        for i, t in enumerate(scales):
+            _check_buffer(t, torch.float32, sc_bytes, f"scales[{i}]", device)
+
+
 def _alloc_outputs(n: int, p: taco_params, device, payload, scales):
     """Split layout: (codes, scales[n_blocks, 2]).  Interleaved: (one buffer of B + 8 byte records, None)."""
     if p.layout == TACO_LAYOUT_INTERLEAVED:
@@ -159,10 +185,11 @@ def taco_compress(x: torch.Tensor, params: Optional[taco_params] = None,
                   stream=None):
     """Sender side of Algorithm 1.  x: contiguous CUDA bf16 tensor.  Returns (payload, scales)."""
     p = params or taco_default_params()
-    assert x.is_cuda and x.dtype == torch.bfloat16 and x.is_contiguous()
+    _check_buffer(x, torch.bfloat16, 2, "x")
     rows, cols = _rows_cols(x.shape)
     n = rows * cols
     payload, scales = _alloc_outputs(n, p, x.device, payload, scales)
+    _check_payload_args(n, p, [payload], [scales], x.device)
     st = lib().taco_compress(x.data_ptr(), rows, cols, ctypes.byref(p), payload.data_ptr(),
                              _ptr_or_null(scales), _stream_handle(stream))
     _check(st, "taco_compress")
@@ -175,8 +202,11 @@ def taco_decompress(payload: torch.Tensor, scales: torch.Tensor, shape,
     """Receiver side of Algorithm 1.  Returns a bf16 tensor of `shape`."""
     p = params or taco_default_params()
     rows, cols = _rows_cols(tuple(shape))
+    _require(isinstance(payload, torch.Tensor) and payload.is_cuda, "payload: expected a CUDA tensor")
     if out is None:
         out = torch.empty(tuple(shape), dtype=torch.bfloat16, device=payload.device)
+    _check_payload_args(rows * cols, p, [payload], [scales], payload.device)
+    _check_buffer(out, torch.bfloat16, 2 * rows * cols, "out", payload.device)
     st = lib().taco_decompress(payload.data_ptr(), _ptr_or_null(scales), rows, cols, ctypes.byref(p),
                                out.data_ptr(), _stream_handle(stream))
     _check(st, "taco_decompress")
@@ -189,11 +219,15 @@ def taco_decompress_sum(payloads: Sequence[torch.Tensor], scales: Sequence[torch
     """Decode k payloads and add them (fp32 accumulation, one bf16 rounding)."""
     p = params or taco_default_params()
     k = len(payloads)
+    _require(1 <= k <= TACO_MAX_K, f"k = {k}: between 1 and {TACO_MAX_K} payloads")
     scales = list(scales) if scales is not None else [None] * k
-    assert k == len(scales)
+    _require(k == len(scales), "as many scales as payloads")
     rows, cols = _rows_cols(tuple(shape))
+    _require(isinstance(payloads[0], torch.Tensor) and payloads[0].is_cuda, "payload[0]: expected a CUDA tensor")
     if out is None:
         out = torch.empty(tuple(shape), dtype=torch.bfloat16, device=payloads[0].device)
+    _check_payload_args(rows * cols, p, payloads, scales, payloads[0].device)
+    _check_buffer(out, torch.bfloat16, 2 * rows * cols, "out", payloads[0].device)
     parr = _pointer_array(payloads, k)
     sarr = _pointer_array(scales, k)
     st = lib().taco_decompress_sum(parr, sarr, k, rows, cols, ctypes.byref(p), out.data_ptr(),
@@ -209,11 +243,14 @@ def taco_decompress_sum_compress(payloads: Sequence[torch.Tensor], scales: Seque
     """Decode and add k payloads, round the sum to bf16 and compress it again, in one pass."""
     p = params or taco_default_params()
     k = len(payloads)
+    _require(1 <= k <= TACO_MAX_K, f"k = {k}: between 1 and {TACO_MAX_K} payloads")
     scales = list(scales) if scales is not None else [None] * k
-    assert k == len(scales)
+    _require(k == len(scales), "as many scales as payloads")
     rows, cols = _rows_cols(tuple(shape))
     n = rows * cols
+    _require(isinstance(payloads[0], torch.Tensor) and payloads[0].is_cuda, "payload[0]: expected a CUDA tensor")
     payload_out, scales_out = _alloc_outputs(n, p, payloads[0].device, payload_out, scales_out)
+    _check_payload_args(n, p, list(payloads) + [payload_out], scales + [scales_out], payloads[0].device)
     parr = _pointer_array(payloads, k)
     sarr = _pointer_array(scales, k)
     st = lib().taco_decompress_sum_compress(parr, sarr, k, rows, cols, ctypes.byref(p), payload_out.data_ptr(),
@@ -224,7 +261,7 @@ def taco_decompress_sum_compress(payloads: Sequence[torch.Tensor], scales: Seque
 
 def taco_debug_cvt_e4m3(values: torch.Tensor, stream=None) -> torch.Tensor:
     """Hardware float32 -> E4M3 conversion of a CUDA float tensor (diagnostic)."""
-    assert values.is_cuda and values.dtype == torch.float32 and values.is_contiguous()
+    _check_buffer(values, torch.float32, 4, "values")
     out = torch.empty(values.numel(), dtype=torch.uint8, device=values.device)
     st = lib().taco_debug_cvt_e4m3(values.data_ptr(), values.numel(), out.data_ptr(),
                                    _stream_handle(stream))
@@ -234,8 +271,10 @@ def taco_debug_cvt_e4m3(values: torch.Tensor, stream=None) -> torch.Tensor:
 
 def taco_debug_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> torch.Tensor:
     """Plain device copy of src into dst (same byte size, a multiple of 16): bandwidth yardstick."""
+    _require(isinstance(src, torch.Tensor) and isinstance(dst, torch.Tensor) and src.is_cuda and dst.is_cuda
+             and src.is_contiguous() and dst.is_contiguous(), "src, dst: contiguous CUDA tensors")
     nbytes = src.numel() * src.element_size()
-    assert src.is_cuda and dst.is_cuda and nbytes == dst.numel() * dst.element_size()
+    _require(nbytes == dst.numel() * dst.element_size(), "src and dst differ in size")
     st = lib().taco_debug_copy(src.data_ptr(), dst.data_ptr(), nbytes, _stream_handle(stream))
     _check(st, "taco_debug_copy")
     return dst
@@ -246,9 +285,14 @@ def taco_debug_traffic(srcs: Sequence[torch.Tensor], src_chunks: int, dst: torch
     """Memory-only stand-in for the operator: per tile reads src_chunks 16-byte words from every source and
     writes dst_chunks words to dst (bandwidth yardstick for that mix of reads and writes)."""
     k = len(srcs)
-    for t in srcs:
-        assert t.is_cuda and t.numel() * t.element_size() >= n_tiles * src_chunks * 16
-    assert dst.is_cuda and dst.numel() * dst.element_size() >= n_tiles * dst_chunks * 16
+    _require(n_tiles >= 1 and 1 <= src_chunks <= 256 and 1 <= dst_chunks <= 256, "chunk counts 1..256, n_tiles >= 1")
+    for i, t in enumerate(srcs):
+        _require(isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()
+                 and t.numel() * t.element_size() >= n_tiles * src_chunks * 16, f"srcs[{i}]: contiguous CUDA tensor of "
+                 f"at least {n_tiles * src_chunks * 16} bytes")
+    _require(isinstance(dst, torch.Tensor) and dst.is_cuda and dst.is_contiguous()
+             and dst.numel() * dst.element_size() >= n_tiles * dst_chunks * 16, f"dst: contiguous CUDA tensor of at least "
+             f"{n_tiles * dst_chunks * 16} bytes")
     st = lib().taco_debug_traffic(_pointer_array(srcs, k), k, src_chunks, dst.data_ptr(), dst_chunks, n_tiles,
                                   _stream_handle(stream))
     _check(st, "taco_debug_traffic")

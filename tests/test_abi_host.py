@@ -143,3 +143,17 @@ def test_decompress_rejects_bad_arguments():
     assert L.taco_debug_cvt_e4m3(A, 0, A, None) == -2
     with pytest.raises(taco.TacoError):
         taco._check(-3, "x")
+
+
+def test_binding_rejects_tensors_that_are_not_gpu_buffers():
+    """The Python binding checks device, dtype, contiguity and size before it hands a pointer to the library."""
+    import torch
+    x = torch.zeros(4, 512, dtype=torch.bfloat16)
+    with pytest.raises(ValueError, match="CUDA"):
+        taco.taco_compress(x)
+    with pytest.raises(ValueError, match="CUDA"):
+        taco.taco_decompress(torch.zeros(2048, dtype=torch.uint8), torch.zeros(16, 2), (4, 512))
+    with pytest.raises(ValueError, match="between 1 and 16"):
+        taco.taco_decompress_sum([], [], (4, 512))
+    with pytest.raises(ValueError, match="CUDA"):
+        taco.taco_debug_copy(x, x.clone())

@@ -520,3 +520,29 @@ def test_extreme_magnitudes(oracle, impl, block, exp):
     torch.cuda.synchronize()
     P.check_recon(bits_of(out), oracle.decompress(rp, rs, xs.size, block=block), block, f"2^{exp} decompress",
                   min_exact=0.99)
+
+
+def test_binding_rejects_undersized_buffers():
+    """A buffer too small for the shape never reaches a kernel."""
+    x = to_dev(sample_rows(W.WORKLOADS["gpt_rowpar"], rows=2))
+    n = x.numel()
+    p = taco.taco_default_params()
+    small = torch.empty(n - 1, dtype=torch.uint8, device=DEV)
+    sc = torch.empty((n // 128, 2), dtype=torch.float32, device=DEV)
+    with pytest.raises(ValueError, match="bytes"):
+        taco.taco_compress(x, p, small, sc)
+    with pytest.raises(ValueError, match="bytes"):
+        taco.taco_compress(x, p, torch.empty(n, dtype=torch.uint8, device=DEV), sc[:-1])
+    pl, sc = taco.taco_compress(x, p)
+    with pytest.raises(ValueError, match="bytes"):
+        taco.taco_decompress(pl, sc, x.shape, p, out=torch.empty(n - 8, dtype=torch.bfloat16, device=DEV))
+    with pytest.raises(ValueError, match="dtype"):
+        taco.taco_decompress(pl, sc, x.shape, p, out=torch.empty(n, dtype=torch.float16, device=DEV))
+    with pytest.raises(ValueError, match="contiguous"):
+        taco.taco_compress(x.t(), p)
+    with pytest.raises(ValueError, match="bytes"):
+        taco.taco_decompress_sum([pl, pl[:-16]], [sc, sc], x.shape, p)
+    pi = taco.taco_default_params(layout=taco.TACO_LAYOUT_INTERLEAVED)
+    with pytest.raises(ValueError, match="bytes"):
+        taco.taco_compress(x, pi, torch.empty(n, dtype=torch.uint8, device=DEV))      # records need n + n/16 bytes
+    torch.cuda.synchronize()
