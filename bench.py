@@ -346,7 +346,7 @@ def main():
 
     achieved = bytes_comp / t_comp / 1e6
     result = {
-        "metric": "compress+decompress GB/s of bf16 input and % of HBM peak, 1xMI355X",
+        "metric": "compress+decompress GB/s of bf16 input and % of HBM peak, 1\u00d7MI355X",
         "value": round(equiv / (ms_step * 1e6), 1),
         "unit": "GB/s",
         "n_gpus": 1,
