@@ -198,7 +198,8 @@ __device__ __forceinline__ void compress_group_butterfly(float (&v)[8], int lane
     // and Z itself is converted, saturating at +-Q_max.
     float s = 1.0f, to_code = alpha * norm;
     if (var.postscale()) {
-        s = wmax > 0.0f ? (wmax * alpha * norm) * (1.0f / qmax) : 0.0f;   // all-zero block: s = 0 even if alpha is infinite (eps = 0)
+        // an all-zero block stores s = 0 even where alpha is infinite (eps = 0)
+        s = wmax > 0.0f ? (wmax * alpha * norm) * (1.0f / qmax) : 0.0f;
         to_code = wmax > 0.0f ? qmax * __builtin_amdgcn_rcpf(wmax) : 0.0f;
     }
     if (slot.blk >= n_blocks_total) return;

@@ -396,9 +396,10 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
 // Wave v = blockIdx.x * kWaves + wave-in-workgroup handles output tiles
 // [v * tiles_per_wave, (v+1) * tiles_per_wave) and exits; the waves of a workgroup share nothing
 // (each has its own LDS region, there is no workgroup barrier).  A wave's work is the flattened
-// list of (tile, payload) items, payload fastest; a ring of kRing items is kept in flight in registers.  For blocks of several units the per-payload work
-// is the 128-point product of every unit times the block factor; the butterfly across units is
-// linear, so it runs once on the accumulated sums.
+// list of (tile, payload) items, payload fastest; a ring of kRing items is kept in flight in
+// registers.  For blocks of several units the per-payload work is the 128-point product of every
+// unit times the block factor; the butterfly across units is linear, so it runs once on the
+// accumulated sums.
 //
 // kRecompress = true turns the kernel into decompress_sum followed by compress of the
 // bf16-rounded sum (the receive side of the reduce-scatter feeding the send side of the
