@@ -53,6 +53,8 @@ def parse():
     ap.add_argument("--block", type=int, default=128)
     ap.add_argument("--impl", default="auto", choices=["auto", "butterfly", "mfma"])
     ap.add_argument("--layout", default="split", choices=["split", "interleaved"])
+    ap.add_argument("--format", default="e4m3", choices=["e4m3", "e5m2", "int8"], help="code book (ablation variants)")
+    ap.add_argument("--mode", type=int, default=7, help="bit mask of the method's stages: 1 rescale, 2 rotate, 4 post-scale")
     ap.add_argument("--chunk-mb", type=float, default=0.0,
                     help="issue every call in row chunks of about this many MB of bf16 (0 = whole tensor): the overlap "
                          "granularity of Section 4.4.2")
@@ -152,7 +154,9 @@ def main():
     k, n, B = w.payloads, w.numel, args.block
     impl = {"auto": taco.TACO_IMPL_AUTO, "butterfly": taco.TACO_IMPL_BUTTERFLY, "mfma": taco.TACO_IMPL_MFMA}[args.impl]
     layout = taco.TACO_LAYOUT_INTERLEAVED if args.layout == "interleaved" else taco.TACO_LAYOUT_SPLIT
-    params = taco.taco_default_params(block=B, impl=impl, layout=layout)
+    fmt = {"e4m3": taco.TACO_FORMAT_E4M3, "e5m2": taco.TACO_FORMAT_E5M2, "int8": taco.TACO_FORMAT_INT8}[args.format]
+    params = taco.taco_default_params(block=B, impl=impl, layout=layout, mode=args.mode, fmt=fmt)
+    variant = args.mode != taco.TACO_MODE_FULL or fmt != taco.TACO_FORMAT_E4M3
 
     # ---- synthetic inputs, resident in HBM
     host = np.empty((w.tokens, w.hidden), dtype=np.uint16)
@@ -363,7 +367,7 @@ def main():
                    "impl": args.impl, "block": B, "layout": args.layout,
                    "chunk_rows": rows_per_chunk if len(bounds) > 1 else None, "chunks_per_call": len(bounds),
                    "streams": max(len(side), 1), "hip_graph": bool(args.graph),
-                   "buffer_sets": n_sets},
+                   "buffer_sets": n_sets, "format": args.format, "mode": args.mode},
         "value_out_basis": round(real_bf16 / (ms_step * 1e6), 1),
         "moved_GBps": round(moved / (ms_step * 1e6), 1),
         "hbm_frac_step": round(moved / (ms_step * 1e6) / HBM_PEAK_GBPS, 4),
@@ -375,16 +379,20 @@ def main():
                   f"decompress_sum_k{k}": call(t_sum, bytes_sum, k * 2.0 * n),
                   f"decompress_sum_compress_k{k} (not in the step)": call(t_fused, (k + 1) * per_elem * n, k * 2.0 * n)},
         "roofline": {"kernel": (f"compress_mfma_kernel<{max(B // 128, 1)},{max(128 // B, 1)},1,"
-                                f"{'true' if args.layout == 'interleaved' else 'false'}>") if args.impl != "butterfly"
+                                f"{'true' if args.layout == 'interleaved' else 'false'},{1 if args.format == 'e5m2' else 0}>")
+                     if args.impl != "butterfly" and args.mode in (6, 7) and args.format != "int8"
                      else f"compress_butterfly_kernel<{B}>",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, B, args.impl)) if args.layout == "split" else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, B, args.impl)) if args.layout == "split" and not variant else None,
                      "alg_bytes_per_launch": bytes_comp, "avg_launch_ms": round(t_comp, 4),
-                     "mfma_busy_frac": MEASURED_MFMA_BUSY.get((w.name, B, args.impl)) if args.layout == "split" else None},
+                     "mfma_busy_frac": MEASURED_MFMA_BUSY.get((w.name, B, args.impl)) if args.layout == "split" and not variant else None},
     }
-    if not args.no_cpu_baseline:
-        gpu = (sets[0][1], sets[0][2], params, taco) if args.layout == "split" and impl != taco.TACO_IMPL_BUTTERFLY else None
+    if not args.no_cpu_baseline and variant:
+        print("bench.py: the CPU baseline is timed for the method itself (mode 7, E4M3) only; skipped", file=sys.stderr)
+    if not args.no_cpu_baseline and not variant:
+        gpu = (sets[0][1], sets[0][2], params, taco) if (args.layout == "split" and impl != taco.TACO_IMPL_BUTTERFLY
+                                                         and not variant) else None
         result["cpu_baseline"], parity = cpu_baseline(w, B, rows=w.tokens, gpu=gpu)
         if parity is not None:
             result["parity_full_size"] = parity

@@ -75,13 +75,15 @@ enum { TACO_FORMAT_E4M3 = 0, TACO_FORMAT_E5M2 = 1, TACO_FORMAT_INT8 = 2 };
 /* Stages of the method, for the paper's component ablations (Section 5.2.2, Section 5.3): a bit
  * mask.  Without RESCALE alpha_k = 1; without ROTATE Z_k = alpha_k G_k; without POSTSCALE s_k = 1
  * and Z_k itself is converted, saturating at +-Q_max.  FULL (7) is the method; 0 is the direct
- * cast, 4 "DS only", 2 the standard Hadamard transform, 3 ASH without DS.  Every variant other
- * than FULL + E4M3 runs on the butterfly kernels: they are there for numerical studies. */
+ * cast, 4 "DS only", 2 the standard Hadamard transform, 3 ASH without DS.  The matrix-core
+ * kernels cover the variants that keep the method's structure (rotation and post-rotation scale
+ * on, i.e. modes 7 and 6, in E4M3 or E5M2); every other variant runs on the butterfly kernels. */
 enum { TACO_MODE_RESCALE = 1, TACO_MODE_ROTATE = 2, TACO_MODE_POSTSCALE = 4, TACO_MODE_FULL = 7 };
 
-/* Kernel selection.  AUTO and MFMA run whole tiles of 2048 elements on the matrix-core
- * kernel and the rest of the tensor on the plain butterfly kernel; BUTTERFLY runs everything
- * on the butterfly kernel (kept for tests and benchmarks that compare the two). */
+/* Kernel selection.  AUTO runs whole tiles of 2048 elements on the matrix-core kernels where the
+ * variant allows it (see above) and the rest of the tensor on the butterfly kernels; MFMA is AUTO
+ * that fails with TACO_ERR_IMPL for a variant the matrix-core kernels do not cover; BUTTERFLY runs
+ * everything on the butterfly kernels (kept for tests and benchmarks that compare the two). */
 enum { TACO_IMPL_AUTO = 0, TACO_IMPL_BUTTERFLY = 1, TACO_IMPL_MFMA = 2 };
 
 /* Where the two scalars of a block travel (Section 4.4.2 of the paper places them directly

@@ -37,6 +37,21 @@ __device__ __forceinline__ uint32_t pack_e4m3x4(float v0, float v1, float v2, fl
     return static_cast<uint32_t>(w);
 }
 
+// The same for E5M2 codes (the format ablation's other 8-bit float).
+__device__ __forceinline__ uint32_t pack_e5m2x4(float v0, float v1, float v2, float v3) {
+    int w = __builtin_amdgcn_cvt_pk_bf8_f32(v0, v1, 0, false);
+    w = __builtin_amdgcn_cvt_pk_bf8_f32(v2, v3, w, true);
+    return static_cast<uint32_t>(w);
+}
+
+// Code book of the matrix-core kernels: 0 = E4M3 (the method), 1 = E5M2 (format ablation).
+template <int kFormat>
+__device__ __forceinline__ uint32_t pack_fp8x4(float v0, float v1, float v2, float v3) {
+    return kFormat == 0 ? pack_e4m3x4(v0, v1, v2, v3) : pack_e5m2x4(v0, v1, v2, v3);
+}
+template <int kFormat>
+__device__ __forceinline__ constexpr float format_qmax() { return kFormat == 0 ? 448.0f : 57344.0f; }
+
 // Sum of squares of the two bf16 halves of a dword, added to acc (v_dot2c_f32_bf16).
 // The dword is taken BY VALUE: bit-casting a vector-element lvalue directly reads element 0.
 __device__ __forceinline__ float dot2_self_bf16(uint32_t pair, float acc) {

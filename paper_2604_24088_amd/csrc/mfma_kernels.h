@@ -234,9 +234,12 @@ struct CompressLane {
     // (measured: 142 us instead of 99 us per compress of the bench tensor).  The tile's records are
     // therefore assembled in LDS (the input buffer is free once the A operands are read) and
     // leave as contiguous 16-byte chunks.
-    template <bool kInterleaved>
-    __device__ __forceinline__ void tile_from_lds(uint32_t* lds, int64_t tile, float tau, float eps,
+    // kFormat: 0 = E4M3, 1 = E5M2 (format ablation).  rescale = false is the component ablation
+    // without the adaptive rescaling ("standard Hadamard" with the post-rotation scale): alpha = 1.
+    template <bool kInterleaved, int kFormat>
+    __device__ __forceinline__ void tile_from_lds(uint32_t* lds, int64_t tile, float tau, float eps, bool rescale,
                                                   u32x2* __restrict__ payload, f32x2* __restrict__ scales) const {
+        constexpr float kQ = format_qmax<kFormat>();
         using Layout = PayloadLayout<kBlock, kInterleaved>;
         u32x2* records = reinterpret_cast<u32x2*>(lds);     // interleaved: the tile's records, 8-byte words
         u32x4 a[4];
@@ -276,7 +279,7 @@ struct CompressLane {
         }
         const float wmax = kSub == 1 ? row16_block_max<kRB>(m, n16) : sub_block_max<kSub>(m, n16);
         // Z / s = W * Q_max / max|W| in exact arithmetic (Eq. post_scale, Eq. quantization).
-        const float to_code = wmax > 0.0f ? kQmax * __builtin_amdgcn_rcpf(wmax) : 0.0f;
+        const float to_code = wmax > 0.0f ? kQ * __builtin_amdgcn_rcpf(wmax) : 0.0f;
 
         // Energy of the owned block: own Gram diagonal plus those of the block's other units,
         // which sit in the neighbouring lanes of the quad.
@@ -302,9 +305,9 @@ struct CompressLane {
             energy = __shfl(energy, energy_src, 64);
         }
         if (owns_scales) {
-            const float alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / kBlock) + eps);   // Eq. ash_sigma, ash_alpha
+            const float alpha = rescale ? tau * __builtin_amdgcn_rsqf(energy * (1.0f / kBlock) + eps) : 1.0f;   // Eq. ash_sigma, ash_alpha
             // max|Z| / Q_max; an all-zero block stores s = 0 whatever alpha is (with eps = 0 it is infinite)
-            const float s = wmax > 0.0f ? (wmax * alpha) * (inv_sqrt_block<kBlock>() / kQmax) : 0.0f;
+            const float s = wmax > 0.0f ? (wmax * alpha) * (inv_sqrt_block<kBlock>() / kQ) : 0.0f;
             if (kInterleaved)
                 records[Layout::scale_word(0, my_block)] = __builtin_bit_cast(u32x2, f32x2{alpha, s});
             else
@@ -319,8 +322,8 @@ struct CompressLane {
         {                                                                                      \
             const float f = dpp_f32<kDppQuadBcast(kRB == 1 ? R : kRB == 2 ? R / 2 : 0)>(to_code); \
             u32x2 w;                                                                           \
-            w.x = pack_e4m3x4(acc[0][R] * f, acc[1][R] * f, acc[2][R] * f, acc[3][R] * f);     \
-            w.y = pack_e4m3x4(acc[4][R] * f, acc[5][R] * f, acc[6][R] * f, acc[7][R] * f);     \
+            w.x = pack_fp8x4<kFormat>(acc[0][R] * f, acc[1][R] * f, acc[2][R] * f, acc[3][R] * f); \
+            w.y = pack_fp8x4<kFormat>(acc[4][R] * f, acc[5][R] * f, acc[6][R] * f, acc[7][R] * f); \
             const int unit = unit_of_row<kRB>(4 * g + R);                                      \
             const int blk = kSub == 1 ? unit / kRB : unit * kSub + n16 / (16 / kSub);          \
             const int word = kSub == 1 ? 16 * (unit % kRB) + n16 : n16 % (16 / kSub);          \
@@ -351,10 +354,10 @@ struct CompressLane {
 // words).  Block size B = 128 kRB / kSub (at most one of kRB, kSub differs from 1).
 // Workgroup w (one wave) handles the kTiles consecutive tiles starting at w * kTiles; all its
 // loads are issued before the first tile is processed.
-template <int kRB, int kSub, int kTiles, bool kInterleaved>
+template <int kRB, int kSub, int kTiles, bool kInterleaved, int kFormat = 0>
 __global__ __launch_bounds__(64) void compress_mfma_kernel(
     const u32x4* __restrict__ x, int64_t n_tiles, float tau, float eps,
-    u32x2* __restrict__ payload, f32x2* __restrict__ scales) {
+    u32x2* __restrict__ payload, f32x2* __restrict__ scales, bool rescale = true) {
     __shared__ uint32_t lds[kCompressLdsDwords];
     const int lane = threadIdx.x;
     const int64_t first_tile = static_cast<int64_t>(blockIdx.x) * kTiles;
@@ -383,7 +386,7 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
             for (int c = 0; c < 4; ++c) lds[wr_base + cp * 528 + 4 * c] = stage[p][cp][c];
         }
         wave_lds_sync();
-        cl.template tile_from_lds<kInterleaved>(lds, tile, tau, eps, payload, scales);
+        cl.template tile_from_lds<kInterleaved, kFormat>(lds, tile, tau, eps, rescale, payload, scales);
     }
 }
 
@@ -405,10 +408,10 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
 // bf16-rounded sum (the receive side of the reduce-scatter feeding the send side of the
 // all-gather, Section 4.4.2): the finished tile goes to LDS in the compress stage's layout
 // instead of HBM, and `out` is unused.
-template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kWaves = 1>
+template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kWaves = 1, int kFormat = 0>
 __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
     PayloadTable tab, int k, int64_t n_tiles, int tiles_per_wave, u32x4* __restrict__ out,
-    float tau, float eps, u32x2* __restrict__ payload_out, f32x2* __restrict__ scales_out) {
+    float tau, float eps, u32x2* __restrict__ payload_out, f32x2* __restrict__ scales_out, bool rescale = true) {
     static_assert((kRB == 1 || kRB == 2 || kRB == 4) && (kSub == 1 || kSub == 2 || kSub == 4) && (kRB == 1 || kSub == 1),
                   "block size must be 32, 64, 128, 256 or 512");
     constexpr int kBlock = 128 * kRB / kSub;
@@ -554,8 +557,9 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
                 i32x8 bv;
 #pragma unroll
                 for (int w = 0; w < 8; ++w) bv[w] = hb[nt][w];
+                // A operand format: 0 = E4M3 codes, 1 = E5M2 codes; the +-1 entries of B stay E4M3.
                 d[nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                    av, bv, f32x4{0.0f, 0.0f, 0.0f, 0.0f}, 0, 0, 0, 0, 0, 0);
+                    av, bv, f32x4{0.0f, 0.0f, 0.0f, 0.0f}, kFormat, 0, 0, 0, 0, 0);
             }
             // Row r of this lane belongs to the block whose factor quad lane r computed.
             const float f0 = dpp_f32<kDppQuadBcast(0)>(factor), f1 = dpp_f32<kDppQuadBcast(1)>(factor);
@@ -597,7 +601,7 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
                 }
                 if (kRecompress) {
                     wave_lds_sync();
-                    cl.template tile_from_lds<kInterleaved>(lds_c, tile, tau, eps, payload_out, scales_out);
+                    cl.template tile_from_lds<kInterleaved, kFormat>(lds_c, tile, tau, eps, rescale, payload_out, scales_out);
                 }
                 i = 0;
                 ++tile;

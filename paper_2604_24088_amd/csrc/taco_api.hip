@@ -34,6 +34,15 @@ int device_cus() {
     return v;
 }
 
+// The matrix-core kernels implement the method itself and the variants that keep its structure
+// (rotation and post-rotation scale on, an 8-bit float code book): the full method and the
+// "standard Hadamard" ablation (no adaptive rescaling), in E4M3 or E5M2.  Everything else runs on
+// the butterfly kernels.
+bool mfma_capable(const taco_params* p) {
+    return (p->mode == TACO_MODE_FULL || p->mode == (TACO_MODE_ROTATE | TACO_MODE_POSTSCALE)) &&
+           (p->format == TACO_FORMAT_E4M3 || p->format == TACO_FORMAT_E5M2);
+}
+
 int check_common(int64_t rows, int64_t cols, const taco_params* p, int64_t* n_out) {
     if (!p) return TACO_ERR_NULL;
     if (rows <= 0 || cols <= 0) return TACO_ERR_SHAPE;
@@ -43,15 +52,12 @@ int check_common(int64_t rows, int64_t cols, const taco_params* p, int64_t* n_ou
     if (p->mode < 0 || p->mode > TACO_MODE_FULL) return TACO_ERR_MODE;
     if (p->impl != TACO_IMPL_AUTO && p->impl != TACO_IMPL_BUTTERFLY && p->impl != TACO_IMPL_MFMA) return TACO_ERR_IMPL;
     if (p->layout != TACO_LAYOUT_SPLIT && p->layout != TACO_LAYOUT_INTERLEAVED) return TACO_ERR_LAYOUT;
-    // The matrix-core kernels implement the method itself; the ablation variants run on the butterfly kernels.
-    if (p->impl == TACO_IMPL_MFMA && !(p->mode == TACO_MODE_FULL && p->format == TACO_FORMAT_E4M3)) return TACO_ERR_IMPL;
+    if (p->impl == TACO_IMPL_MFMA && !mfma_capable(p)) return TACO_ERR_IMPL;
     *n_out = rows * cols;
     return TACO_OK;
 }
 
-bool use_mfma(const taco_params* p) {
-    return p->impl != TACO_IMPL_BUTTERFLY && p->mode == TACO_MODE_FULL && p->format == TACO_FORMAT_E4M3;
-}
+bool use_mfma(const taco_params* p) { return p->impl != TACO_IMPL_BUTTERFLY && mfma_capable(p); }
 
 taco::Variant variant_of(const taco_params* p) { return taco::Variant{p->mode, p->format}; }
 
@@ -81,12 +87,18 @@ bool params_ok_for_compress(const taco_params* p) {
     return p->tau > 0.0f && p->eps >= 0.0f && std::isfinite(p->tau) && std::isfinite(p->eps);
 }
 
-// Calls f(kRB, kSub, kInterleaved) with the three as compile-time constants.
+// Calls f(kRB, kSub, kInterleaved, kFormat) with the four as compile-time constants.
 template <typename F>
-void dispatch_shape(int block, bool interleaved, F&& f) {
+void dispatch_shape(int block, bool interleaved, int format, F&& f) {
     auto with_layout = [&](auto rb, auto sub) {
-        if (interleaved) f(rb, sub, std::true_type{});
-        else f(rb, sub, std::false_type{});
+        using std::integral_constant;
+        if (format == TACO_FORMAT_E5M2) {
+            if (interleaved) f(rb, sub, std::true_type{}, integral_constant<int, 1>{});
+            else f(rb, sub, std::false_type{}, integral_constant<int, 1>{});
+        } else {
+            if (interleaved) f(rb, sub, std::true_type{}, integral_constant<int, 0>{});
+            else f(rb, sub, std::false_type{}, integral_constant<int, 0>{});
+        }
     };
     using std::integral_constant;
     switch (block) {
@@ -129,21 +141,22 @@ int launch_decode(const taco::PayloadTable& tab, int k, int64_t n, const taco_pa
             const int tiles_per_wave = wide ? 1 : 2;
             const int64_t tiles_per_group = 2;      // either 1 wave x 2 tiles or 2 waves x 1 tile
             const unsigned groups = static_cast<unsigned>((n_tiles + tiles_per_group - 1) / tiles_per_group);
-            dispatch_shape(B, il, [&](auto rb, auto sub, auto layout) {
-                constexpr int kRB = decltype(rb)::value, kSub = decltype(sub)::value;
+            const bool rescale = (p->mode & TACO_MODE_RESCALE) != 0;
+            dispatch_shape(B, il, p->format, [&](auto rb, auto sub, auto layout, auto fmt) {
+                constexpr int kRB = decltype(rb)::value, kSub = decltype(sub)::value, kFmt = decltype(fmt)::value;
                 constexpr bool kIl = decltype(layout)::value;
                 if (recompress)
-                    hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, true, 1>), dim3(groups), dim3(64), 0, st,
-                                       tab, k, n_tiles, tiles_per_wave, static_cast<taco::u32x4*>(nullptr), p->tau, p->eps,
-                                       static_cast<taco::u32x2*>(payload_out), static_cast<taco::f32x2*>(scales_out));
+                    hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, true, 1, kFmt>), dim3(groups), dim3(64),
+                                       0, st, tab, k, n_tiles, tiles_per_wave, static_cast<taco::u32x4*>(nullptr), p->tau, p->eps,
+                                       static_cast<taco::u32x2*>(payload_out), static_cast<taco::f32x2*>(scales_out), rescale);
                 else if (wide)
-                    hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 2>), dim3(groups), dim3(128), 0, st,
-                                       tab, k, n_tiles, tiles_per_wave, static_cast<taco::u32x4*>(out_bf16), 0.0f, 0.0f,
-                                       static_cast<taco::u32x2*>(nullptr), static_cast<taco::f32x2*>(nullptr));
+                    hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 2, kFmt>), dim3(groups), dim3(128),
+                                       0, st, tab, k, n_tiles, tiles_per_wave, static_cast<taco::u32x4*>(out_bf16), 0.0f, 0.0f,
+                                       static_cast<taco::u32x2*>(nullptr), static_cast<taco::f32x2*>(nullptr), true);
                 else
-                    hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 1>), dim3(groups), dim3(64), 0, st,
-                                       tab, k, n_tiles, tiles_per_wave, static_cast<taco::u32x4*>(out_bf16), 0.0f, 0.0f,
-                                       static_cast<taco::u32x2*>(nullptr), static_cast<taco::f32x2*>(nullptr));
+                    hipLaunchKernelGGL((taco::decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 1, kFmt>), dim3(groups), dim3(64),
+                                       0, st, tab, k, n_tiles, tiles_per_wave, static_cast<taco::u32x4*>(out_bf16), 0.0f, 0.0f,
+                                       static_cast<taco::u32x2*>(nullptr), static_cast<taco::f32x2*>(nullptr), true);
             });
             if (int rc = launch_status()) return rc;
         }
@@ -214,11 +227,12 @@ int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_par
             const auto* xin = static_cast<const taco::u32x4*>(x_bf16);
             auto* pout = static_cast<taco::u32x2*>(payload);
             auto* sout = static_cast<taco::f32x2*>(scales);
-            dispatch_shape(B, il, [&](auto rb, auto sub, auto layout) {
-                constexpr int kRB = decltype(rb)::value, kSub = decltype(sub)::value;
+            const bool rescale = (p->mode & TACO_MODE_RESCALE) != 0;
+            dispatch_shape(B, il, p->format, [&](auto rb, auto sub, auto layout, auto fmt) {
+                constexpr int kRB = decltype(rb)::value, kSub = decltype(sub)::value, kFmt = decltype(fmt)::value;
                 constexpr bool kIl = decltype(layout)::value;
-                hipLaunchKernelGGL((taco::compress_mfma_kernel<kRB, kSub, 1, kIl>), dim3(waves), dim3(64), 0, st,
-                                   xin, n_tiles, p->tau, p->eps, pout, sout);
+                hipLaunchKernelGGL((taco::compress_mfma_kernel<kRB, kSub, 1, kIl, kFmt>), dim3(waves), dim3(64), 0, st,
+                                   xin, n_tiles, p->tau, p->eps, pout, sout, rescale);
             });
             if (int rc = launch_status()) return rc;
         }
@@ -334,7 +348,7 @@ const char* taco_strerror(int status) {
         case TACO_ERR_K: return "k must be between 1 and 16";
         case TACO_ERR_FORMAT: return "bad format: must be E4M3, E5M2 or INT8";
         case TACO_ERR_LAUNCH: return "kernel launch failed";
-        case TACO_ERR_IMPL: return "bad kernel selection (the matrix-core kernels run the full method in E4M3 only)";
+        case TACO_ERR_IMPL: return "bad kernel selection (the matrix-core kernels cover modes 7 and 6 in E4M3 or E5M2)";
         case TACO_ERR_PARAM: return "bad parameter: tau must be positive and eps non-negative, both finite";
         case TACO_ERR_LAYOUT: return "bad layout: must be split or interleaved";
         case TACO_ERR_MODE: return "bad mode: must be a combination of the three TACO_MODE_* bits";

@@ -12,7 +12,8 @@ import parity_util as P
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
-VARIANTS = [(7, 0), (6, 0), (4, 0), (2, 0), (3, 0), (0, 0), (5, 0), (1, 0), (7, 1), (4, 1), (0, 1), (7, 2), (4, 2), (6, 2)]
+VARIANTS = [(7, 0), (6, 0), (4, 0), (2, 0), (3, 0), (0, 0), (5, 0), (1, 0), (7, 1), (6, 1), (4, 1), (0, 1), (7, 2), (4, 2),
+            (6, 2)]
 
 
 def to_dev(bits):
@@ -70,6 +71,44 @@ def test_variant_sum_and_layout(oracle, mode, fmt):
     torch.cuda.synchronize()
     gp, gs = P.deinterleave(rec.cpu().numpy(), block)
     assert np.array_equal(gp, sp.cpu().numpy()) and np.array_equal(gs, ss.cpu().numpy())
+
+
+@pytest.mark.parametrize("mode,fmt", [(7, 1), (6, 0), (6, 1)])
+@pytest.mark.parametrize("block,layout", [(64, 0), (128, 1), (256, 0), (512, 1)])
+def test_variants_on_the_matrix_cores(oracle, mode, fmt, block, layout):
+    """The variants the matrix-core kernels cover (E5M2 code book, no adaptive rescaling), forced onto them with
+    impl = MFMA: every entry point against the oracle, k = 8 so that the two-waves-per-workgroup form runs too."""
+    w = W.WORKLOADS["qwen_act"]
+    k, rows = 8, 4                                       # 4 x 5120 elements = 10 tiles per payload
+    xs = [W.generate_rows(w, 0, rows * i, rows) for i in range(k)]
+    n = xs[0].size
+    p = taco.taco_default_params(block=block, mode=mode, fmt=fmt, layout=layout, impl=taco.TACO_IMPL_MFMA)
+    enc = [oracle.compress(x, block=block, mode=mode, fmt=fmt) for x in xs]
+    buf, sc = taco.taco_compress(to_dev(xs[0]), p)
+    torch.cuda.synchronize()
+    gp, gs = P.deinterleave(buf.cpu().numpy(), block) if layout else (buf.cpu().numpy(), sc.cpu().numpy())
+    P.check_scales(gs, enc[0][1], f"mfma mode={mode} fmt={fmt}")
+    P.check_codes(gp, enc[0][0], enc[0][1], block, f"mfma mode={mode} fmt={fmt}", fmt=fmt)
+    if layout:
+        dp, ds = [torch.from_numpy(P.interleave(e[0], e[1], block)).to(DEV) for e in enc], [None] * k
+    else:
+        dp, ds = [torch.from_numpy(e[0]).to(DEV) for e in enc], [torch.from_numpy(e[1]).to(DEV) for e in enc]
+    ref = oracle.decompress_sum([e[0] for e in enc], [e[1] for e in enc], n, block=block, mode=mode, fmt=fmt)
+    out = taco.taco_decompress_sum(dp, ds, xs[0].shape, p)
+    one = taco.taco_decompress(dp[0], ds[0], xs[0].shape, p)
+    fp, fs = taco.taco_decompress_sum_compress(dp, ds, xs[0].shape, p)
+    up, us = taco.taco_compress(out, p)
+    torch.cuda.synchronize()
+    P.check_recon(bits_of(out), ref, block, f"mfma sum mode={mode} fmt={fmt}", min_exact=P.RECON_EXACT_MIN_SUM)
+    P.check_recon(bits_of(one), oracle.decompress(enc[0][0], enc[0][1], n, block=block, mode=mode, fmt=fmt), block,
+                  f"mfma decompress mode={mode} fmt={fmt}", min_exact=P.RECON_EXACT_MIN_SUM)
+    assert torch.equal(fp, up) and (layout == 1 or torch.equal(fs, us))
+    # the other family agrees with the same oracle, so the two agree with each other to the same bar
+    pb = taco.taco_default_params(block=block, mode=mode, fmt=fmt, layout=layout, impl=taco.TACO_IMPL_BUTTERFLY)
+    bb, bs = taco.taco_compress(to_dev(xs[0]), pb)
+    torch.cuda.synchronize()
+    bp, bsc = P.deinterleave(bb.cpu().numpy(), block) if layout else (bb.cpu().numpy(), bs.cpu().numpy())
+    P.check_codes(bp, enc[0][0], enc[0][1], block, f"butterfly mode={mode} fmt={fmt}", fmt=fmt)
 
 
 def test_error_report(oracle, capsys):
