@@ -34,14 +34,14 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
 # WRITE_SIZE runs, scaled by a copy kernel of known size); None until measured.  The summary
 # the number comes from is committed under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    # fetch 393236 KiB + write 208896 KiB per compress launch: profiles/mfma_kernels_large_k8.txt
-    ("large_k8", 128, "auto"): 616582860,
+    # fetch 393250 KiB + write 208896 KiB per compress launch: profiles/mfma_kernels_large_k8.txt
+    ("large_k8", 128, "auto"): 616597437,
 }
 
 
 # Share of time the matrix cores are busy in the dominant kernel (SQ_VALU_MFMA_BUSY_CYCLES over SIMD-cycles,
 # rocprofv3 --pmc run summarised in the same profile); the Hadamard rotation is an MFMA contraction there.
-MEASURED_MFMA_BUSY = {("large_k8", 128, "auto"): 0.205}
+MEASURED_MFMA_BUSY = {("large_k8", 128, "auto"): 0.203}
 
 
 def parse():
