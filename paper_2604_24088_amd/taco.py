@@ -115,7 +115,10 @@ def taco_scales_bytes(n: int, block: int) -> int:
 def _stream_handle(stream) -> int:
     if stream is None:
         stream = torch.cuda.current_stream()
-    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+    try:
+        return stream.cuda_stream
+    except AttributeError:
+        return int(stream)
 
 
 def _check(status: int, where: str):
@@ -132,9 +135,19 @@ def _require(cond: bool, what: str):
         raise ValueError(what)
 
 
+_ESIZE = {torch.uint8: 1, torch.bfloat16: 2, torch.float32: 4}
+
+
 def _check_buffer(t, dtype, min_bytes: int, name: str, device=None):
     """A tensor handed to a kernel: on the GPU, contiguous, of the expected dtype and large enough.  The C entry
-    points see only a pointer, so this is where an undersized buffer is caught before a kernel writes past its end."""
+    points see only a pointer, so this is where an undersized buffer is caught before a kernel writes past its end.
+    One combined test on the hot path; the individual messages are produced only when it fails."""
+    try:
+        if (t.is_cuda and t.dtype is dtype and t.is_contiguous() and t.numel() * _ESIZE[dtype] >= min_bytes
+                and (device is None or t.device == device)):
+            return
+    except AttributeError:
+        pass
     _require(isinstance(t, torch.Tensor) and t.is_cuda, f"{name}: expected a CUDA tensor")
     _require(t.dtype == dtype, f"{name}: expected dtype {dtype}, got {t.dtype}")
     _require(t.is_contiguous(), f"{name}: must be contiguous")
@@ -142,12 +155,21 @@ def _check_buffer(t, dtype, min_bytes: int, name: str, device=None):
     _require(device is None or t.device == device, f"{name}: on {t.device}, expected {device}")
 
 
+def _sizes(n: int, block: int):
+    """(payload bytes, scales bytes) as taco_payload_bytes / taco_scales_bytes give them, without the two library calls."""
+    if n <= 0 or block not in (32, 64, 128, 256, 512):
+        return 0, 0
+    blocks = -(-n // block)
+    return blocks * block, blocks * 8
+
+
 def _check_payload_args(n: int, p: "taco_params", payloads, scales, device):
     il = p.layout == TACO_LAYOUT_INTERLEAVED
-    codes, sc_bytes = taco_payload_bytes(n, p.block), taco_scales_bytes(n, p.block)
+    codes, sc_bytes = _sizes(n, p.block)
     _require(codes > 0, f"bad shape or block size (n = {n}, block = {p.block})")
+    need = codes + (sc_bytes if il else 0)
     for i, t in enumerate(payloads):
-        _check_buffer(t, torch.uint8, codes + (sc_bytes if il else 0), f"payload[{i}]", device)
+        _check_buffer(t, torch.uint8, need, f"payload[{i}]", device)
     if not il:
         for i, t in enumerate(scales):
             _check_buffer(t, torch.float32, sc_bytes, f"scales[{i}]", device)
@@ -155,20 +177,24 @@ def _check_payload_args(n: int, p: "taco_params", payloads, scales, device):
 
 def _alloc_outputs(n: int, p: taco_params, device, payload, scales):
     """Split layout: (codes, scales[n_blocks, 2]).  Interleaved: (one buffer of B + 8 byte records, None)."""
+    if payload is not None and (scales is not None or p.layout == TACO_LAYOUT_INTERLEAVED):
+        return payload, (None if p.layout == TACO_LAYOUT_INTERLEAVED else scales)
+    codes, sc_bytes = _sizes(n, p.block)
+    _require(codes > 0, f"bad shape or block size (n = {n}, block = {p.block})")
     if p.layout == TACO_LAYOUT_INTERLEAVED:
-        if payload is None:
-            payload = torch.empty(taco_payload_bytes(n, p.block) + taco_scales_bytes(n, p.block),
-                                  dtype=torch.uint8, device=device)
-        return payload, None
+        return torch.empty(codes + sc_bytes, dtype=torch.uint8, device=device), None
     if payload is None:
-        payload = torch.empty(taco_payload_bytes(n, p.block), dtype=torch.uint8, device=device)
+        payload = torch.empty(codes, dtype=torch.uint8, device=device)
     if scales is None:
-        scales = torch.empty((taco_scales_bytes(n, p.block) // 8, 2), dtype=torch.float32, device=device)
+        scales = torch.empty((sc_bytes // 8, 2), dtype=torch.float32, device=device)
     return payload, scales
 
 
+_PTR_ARRAYS = {k: ctypes.c_void_p * k for k in range(1, TACO_MAX_K + 1)}
+
+
 def _pointer_array(tensors, k):
-    return (ctypes.c_void_p * max(k, 1))(*[_ptr_or_null(t) for t in tensors])
+    return _PTR_ARRAYS[max(k, 1)](*[None if t is None else t.data_ptr() for t in tensors])
 
 
 def _rows_cols(shape) -> tuple:

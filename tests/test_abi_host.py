@@ -157,3 +157,9 @@ def test_binding_rejects_tensors_that_are_not_gpu_buffers():
         taco.taco_decompress_sum([], [], (4, 512))
     with pytest.raises(ValueError, match="CUDA"):
         taco.taco_debug_copy(x, x.clone())
+
+
+def test_binding_size_formula_matches_the_library():
+    for n in (0, -3, 1, 31, 32, 33, 127, 128, 129, 2048, 2049, 10 ** 9 + 7, 2 ** 40):
+        for b in (16, 32, 64, 100, 128, 256, 512, 1024):
+            assert taco._sizes(n, b) == (taco.taco_payload_bytes(n, b), taco.taco_scales_bytes(n, b)), (n, b)
