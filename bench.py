@@ -11,7 +11,7 @@ Prints ONE JSON line.  `value` counts bf16-equivalent
 bytes: 2N per compressed tensor, 2N per decompressed tensor, k*2N for decompress_sum
 (k tensors decoded); `value_out_basis` counts only bf16 bytes that really cross HBM.
 `calls` times each call inside the step (HIP events between the calls); `calls_back_to_back` times
-16 launches of one call in a row, which is what a kernel costs when the host's launch time (about 8 us
+16 launches of one call in a row, which is what a kernel costs when the host's launch time (6-9 us
 per call through this binding) is not in the way: on the smaller workloads the two differ.
 `mix_yardstick` times memory-only kernels (taco_debug_traffic) that move exactly the bytes of a
 compress and of a decompress_sum call and compute nothing: what the memory system gives that mix.
