@@ -119,20 +119,25 @@ size_t taco_scales_bytes(int64_t n, int32_t block);
 /* Sender side of Algorithm 1 (fused compression kernel, Section 4.4.1).
  *   x_bf16   in   device, rows*cols bf16 values
  *   payload  out  device, taco_payload_bytes(rows*cols, B) bytes
- *   scales   out  device, taco_scales_bytes(rows*cols, B) bytes */
+ *   scales   out  device, taco_scales_bytes(rows*cols, B) bytes
+ * Errors, all found before anything is launched except the last: TACO_ERR_NULL, _SHAPE, _BLOCK,
+ * _FORMAT, _MODE, _IMPL, _LAYOUT, _PARAM (tau, eps), _ALIGN; TACO_ERR_LAUNCH from the runtime. */
 int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_params* p,
                   void* payload, void* scales, void* stream);
 
 /* Receiver side of Algorithm 1 (fused decompression kernel, Section 4.1 / 4.4.1):
  * out = bf16( H (codes * s) / sqrt(B) / alpha ).  tau and eps are ignored.
- *   out_bf16 out  device, rows*cols bf16 values */
+ *   out_bf16 out  device, rows*cols bf16 values
+ * Errors: as taco_compress without TACO_ERR_PARAM. */
 int taco_decompress(const void* payload, const void* scales, int64_t rows, int64_t cols,
                     const taco_params* p, void* out_bf16, void* stream);
 
 /* Receiver side followed by the single local reduction of Section 4.4.2:
  * out = bf16( sum_{i<k} decode(payloads[i], scales[i]) ), accumulated in fp32 with one
  * final rounding.  `payloads` and `scales` are HOST arrays of k device pointers, read
- * during the call (they may be freed as soon as it returns).  k = 1 equals taco_decompress. */
+ * during the call (they may be freed as soon as it returns).  k = 1 equals taco_decompress.
+ * Errors: as taco_decompress, and TACO_ERR_K for k outside 1..TACO_MAX_K; a NULL or misaligned
+ * entry of the arrays is TACO_ERR_NULL / TACO_ERR_ALIGN. */
 int taco_decompress_sum(const void* const* payloads, const void* const* scales, int32_t k,
                         int64_t rows, int64_t cols, const taco_params* p, void* out_bf16,
                         void* stream);
@@ -144,7 +149,8 @@ int taco_decompress_sum(const void* const* payloads, const void* const* scales, 
  *   payloads, scales  in   HOST arrays of k device pointers (as for taco_decompress_sum)
  *   payload_out       out  device, taco_payload_bytes(rows*cols, B) bytes
  *   scales_out        out  device, taco_scales_bytes(rows*cols, B) bytes
- * Outputs must not overlap any input. */
+ * Outputs must not overlap any input.
+ * Errors: as taco_decompress_sum, and TACO_ERR_PARAM (tau and eps are used by the compress half). */
 int taco_decompress_sum_compress(const void* const* payloads, const void* const* scales, int32_t k,
                                  int64_t rows, int64_t cols, const taco_params* p, void* payload_out,
                                  void* scales_out, void* stream);

@@ -356,6 +356,6 @@ const char* taco_strerror(int status) {
     }
 }
 
-const char* taco_version(void) { return "0.2"; }
+const char* taco_version(void) { return "0.3"; }
 
 }  // extern "C"
