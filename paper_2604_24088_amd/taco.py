@@ -323,3 +323,61 @@ def taco_debug_traffic(srcs: Sequence[torch.Tensor], src_chunks: int, dst: torch
                                   _stream_handle(stream))
     _check(st, "taco_debug_traffic")
     return dst
+
+
+class PreparedCall:
+    """An entry point with its arguments checked and marshalled once, for loops that launch the same call on
+    the same buffers many times (static activations buffers, serving loops): `plan(stream)` then costs little more
+    than the bare library call.  The plan keeps references to its tensors, so their storage stays alive; their
+    CONTENTS may change between launches, their addresses may not."""
+
+    def __init__(self, fn, args, keep, where):
+        self._fn, self._args, self._keep, self._where = fn, args, keep, where
+
+    def __call__(self, stream=None):
+        st = self._fn(*self._args, _stream_handle(stream))
+        if st != 0:
+            raise TacoError(st, self._where)
+
+
+def prepare_compress(x, params: Optional[taco_params], payload, scales=None) -> PreparedCall:
+    """taco_compress(x, params, payload, scales) as a PreparedCall; the outputs must be given."""
+    p = params or taco_default_params()
+    _check_buffer(x, torch.bfloat16, 2, "x")
+    rows, cols = _rows_cols(x.shape)
+    _check_payload_args(rows * cols, p, [payload], [scales], x.device)
+    args = (x.data_ptr(), rows, cols, ctypes.byref(p), payload.data_ptr(), _ptr_or_null(scales))
+    return PreparedCall(lib().taco_compress, args, (x, p, payload, scales), "taco_compress")
+
+
+def prepare_decompress_sum(payloads, scales, shape, params: Optional[taco_params], out) -> PreparedCall:
+    """taco_decompress_sum(payloads, scales, shape, params, out) as a PreparedCall (k = 1: taco_decompress)."""
+    p = params or taco_default_params()
+    k = len(payloads)
+    _require(1 <= k <= TACO_MAX_K, f"k = {k}: between 1 and {TACO_MAX_K} payloads")
+    scales = list(scales) if scales is not None else [None] * k
+    _require(k == len(scales), "as many scales as payloads")
+    rows, cols = _rows_cols(tuple(shape))
+    _require(isinstance(payloads[0], torch.Tensor) and payloads[0].is_cuda, "payload[0]: expected a CUDA tensor")
+    _check_payload_args(rows * cols, p, payloads, scales, payloads[0].device)
+    _check_buffer(out, torch.bfloat16, 2 * rows * cols, "out", payloads[0].device)
+    parr, sarr = _pointer_array(payloads, k), _pointer_array(scales, k)
+    args = (parr, sarr, k, rows, cols, ctypes.byref(p), out.data_ptr())
+    return PreparedCall(lib().taco_decompress_sum, args, (list(payloads), scales, p, out, parr, sarr), "taco_decompress_sum")
+
+
+def prepare_decompress_sum_compress(payloads, scales, shape, params: Optional[taco_params], payload_out,
+                                    scales_out=None) -> PreparedCall:
+    """taco_decompress_sum_compress(...) as a PreparedCall; the outputs must be given."""
+    p = params or taco_default_params()
+    k = len(payloads)
+    _require(1 <= k <= TACO_MAX_K, f"k = {k}: between 1 and {TACO_MAX_K} payloads")
+    scales = list(scales) if scales is not None else [None] * k
+    _require(k == len(scales), "as many scales as payloads")
+    rows, cols = _rows_cols(tuple(shape))
+    _require(isinstance(payloads[0], torch.Tensor) and payloads[0].is_cuda, "payload[0]: expected a CUDA tensor")
+    _check_payload_args(rows * cols, p, list(payloads) + [payload_out], scales + [scales_out], payloads[0].device)
+    parr, sarr = _pointer_array(payloads, k), _pointer_array(scales, k)
+    args = (parr, sarr, k, rows, cols, ctypes.byref(p), payload_out.data_ptr(), _ptr_or_null(scales_out))
+    return PreparedCall(lib().taco_decompress_sum_compress, args,
+                        (list(payloads), scales, p, payload_out, scales_out, parr, sarr), "taco_decompress_sum_compress")
