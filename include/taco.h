@@ -2,7 +2,7 @@
  * taco.h - C ABI of the MI355X (gfx950) implementation of the TACO fused FP8
  * compression operator for tensor-parallel intermediate tensors.
  *
- * The operator is the one the TACO paper defines in Section 4 ("Design of TACO"):
+ * The operator is the one the TACO paper defines in Section 4:
  *   - the flattened bf16 tensor is cut into contiguous blocks of B elements
  *     (Section 4.2.2, Eq. ash_partition);
  *   - each block is rescaled by alpha_k = tau / sigma_k, sigma_k its RMS with eps inside
@@ -75,7 +75,7 @@ enum { TACO_FORMAT_E4M3 = 0, TACO_FORMAT_E5M2 = 1, TACO_FORMAT_INT8 = 2 };
 /* Stages of the method, for the paper's component ablations (Section 5.2.2, Section 5.3): a bit
  * mask.  Without RESCALE alpha_k = 1; without ROTATE Z_k = alpha_k G_k; without POSTSCALE s_k = 1
  * and Z_k itself is converted, saturating at +-Q_max.  FULL (7) is the method; 0 is the direct
- * cast, 4 "DS only", 2 the standard Hadamard transform, 3 ASH without DS.  The matrix-core
+ * cast, 4 dual scale only, 2 the standard Hadamard transform, 3 ASH without DS.  The matrix-core
  * kernels cover the variants that keep the method's structure (rotation and post-rotation scale
  * on, i.e. modes 7 and 6, in E4M3 or E5M2); every other variant runs on the butterfly kernels. */
 enum { TACO_MODE_RESCALE = 1, TACO_MODE_ROTATE = 2, TACO_MODE_POSTSCALE = 4, TACO_MODE_FULL = 7 };
@@ -95,7 +95,7 @@ enum { TACO_IMPL_AUTO = 0, TACO_IMPL_BUTTERFLY = 1, TACO_IMPL_MFMA = 2 };
  *                ignored and may be NULL.  Records are 8-byte but not 16-byte aligned. */
 enum { TACO_LAYOUT_SPLIT = 0, TACO_LAYOUT_INTERLEAVED = 1 };
 
-/* Hyper-parameters of Algorithm 1 ("Require" line): block size B, target energy tau,
+/* Hyper-parameters of Algorithm 1 (its input line): block size B, target energy tau,
  * stabiliser eps; Q_max follows from the format. */
 typedef struct taco_params {
     int32_t block;  /* B: 32, 64, 128, 256 or 512                                  */

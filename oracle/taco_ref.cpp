@@ -30,7 +30,7 @@
 //   * A block whose rotated maximum is zero stores s_k = 0 and all-zero codes.
 //   * The last block is zero padded when N is not a multiple of B; sigma still divides by B.
 //   * The reduction of k decoded payloads accumulates in double, payload index ascending,
-//     and rounds once to bf16 (via binary32), Section 4.4.2 "single local reduction".
+//     and rounds once to bf16 (via binary32), the one local reduction of Section 4.4.2.
 //
 // Ablation variants (Section 5.3 "Ablation Study", Section 5.2.2 "Component-wise Analysis"): the
 // same pipeline with a stage switched off or another code book.  `mode` is a bit mask

@@ -3,7 +3,7 @@
 
 The oracle cannot be run over gigabytes inside a test, so it is run on SAMPLED tiles (groups
 of 16 consecutive blocks, including the first and the last of the tensor): blocks are
-independent (Algorithm 1, "for each block in parallel"), so the oracle's result for a block
+independent (Algorithm 1 loops over them in parallel), so the oracle's result for a block
 does not depend on the rest of the tensor.
 
   compress         GPU output at the sampled tiles against the oracle on the same inputs.
