@@ -34,10 +34,11 @@ def test_variant_parity(oracle, mode, fmt, block, name):
     p = taco.taco_default_params(block=block, mode=mode, fmt=fmt)
     payload, scales = taco.taco_compress(to_dev(x), p)
     torch.cuda.synchronize()
-    rp, rs = oracle.compress(x, block=block, mode=mode, fmt=fmt)
+    rp, rs, z = oracle.compress(x, block=block, mode=mode, fmt=fmt, want_z=True)
     P.check_scales(scales.cpu().numpy(), rs, f"mode={mode} fmt={fmt}")
+    # every differing code must sit on a rounding tie of the oracle's Z / s (z=z), whatever the share
     P.check_codes(payload.cpu().numpy(), rp, rs, block, f"mode={mode} fmt={fmt}", fmt=fmt,
-                  min_match=P.CODE_MATCH_MIN if mode & 2 else P.CODE_MATCH_MIN_UNROTATED)
+                  min_match=P.CODE_MATCH_MIN if mode & 2 else P.CODE_MATCH_MIN_UNROTATED, z=z)
     ref = oracle.decompress(rp, rs, n, block=block, mode=mode, fmt=fmt)
     out = taco.taco_decompress(torch.from_numpy(rp).to(DEV), torch.from_numpy(rs).to(DEV), x.shape, p)
     torch.cuda.synchronize()
@@ -84,11 +85,12 @@ def test_variants_on_the_matrix_cores(oracle, mode, fmt, block, layout):
     n = xs[0].size
     p = taco.taco_default_params(block=block, mode=mode, fmt=fmt, layout=layout, impl=taco.TACO_IMPL_MFMA)
     enc = [oracle.compress(x, block=block, mode=mode, fmt=fmt) for x in xs]
+    z0 = oracle.compress(xs[0], block=block, mode=mode, fmt=fmt, want_z=True)[2]
     buf, sc = taco.taco_compress(to_dev(xs[0]), p)
     torch.cuda.synchronize()
     gp, gs = P.deinterleave(buf.cpu().numpy(), block) if layout else (buf.cpu().numpy(), sc.cpu().numpy())
     P.check_scales(gs, enc[0][1], f"mfma mode={mode} fmt={fmt}")
-    P.check_codes(gp, enc[0][0], enc[0][1], block, f"mfma mode={mode} fmt={fmt}", fmt=fmt)
+    P.check_codes(gp, enc[0][0], enc[0][1], block, f"mfma mode={mode} fmt={fmt}", fmt=fmt, z=z0)
     if layout:
         dp, ds = [torch.from_numpy(P.interleave(e[0], e[1], block)).to(DEV) for e in enc], [None] * k
     else:
@@ -108,7 +110,7 @@ def test_variants_on_the_matrix_cores(oracle, mode, fmt, block, layout):
     bb, bs = taco.taco_compress(to_dev(xs[0]), pb)
     torch.cuda.synchronize()
     bp, bsc = P.deinterleave(bb.cpu().numpy(), block) if layout else (bb.cpu().numpy(), bs.cpu().numpy())
-    P.check_codes(bp, enc[0][0], enc[0][1], block, f"butterfly mode={mode} fmt={fmt}", fmt=fmt)
+    P.check_codes(bp, enc[0][0], enc[0][1], block, f"butterfly mode={mode} fmt={fmt}", fmt=fmt, z=z0)
 
 
 def test_error_report(oracle, capsys):

@@ -65,11 +65,11 @@ def test_full_size_workload(oracle, name, B):
         del xd
         # --- compress parity on the sampled tiles
         x_s = gather_tiles(host.reshape(-1), tiles, TILE)
-        rp, rs = oracle.compress(x_s, block=B)
+        rp, rs, z = oracle.compress(x_s, block=B, want_z=True)
         gp = gather_tiles(pl.cpu().numpy(), tiles, TILE)
         gs = gather_tiles(sc.cpu().numpy().reshape(-1), tiles, 2 * per_tile).reshape(-1, 2)
         worst_alpha, worst_s = P.check_scales(gs, rs, f"{name}/B{B}[{i}]")
-        match = P.check_codes(gp, rp, rs, B, f"{name}/B{B}[{i}]")
+        match = P.check_codes(gp, rp, rs, B, f"{name}/B{B}[{i}]", z=z)
         print(f"[{name}/B{B}] payload {i}: compress parity ok, {match:.6f} of sampled codes identical, "
               f"worst relative error alpha {worst_alpha:.2e}, s {worst_s:.2e}", flush=True)
         # --- patch the oracle's payload into the sampled tiles for the decode test

@@ -52,6 +52,7 @@ def test_random_case(oracle, block, n, k, layout, impl, kind, seed):
     p = taco.taco_default_params(block=block, impl=impl, layout=layout)
     xs = [make_input(n, kind, rng) for _ in range(k)]
     enc = [oracle.compress(x, block=block) for x in xs]
+    z0 = oracle.compress(xs[0], block=block, want_z=True)[2]
     pad8 = np.zeros((-n) % 8, dtype=np.uint16)
     # compress
     buf, sc = taco.taco_compress(torch.from_numpy(np.concatenate([xs[0], pad8]).view(np.int16)).to(DEV).view(torch.bfloat16)[:n], p)
@@ -60,8 +61,10 @@ def test_random_case(oracle, block, n, k, layout, impl, kind, seed):
     P.check_scales(gs, enc[0][1], what)
     # Sparse inputs (kind 3) leave rotated values that are sums of a handful of bf16 numbers, and their
     # ratios to the block maximum hit rounding ties exactly far more often than dense data does: the
-    # share of identical codes is lower there, the one-code bound is not.
-    P.check_codes(gp, enc[0][0], enc[0][1], block, what, min_match=0.999 if kind == 3 else P.CODE_MATCH_MIN)
+    # share of identical codes is lower there, the one-code bound is not; z=z0 makes check_codes assert that
+    # every differing code does sit on such a tie of the oracle's own Z / s.
+    P.check_codes(gp, enc[0][0], enc[0][1], block, what, min_match=P.CODE_MATCH_MIN_SPARSE if kind == 3 else P.CODE_MATCH_MIN,
+                  z=z0)
     # decompress_sum of the oracle's payloads
     if layout:
         dp = [torch.from_numpy(P.interleave(e[0], e[1], block)).to(DEV) for e in enc]
