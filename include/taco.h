@@ -19,8 +19,10 @@
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller; the library allocates
  *     nothing, keeps no state and never synchronises.  `stream` is a hipStream_t (NULL =
- *     the default stream); each call enqueues its kernels on it and returns.
- *   - Inputs and outputs must not overlap.  Data pointers must be 16-byte aligned.
+ *     the default stream); each call enqueues exactly ONE kernel on it and returns.
+ *   - Outputs must not overlap inputs or each other: the byte ranges are compared on the host
+ *     and an overlap is TACO_ERR_OVERLAP before anything is launched (inputs may overlap or
+ *     repeat one another).  Data pointers must be 16-byte aligned.
  *   - A tensor of `rows` x `cols` bf16 values is row-major and is treated as the flat
  *     vector of n = rows*cols elements; blocks may straddle rows.  When n is not a
  *     multiple of B the last block is zero padded (sigma still divides by B).
@@ -37,7 +39,11 @@
  *     leaves the range of normal fp32 numbers (|x| up to about 2^60 and down to 2^-60 are
  *     tested): the kernels work in fp32.
  *   - Return value: TACO_OK (0) or a negative taco_status.  Argument errors are found on
- *     the host before anything is launched.
+ *     the host before anything is launched.  TACO_ERR_LAUNCH is the result of this call's own
+ *     launch; an error left on the thread by earlier, unrelated work is neither reported nor
+ *     cleared.
+ *   - A tensor has at most 2^36 elements (one launch covers it with one workgroup per 2048
+ *     elements).
  */
 #ifndef TACO_H_
 #define TACO_H_
@@ -49,22 +55,27 @@
 extern "C" {
 #endif
 
-#define TACO_MAX_K 16 /* most payloads one taco_decompress_sum call can add */
+#define TACO_MAX_K 16               /* most payloads one taco_decompress_sum call can add        */
+#define TACO_MAX_BATCH 32           /* most tensors one batched call can take                     */
+#define TACO_MAX_BATCH_PAYLOADS 128 /* most payloads of all tensors of a batched decode together  */
 
 typedef enum taco_status {
     TACO_OK = 0,
     TACO_ERR_NULL = -1,   /* a required pointer is NULL                               */
-    TACO_ERR_SHAPE = -2,  /* rows <= 0, cols <= 0 or rows*cols overflows 2^40        */
+    TACO_ERR_SHAPE = -2,  /* rows <= 0, cols <= 0 or rows*cols above 2^36             */
     TACO_ERR_BLOCK = -3,  /* block is not one of 32, 64, 128, 256, 512                */
     TACO_ERR_ALIGN = -4,  /* a data pointer is not 16-byte aligned                    */
     TACO_ERR_K = -5,      /* k outside 1..TACO_MAX_K                                  */
     TACO_ERR_FORMAT = -6, /* params->format is not one of TACO_FORMAT_*               */
-    TACO_ERR_LAUNCH = -7, /* the HIP runtime refused the launch (hipGetLastError)     */
+    TACO_ERR_LAUNCH = -7, /* the HIP runtime refused this call's launch               */
     TACO_ERR_IMPL = -8,   /* params->impl is not one of TACO_IMPL_*, or MFMA was forced
                              for an ablation variant                                  */
     TACO_ERR_PARAM = -9,  /* tau <= 0, eps < 0, or a non-finite parameter             */
     TACO_ERR_LAYOUT = -10,/* params->layout is not one of TACO_LAYOUT_*               */
-    TACO_ERR_MODE = -11   /* params->mode is outside 0..TACO_MODE_FULL                */
+    TACO_ERR_MODE = -11,  /* params->mode is outside 0..TACO_MODE_FULL                */
+    TACO_ERR_OVERLAP = -12,/* an output buffer overlaps an input or another output    */
+    TACO_ERR_BATCH = -13  /* count outside 1..TACO_MAX_BATCH, or count * k above
+                             TACO_MAX_BATCH_PAYLOADS                                  */
 } taco_status;
 
 /* Code book.  E4M3 is the method's (chosen by the paper's format ablation, Section 5.3); E5M2
@@ -77,13 +88,14 @@ enum { TACO_FORMAT_E4M3 = 0, TACO_FORMAT_E5M2 = 1, TACO_FORMAT_INT8 = 2 };
  * and Z_k itself is converted, saturating at +-Q_max.  FULL (7) is the method; 0 is the direct
  * cast, 4 dual scale only, 2 the standard Hadamard transform, 3 ASH without DS.  The matrix-core
  * kernels cover the variants that keep the method's structure (rotation and post-rotation scale
- * on, i.e. modes 7 and 6, in E4M3 or E5M2); every other variant runs on the butterfly kernels. */
+ * on, i.e. modes 7 and 6, with any of the three code books); every other variant runs on the
+ * butterfly kernels. */
 enum { TACO_MODE_RESCALE = 1, TACO_MODE_ROTATE = 2, TACO_MODE_POSTSCALE = 4, TACO_MODE_FULL = 7 };
 
-/* Kernel selection.  AUTO runs whole tiles of 2048 elements on the matrix-core kernels where the
- * variant allows it (see above) and the rest of the tensor on the butterfly kernels; MFMA is AUTO
- * that fails with TACO_ERR_IMPL for a variant the matrix-core kernels do not cover; BUTTERFLY runs
- * everything on the butterfly kernels (kept for tests and benchmarks that compare the two). */
+/* Kernel selection.  AUTO runs the matrix-core kernels where the variant allows it (see above) and
+ * the butterfly kernels otherwise; MFMA is AUTO that fails with TACO_ERR_IMPL for a variant the
+ * matrix-core kernels do not cover; BUTTERFLY runs the butterfly kernels (kept for tests and
+ * benchmarks that compare the two).  Either family handles any n in its one kernel. */
 enum { TACO_IMPL_AUTO = 0, TACO_IMPL_BUTTERFLY = 1, TACO_IMPL_MFMA = 2 };
 
 /* Where the two scalars of a block travel (Section 4.4.2 of the paper places them directly
@@ -155,36 +167,47 @@ int taco_decompress_sum_compress(const void* const* payloads, const void* const*
                                  int64_t rows, int64_t cols, const taco_params* p, void* payload_out,
                                  void* scales_out, void* stream);
 
-/* Diagnostic: converts n device floats to E4M3 codes with the same hardware conversion
- * the compression kernels use (Cvt_FP8 of Eq. quantization), so that it can be compared
- * against a code table.  in_f32: device, n floats; out_codes: device, n bytes. */
-int taco_debug_cvt_e4m3(const void* in_f32, int64_t n, void* out_codes, void* stream);
+/* ---- Several tensors in one launch ------------------------------------------------------------
+ * A launch costs a ramp-up and a drain of a few microseconds whatever it works on, which is a visible
+ * share of the time for tensors of tens of megabytes (Section 4.4.1 counts kernel launches among the
+ * costs that fusion removes; Section 4.4.2 exchanges the tensor in chunks of 64 MB).  The batched
+ * calls run the same kernels over up to TACO_MAX_BATCH tensors (or chunks of one tensor: any row
+ * range of a tensor whose element offset is a multiple of 2048 is a tensor of its own with its
+ * pointers advanced) in ONE kernel.  All tensors of a call share `p`; the results are bit-identical
+ * to the single calls.  The item arrays are HOST arrays, read during the call.
+ * Errors: those of the single calls (the first offending item decides), TACO_ERR_BATCH for count
+ * outside 1..TACO_MAX_BATCH or count * k above TACO_MAX_BATCH_PAYLOADS, and TACO_ERR_OVERLAP if an
+ * output of one item overlaps an input or output of any item. */
+typedef struct taco_compress_item {
+    const void* x_bf16; /* in   device, rows*cols bf16 values                               */
+    int64_t rows, cols;
+    void* payload;      /* out  device, as for taco_compress                                */
+    void* scales;       /* out  device, as for taco_compress (ignored when interleaved)     */
+} taco_compress_item;
 
-/* Diagnostic: plain device-to-device copy of `bytes` bytes (a multiple of 16) with 16-byte
- * loads and stores.  A yardstick for the memory system (reads `bytes`, writes `bytes`) and
- * the known-size kernel that calibrates hardware traffic counters.  src, dst: device. */
-int taco_debug_copy(const void* src, void* dst, int64_t bytes, void* stream);
+typedef struct taco_decode_item {
+    const void* const* payloads; /* in   HOST array of k device pointers                    */
+    const void* const* scales;   /* in   HOST array of k device pointers (or NULL when interleaved) */
+    int64_t rows, cols;
+    void* out_bf16;              /* out  device, rows*cols bf16 values                      */
+} taco_decode_item;
 
-/* Diagnostic: the memory traffic of the operator without its arithmetic, as a yardstick for
- * what the memory system gives a kernel with that mix of reads and writes (Section 4.4.1 puts the
- * cost of the method in its passes over memory).  For each of n_tiles tiles one wave reads
- * src_chunks 16-byte words from each of the k sources (tile t of source i starts at byte
- * t * src_chunks * 16 of srcs[i]) and writes dst_chunks 16-byte words (tile t at byte
- * t * dst_chunks * 16 of dst); the written words are XORs of the loaded ones.  With tiles of 2048
- * elements and block 128: compress is k = 1, src_chunks = 256 (4 KiB of bf16), dst_chunks = 136
- * (2048 codes + 16 pairs of scalars); decompress_sum is k sources of 136 chunks, dst_chunks = 256.
- * srcs: host array of k device pointers, each at least n_tiles * src_chunks * 16 bytes; dst:
- * device, n_tiles * dst_chunks * 16 bytes; 1 <= k <= TACO_MAX_K; 1 <= src_chunks, dst_chunks <= 256.
- * Errors: TACO_ERR_NULL, TACO_ERR_K, TACO_ERR_SHAPE (chunk counts or n_tiles out of range),
- * TACO_ERR_ALIGN, TACO_ERR_LAUNCH. */
-int taco_debug_traffic(const void* const* srcs, int32_t k, int32_t src_chunks, void* dst,
-                       int32_t dst_chunks, int64_t n_tiles, void* stream);
+int taco_compress_batch(const taco_compress_item* items, int32_t count, const taco_params* p, void* stream);
+
+/* Every item adds k payloads (the same k for all items; k = 1 is taco_decompress). */
+int taco_decompress_sum_batch(const taco_decode_item* items, int32_t count, int32_t k, const taco_params* p,
+                              void* stream);
 
 /* Text for a taco_status value (static storage, never NULL). */
 const char* taco_strerror(int status);
 
 /* Library version, "major.minor". */
 const char* taco_version(void);
+
+/* Identifies the sources the library was built from: a hexadecimal digest of the kernel, host and
+ * header files, fixed at compile time (static storage).  A build system or a benchmark can compare
+ * it with the digest of the sources in front of it to detect a stale binary. */
+const char* taco_build_id(void);
 
 #ifdef __cplusplus
 }

@@ -2,9 +2,12 @@
 // They serve the part of a tensor that does not fill a whole tile of the matrix-core kernels, the
 // run-time selectable ablation variants, and impl = BUTTERFLY as a second, independent family.
 //
-// A wave works on a GROUP of 512 consecutive elements = 512 / B whole blocks: lane L holds the
-// eight elements 8 L .. 8 L + 7 of the group (one 16-byte load of bf16, one 8-byte load or store
-// of codes), so a block occupies B / 8 neighbouring lanes.  The fast Walsh-Hadamard transform
+// A wave works on a TILE of 2048 consecutive elements (the same unit of work as the matrix-core
+// kernels: one single-wave workgroup per tile, no persistent loop) as four GROUPS of 512 elements =
+// 512 / B whole blocks each: lane L holds the eight elements 8 L .. 8 L + 7 of a group (one 16-byte
+// load of bf16, one 8-byte load or store of codes), so a block occupies B / 8 neighbouring lanes.
+// The loads of all four groups are issued before the first is used; loads and stores are
+// non-temporal (every byte is touched once).  The fast Walsh-Hadamard transform
 // (Algorithm 1, sender and receiver sides) then splits into three stages between the registers of
 // a lane (strides 1, 2, 4) and log2(B / 8) stages that exchange values between lanes L and L ^ m.
 // The in-place butterfly with stride h maps (a, b) -> (a + b, a - b) for the pair whose indices
@@ -17,10 +20,12 @@
 #pragma once
 
 #include "device_util.h"
+#include "tables.h"
 
 namespace taco {
 
-constexpr int kGroupElems = 512;     // elements per wave iteration of the butterfly kernels
+constexpr int kGroupElems = 512;      // elements whose transform one wave holds in registers at a time
+constexpr int kGroupsPerTile = 4;     // groups per wave: one tile of 2048 elements
 
 // Butterfly between lanes L and L ^ kMask (element stride 8 kMask); nothing when the block is narrower.
 template <int B, int kMask>
@@ -173,7 +178,7 @@ __device__ __forceinline__ u32x2 encode8(const float (&q)[8], const Variant& var
 template <int B>
 __device__ __forceinline__ void compress_group_butterfly(float (&v)[8], int lane, int64_t group, int64_t n_blocks_total,
                                                          float tau, float eps, uint8_t* __restrict__ payload,
-                                                         float2* __restrict__ scales, bool interleaved, Variant var) {
+                                                         f32x2* __restrict__ scales, bool interleaved, Variant var) {
     const LaneSlot<B> slot(group, lane);
     float alpha = 1.0f;
     if (var.rescale()) {
@@ -210,53 +215,59 @@ __device__ __forceinline__ void compress_group_butterfly(float (&v)[8], int lane
         if (!var.postscale() || var.format == 2) q[r] = __builtin_amdgcn_fmed3f(q[r], -qmax, qmax);
     }
     uint8_t* dst = payload + code_offset<B>(slot.blk, interleaved);
-    *reinterpret_cast<u32x2*>(dst + slot.pos) = encode8(q, var);
+    store_stream<true>(reinterpret_cast<u32x2*>(dst + slot.pos), encode8(q, var));
     if (slot.pos == 0) {
-        if (interleaved) *reinterpret_cast<float2*>(dst + B) = make_float2(alpha, s);
-        else scales[slot.blk] = make_float2(alpha, s);
+        if (interleaved) store_stream<true>(reinterpret_cast<f32x2*>(dst + B), f32x2{alpha, s});
+        else store_stream<true>(&scales[slot.blk], f32x2{alpha, s});
     }
 }
 
-// Eight bf16 elements of the group for this lane as floats, zeros past the end of the tensor.
-__device__ __forceinline__ void load_group_elems(const uint16_t* __restrict__ x, int64_t n, int64_t first, float (&v)[8]) {
-    if (first + 8 <= n) {
-        const u32x4 w = *reinterpret_cast<const u32x4*>(x + first);
-        v[0] = bf16_bits_to_f32(w.x & 0xFFFF); v[1] = bf16_bits_to_f32(w.x >> 16);
-        v[2] = bf16_bits_to_f32(w.y & 0xFFFF); v[3] = bf16_bits_to_f32(w.y >> 16);
-        v[4] = bf16_bits_to_f32(w.z & 0xFFFF); v[5] = bf16_bits_to_f32(w.z >> 16);
-        v[6] = bf16_bits_to_f32(w.w & 0xFFFF); v[7] = bf16_bits_to_f32(w.w >> 16);
+// The eight bf16 values of a 16-byte chunk as floats.
+__device__ __forceinline__ void unpack_chunk(u32x4 w, float (&v)[8]) {
+    v[0] = bf16_bits_to_f32(w.x & 0xFFFF); v[1] = bf16_bits_to_f32(w.x >> 16);
+    v[2] = bf16_bits_to_f32(w.y & 0xFFFF); v[3] = bf16_bits_to_f32(w.y >> 16);
+    v[4] = bf16_bits_to_f32(w.z & 0xFFFF); v[5] = bf16_bits_to_f32(w.z >> 16);
+    v[6] = bf16_bits_to_f32(w.w & 0xFFFF); v[7] = bf16_bits_to_f32(w.w >> 16);
+}
+
+// Sender side of Algorithm 1: workgroup w of a tensor (one wave) handles its tile w.
+template <int B, typename Table>
+__global__ __launch_bounds__(64) void compress_butterfly_kernel(Table tab, int count, float tau, float eps,
+                                                                bool interleaved, Variant var) {
+    const int lane = threadIdx.x;
+    int idx;
+    int64_t tile;
+    tab.locate(blockIdx.x, count, idx, tile);
+    const u32x4* __restrict__ x = static_cast<const u32x4*>(tab.x(idx));
+    const int64_t n = tab.n(idx);
+    const int64_t n_blocks_total = (n + B - 1) / B;
+    const int64_t first_elem = tile * (kGroupsPerTile * kGroupElems);
+    u32x4 raw[kGroupsPerTile];
+    if (first_elem + kGroupsPerTile * kGroupElems <= n) {
+#pragma unroll
+        for (int j = 0; j < kGroupsPerTile; ++j) raw[j] = load16<true>(&x[tile * 256 + 64 * j + lane]);
     } else {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) v[r] = first + r < n ? bf16_bits_to_f32(x[first + r]) : 0.0f;   // zero padding
+        for (int j = 0; j < kGroupsPerTile; ++j) raw[j] = load_chunk_guarded(x, first_elem + 8 * (64 * j + lane), n);   // zero padding
     }
-}
-
-// Sender side of Algorithm 1 for the groups [first_group, first_group + n_groups) of 512 elements.
-template <int B>
-__global__ __launch_bounds__(64) void compress_butterfly_kernel(
-    const uint16_t* __restrict__ x, int64_t n, int64_t first_group, int64_t n_groups, float tau,
-    float eps, uint8_t* __restrict__ payload, float2* __restrict__ scales, bool interleaved, Variant var) {
-    const int lane = threadIdx.x;
-    const int64_t n_blocks_total = (n + B - 1) / B;
-    for (int64_t g = first_group + blockIdx.x; g < first_group + n_groups; g += gridDim.x) {
+#pragma unroll
+    for (int j = 0; j < kGroupsPerTile; ++j) {
+        const int64_t group = tile * kGroupsPerTile + j;
+        if (group * kGroupElems >= n) break;
         float v[8];
-        load_group_elems(x, n, g * kGroupElems + 8 * lane, v);
-        compress_group_butterfly<B>(v, lane, g, n_blocks_total, tau, eps, payload, scales, interleaved, var);
+        unpack_chunk(raw[j], v);
+        compress_group_butterfly<B>(v, lane, group, n_blocks_total, tau, eps, static_cast<uint8_t*>(tab.payload(idx)),
+                                    static_cast<f32x2*>(tab.scales(idx)), interleaved, var);
     }
 }
-
-struct PayloadTable {
-    const void* payload[16];
-    const void* scales[16];
-};
 
 // Receiver side of Algorithm 1 plus the local reduction over k payloads for one group; the
 // result (before the final rounding to bf16) is left in v.  The rotation is linear, so for
 // k > 1 the codes are first combined with their block factors s / (alpha sqrt(B)) and rotated
 // once; for k = 1 the raw codes are rotated (exact partial sums) and the factor is applied
 // afterwards.  Lanes whose block lies past the end of the tensor read nothing and carry zeros.
-template <int B>
-__device__ __forceinline__ void decode_sum_group_butterfly(const PayloadTable& tab, int k, int64_t group, int lane,
+template <int B, typename Table>
+__device__ __forceinline__ void decode_sum_group_butterfly(const Table& tab, int idx, int k, int64_t group, int lane,
                                                            int64_t n_blocks_total, float (&v)[8], bool interleaved,
                                                            Variant var) {
     const LaneSlot<B> slot(group, lane);
@@ -268,16 +279,16 @@ __device__ __forceinline__ void decode_sum_group_butterfly(const PayloadTable& t
     // Four payloads at a time, all their loads issued before the first is used.
     for (int i0 = 0; i0 < k; i0 += 4) {
         u32x2 w8[4];
-        float2 sc[4];
+        f32x2 sc[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             w8[j] = u32x2{0, 0};
-            sc[j] = make_float2(1.0f, 0.0f);
+            sc[j] = f32x2{1.0f, 0.0f};
             if (live && i0 + j < k) {
-                const uint8_t* codes = static_cast<const uint8_t*>(tab.payload[i0 + j]) + code_offset<B>(slot.blk, interleaved);
-                sc[j] = interleaved ? *reinterpret_cast<const float2*>(codes + B)
-                                    : static_cast<const float2*>(tab.scales[i0 + j])[slot.blk];
-                w8[j] = *reinterpret_cast<const u32x2*>(codes + slot.pos);
+                const uint8_t* codes = static_cast<const uint8_t*>(tab.payload(idx, k, i0 + j)) + code_offset<B>(slot.blk, interleaved);
+                sc[j] = interleaved ? *reinterpret_cast<const f32x2*>(codes + B)
+                                    : static_cast<const f32x2*>(tab.scales(idx, k, i0 + j))[slot.blk];
+                w8[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(codes + slot.pos));
             }
         }
 #pragma unroll
@@ -299,21 +310,28 @@ __device__ __forceinline__ void decode_sum_group_butterfly(const PayloadTable& t
     for (int r = 0; r < 8; ++r) v[r] *= post;
 }
 
-template <int B>
-__global__ __launch_bounds__(64) void decompress_sum_butterfly_kernel(
-    PayloadTable tab, int k, int64_t n, int64_t first_group, int64_t n_groups,
-    uint16_t* __restrict__ out, bool interleaved, Variant var) {
+// Receiver side of Algorithm 1 and the local reduction: workgroup w of a tensor (one wave) handles its tile w.
+template <int B, typename Table>
+__global__ __launch_bounds__(64) void decompress_sum_butterfly_kernel(Table tab, int count, int k, bool interleaved, Variant var) {
     const int lane = threadIdx.x;
+    int idx;
+    int64_t tile;
+    tab.locate(blockIdx.x, count, idx, tile);
+    const int64_t n = tab.n(idx);
     const int64_t n_blocks_total = (n + B - 1) / B;
-    for (int64_t g = first_group + blockIdx.x; g < first_group + n_groups; g += gridDim.x) {
+    uint16_t* __restrict__ out = static_cast<uint16_t*>(tab.output(idx));
+#pragma unroll
+    for (int j = 0; j < kGroupsPerTile; ++j) {
+        const int64_t g = tile * kGroupsPerTile + j;
+        if (g * kGroupElems >= n) break;
         float v[8];
-        decode_sum_group_butterfly<B>(tab, k, g, lane, n_blocks_total, v, interleaved, var);
+        decode_sum_group_butterfly<B>(tab, idx, k, g, lane, n_blocks_total, v, interleaved, var);
         const int64_t first = g * kGroupElems + 8 * lane;
         if (first + 8 <= n) {
             u32x4 w;
             w.x = pack_bf16x2(v[0], v[1]); w.y = pack_bf16x2(v[2], v[3]);
             w.z = pack_bf16x2(v[4], v[5]); w.w = pack_bf16x2(v[6], v[7]);
-            *reinterpret_cast<u32x4*>(out + first) = w;
+            store_stream<true>(reinterpret_cast<u32x4*>(out + first), w);
         } else {
 #pragma unroll
             for (int r = 0; r < 8; ++r)
@@ -324,76 +342,28 @@ __global__ __launch_bounds__(64) void decompress_sum_butterfly_kernel(
 
 // decompress_sum followed by compress of the bf16-rounded sum, group by group, without the
 // bf16 tensor leaving the registers.
-template <int B>
-__global__ __launch_bounds__(64) void decompress_sum_compress_butterfly_kernel(
-    PayloadTable tab, int k, int64_t n, int64_t first_group, int64_t n_groups, float tau, float eps,
-    uint8_t* __restrict__ payload_out, float2* __restrict__ scales_out, bool interleaved, Variant var) {
+template <int B, typename Table>
+__global__ __launch_bounds__(64) void decompress_sum_compress_butterfly_kernel(Table tab, int count, int k, float tau, float eps,
+                                                                               bool interleaved, Variant var) {
     const int lane = threadIdx.x;
+    int idx;
+    int64_t tile;
+    tab.locate(blockIdx.x, count, idx, tile);
+    const int64_t n = tab.n(idx);
     const int64_t n_blocks_total = (n + B - 1) / B;
-    for (int64_t g = first_group + blockIdx.x; g < first_group + n_groups; g += gridDim.x) {
+#pragma unroll
+    for (int j = 0; j < kGroupsPerTile; ++j) {
+        const int64_t g = tile * kGroupsPerTile + j;
+        if (g * kGroupElems >= n) break;
         float v[8];
-        decode_sum_group_butterfly<B>(tab, k, g, lane, n_blocks_total, v, interleaved, var);
+        decode_sum_group_butterfly<B>(tab, idx, k, g, lane, n_blocks_total, v, interleaved, var);
         const int64_t first = g * kGroupElems + 8 * lane;
 #pragma unroll
         for (int r = 0; r < 8; ++r)
             v[r] = first + r < n ? bf16_bits_to_f32(pack_bf16x2(v[r], 0.0f) & 0xFFFF) : 0.0f;
-        compress_group_butterfly<B>(v, lane, g, n_blocks_total, tau, eps, payload_out, scales_out, interleaved, var);
+        compress_group_butterfly<B>(v, lane, g, n_blocks_total, tau, eps, static_cast<uint8_t*>(tab.payload_output(idx)),
+                                    static_cast<f32x2*>(tab.scales_output(idx)), interleaved, var);
     }
-}
-
-// Hardware float -> E4M3 conversion, one value per thread (diagnostic entry point).
-__global__ void cvt_e4m3_kernel(const float* __restrict__ in, int64_t n, uint8_t* __restrict__ out) {
-    int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (i < n) {
-        const float v = in[i];
-        out[i] = static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_fp8_f32(v, v, 0, false) & 0xFF);
-    }
-}
-
-// Plain copy, 16 bytes per lane, grid-stride (diagnostic entry point).
-__global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t n16) {
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
-    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
-}
-
-// The operator's memory traffic without its arithmetic (diagnostic entry point): wave v reads
-// src_chunks 16-byte words of tile v from each of k sources and writes dst_chunks words of tile v,
-// with the non-temporal loads and stores and the one-shot launch shape of the matrix-core kernels.
-// The written words are XORs of the loaded ones, so no load can be dropped.
-template <int kWaves>
-__global__ __launch_bounds__(64 * kWaves) void traffic_kernel(PayloadTable srcs, int k, int src_chunks,
-                                                              u32x4* __restrict__ dst, int dst_chunks, int64_t n_tiles) {
-    const int lane = threadIdx.x & 63;
-    const int64_t tile = static_cast<int64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6);
-    if (tile >= n_tiles) return;
-    u32x4 acc[4] = {u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
-    for (int i0 = 0; i0 < k; i0 += 4) {
-        u32x4 v[4][4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) v[j][c] = u32x4{0, 0, 0, 0};
-            if (i0 + j < k) {
-                const u32x4* src = static_cast<const u32x4*>(srcs.payload[i0 + j]) + tile * src_chunks;
-#pragma unroll
-                for (int c = 0; c < 4; ++c)
-                    if (64 * c + lane < src_chunks) v[j][c] = load16<true>(&src[64 * c + lane]);
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) acc[c] ^= v[j][c];
-        }
-    }
-    acc[0] ^= acc[2];
-    acc[1] ^= acc[3];
-    acc[2] ^= acc[1];
-    acc[3] ^= acc[0];
-    u32x4* out = dst + tile * dst_chunks;
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-        if (64 * c + lane < dst_chunks) store_stream<true>(&out[64 * c + lane], acc[c]);
 }
 
 }  // namespace taco

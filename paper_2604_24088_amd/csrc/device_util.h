@@ -12,6 +12,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));   // one {alpha, s} rec
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // one 16-byte load / store / LDS slot
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -44,13 +45,31 @@ __device__ __forceinline__ uint32_t pack_e5m2x4(float v0, float v1, float v2, fl
     return static_cast<uint32_t>(w);
 }
 
-// Code book of the matrix-core kernels: 0 = E4M3 (the method), 1 = E5M2 (format ablation).
+// Four floats, each times f, -> four INT8 codes in one dword (round to nearest, ties to even).
+// fma(v, f, 1.5 * 2^23) rounds the EXACT product to an integer in one step (the sum lies in
+// [2^23, 2^24), where fp32 numbers are the integers) and leaves that integer, in two's complement,
+// in the low bits of the result; |v f| <= 127 (1 + 2^-22) by construction, so no clamp is needed.
+__device__ __forceinline__ uint32_t pack_int8x4_scaled(float v0, float v1, float v2, float v3, float f) {
+    constexpr float kMagic = 12582912.0f;
+    const uint32_t b0 = __builtin_bit_cast(uint32_t, __builtin_fmaf(v0, f, kMagic));
+    const uint32_t b1 = __builtin_bit_cast(uint32_t, __builtin_fmaf(v1, f, kMagic));
+    const uint32_t b2 = __builtin_bit_cast(uint32_t, __builtin_fmaf(v2, f, kMagic));
+    const uint32_t b3 = __builtin_bit_cast(uint32_t, __builtin_fmaf(v3, f, kMagic));
+    const uint32_t lo = __builtin_amdgcn_perm(b1, b0, 0x0c0c0400u);    // bytes: b0.0, b1.0, 0, 0
+    const uint32_t hi = __builtin_amdgcn_perm(b3, b2, 0x04000c0cu);    // bytes: 0, 0, b2.0, b3.0
+    return lo | hi;
+}
+
+// Code book of the matrix-core kernels: 0 = E4M3 (the method), 1 = E5M2, 2 = INT8 (format ablation).
+// Byte i of the result = code of v_i * f.
 template <int kFormat>
-__device__ __forceinline__ uint32_t pack_fp8x4(float v0, float v1, float v2, float v3) {
-    return kFormat == 0 ? pack_e4m3x4(v0, v1, v2, v3) : pack_e5m2x4(v0, v1, v2, v3);
+__device__ __forceinline__ uint32_t pack_codes4(float v0, float v1, float v2, float v3, float f) {
+    if (kFormat == 0) return pack_e4m3x4(v0 * f, v1 * f, v2 * f, v3 * f);
+    if (kFormat == 1) return pack_e5m2x4(v0 * f, v1 * f, v2 * f, v3 * f);
+    return pack_int8x4_scaled(v0, v1, v2, v3, f);
 }
 template <int kFormat>
-__device__ __forceinline__ constexpr float format_qmax() { return kFormat == 0 ? 448.0f : 57344.0f; }
+__device__ __forceinline__ constexpr float format_qmax() { return kFormat == 0 ? 448.0f : kFormat == 1 ? 57344.0f : 127.0f; }
 
 // Sum of squares of the two bf16 halves of a dword, added to acc (v_dot2c_f32_bf16).
 // The dword is taken BY VALUE: bit-casting a vector-element lvalue directly reads element 0.
@@ -68,6 +87,18 @@ __device__ __forceinline__ u32x4 load16(const u32x4* p) {
 template <bool kStream, typename T>
 __device__ __forceinline__ void store_stream(T* p, T v) {
     if (kStream) __builtin_nontemporal_store(v, p); else *p = v;
+}
+
+// One 16-byte chunk (8 bf16) whose first element is e0, from a tensor of n elements at x: the part of
+// it that exists, zeros for the rest.  Only the wave that owns a partial last tile comes here.
+__device__ __forceinline__ u32x4 load_chunk_guarded(const u32x4* __restrict__ x, int64_t e0, int64_t n) {
+    if (e0 + 8 <= n) return load16<true>(&x[e0 >> 3]);
+    const uint16_t* xe = reinterpret_cast<const uint16_t*>(x);
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int r = 0; r < 8; ++r)
+        if (e0 + r < n) w[r >> 1] |= static_cast<uint32_t>(xe[e0 + r]) << (16 * (r & 1));
+    return u32x4{w[0], w[1], w[2], w[3]};
 }
 
 __device__ __forceinline__ int parity32(uint32_t v) { return __builtin_popcount(v) & 1; }

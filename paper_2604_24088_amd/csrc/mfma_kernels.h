@@ -12,6 +12,10 @@
 // Everything else (sum of squares, max|W|, the two block scalars, conversion) rides along in
 // the same pass, so each byte of the tensor crosses HBM once.
 //
+// The last tile of a tensor may be partial (n not a multiple of 2048): the wave that owns it reads
+// zeros past the end (the zero padding of the last block, which sigma still divides by B) and
+// stores only the blocks and elements that exist, so every call is ONE kernel whatever n is.
+//
 // A 64-lane wavefront handles one or two consecutive tiles and exits: no persistent loop.  The
 // dispatcher hands out workgroups in index order, so the tiles in flight form one dense,
 // advancing window of memory, which measured ~15 % faster on HBM than a grid-stride loop over the
@@ -35,8 +39,8 @@
 //   B entry                      H[e][p] = (-1)^popcount(e & p)
 #pragma once
 
-#include "butterfly_kernels.h"  // PayloadTable
 #include "device_util.h"
+#include "tables.h"
 
 namespace taco {
 
@@ -234,11 +238,13 @@ struct CompressLane {
     // (measured: 142 us instead of 99 us per compress of the bench tensor).  The tile's records are
     // therefore assembled in LDS (the input buffer is free once the A operands are read) and
     // leave as contiguous 16-byte chunks.
-    // kFormat: 0 = E4M3, 1 = E5M2 (format ablation).  rescale = false is the component ablation
+    // kFormat: 0 = E4M3, 1 = E5M2, 2 = INT8 (format ablation).  rescale = false is the component ablation
     // without the adaptive rescaling ("standard Hadamard" with the post-rotation scale): alpha = 1.
+    // blocks_left: blocks of the tensor from this tile's first block on; only the first
+    // min(blocks_left, kBlocksPerTile) blocks of the tile exist and are stored.
     template <bool kInterleaved, int kFormat>
-    __device__ __forceinline__ void tile_from_lds(uint32_t* lds, int64_t tile, float tau, float eps, bool rescale,
-                                                  u32x2* __restrict__ payload, f32x2* __restrict__ scales) const {
+    __device__ __forceinline__ void tile_from_lds(uint32_t* lds, int64_t tile, int64_t blocks_left, float tau, float eps,
+                                                  bool rescale, u32x2* __restrict__ payload, f32x2* __restrict__ scales) const {
         constexpr float kQ = format_qmax<kFormat>();
         using Layout = PayloadLayout<kBlock, kInterleaved>;
         u32x2* records = reinterpret_cast<u32x2*>(lds);     // interleaved: the tile's records, 8-byte words
@@ -304,7 +310,7 @@ struct CompressLane {
             if (kSub == 2) energy += __shfl_xor(energy, 16, 64);
             energy = __shfl(energy, energy_src, 64);
         }
-        if (owns_scales) {
+        if (owns_scales && my_block < blocks_left) {
             const float alpha = rescale ? tau * __builtin_amdgcn_rsqf(energy * (1.0f / kBlock) + eps) : 1.0f;   // Eq. ash_sigma, ash_alpha
             // max|Z| / Q_max; an all-zero block stores s = 0 whatever alpha is (with eps = 0 it is infinite)
             const float s = wmax > 0.0f ? (wmax * alpha) * (inv_sqrt_block<kBlock>() / kQ) : 0.0f;
@@ -322,13 +328,13 @@ struct CompressLane {
         {                                                                                      \
             const float f = dpp_f32<kDppQuadBcast(kRB == 1 ? R : kRB == 2 ? R / 2 : 0)>(to_code); \
             u32x2 w;                                                                           \
-            w.x = pack_fp8x4<kFormat>(acc[0][R] * f, acc[1][R] * f, acc[2][R] * f, acc[3][R] * f); \
-            w.y = pack_fp8x4<kFormat>(acc[4][R] * f, acc[5][R] * f, acc[6][R] * f, acc[7][R] * f); \
+            w.x = pack_codes4<kFormat>(acc[0][R], acc[1][R], acc[2][R], acc[3][R], f);          \
+            w.y = pack_codes4<kFormat>(acc[4][R], acc[5][R], acc[6][R], acc[7][R], f);          \
             const int unit = unit_of_row<kRB>(4 * g + R);                                      \
             const int blk = kSub == 1 ? unit / kRB : unit * kSub + n16 / (16 / kSub);          \
             const int word = kSub == 1 ? 16 * (unit % kRB) + n16 : n16 % (16 / kSub);          \
             if (kInterleaved) records[Layout::code_word(0, blk, word)] = w;                    \
-            else store_stream<true>(&payload[Layout::code_word(tile, blk, word)], w);         \
+            else if (blk < blocks_left) store_stream<true>(&payload[Layout::code_word(tile, blk, word)], w); \
         }
         TACO_STORE_ROW(0)
         TACO_STORE_ROW(1)
@@ -340,54 +346,57 @@ struct CompressLane {
             const u32x4* chunks = reinterpret_cast<const u32x4*>(lds);
             u32x4* dst = reinterpret_cast<u32x4*>(payload) + tile * Layout::kTileChunks;
             const int lane = 16 * g + n16;
+            // 8-byte words of the tile that exist (records are a whole number of words, not of chunks)
+            const int words = blocks_left >= kBlocksPerTile ? Layout::kTileWords : static_cast<int>(blocks_left) * Layout::kRecordWords;
 #pragma unroll
             for (int c = 0; c < (Layout::kTileChunks + 63) / 64; ++c) {
                 const int chunk = 64 * c + lane;
-                if (chunk < Layout::kTileChunks) store_stream<true>(&dst[chunk], chunks[chunk]);
+                if (2 * chunk + 2 <= words) store_stream<true>(&dst[chunk], chunks[chunk]);
+                else if (2 * chunk + 1 <= words)
+                    store_stream<true>(reinterpret_cast<u32x2*>(&dst[chunk]), u32x2{chunks[chunk].x, chunks[chunk].y});
             }
             wave_lds_sync();
         }
     }
 };
 
-// x: n_tiles * 2048 bf16 (as 16-byte words); payload, scales: see PayloadLayout (payload as 8-byte
-// words).  Block size B = 128 kRB / kSub (at most one of kRB, kSub differs from 1).
-// Workgroup w (one wave) handles the kTiles consecutive tiles starting at w * kTiles; all its
-// loads are issued before the first tile is processed.
-template <int kRB, int kSub, int kTiles, bool kInterleaved, int kFormat = 0>
-__global__ __launch_bounds__(64) void compress_mfma_kernel(
-    const u32x4* __restrict__ x, int64_t n_tiles, float tau, float eps,
-    u32x2* __restrict__ payload, f32x2* __restrict__ scales, bool rescale = true) {
+// tab: the tensors of the launch (tables.h): x = n bf16 values (16-byte aligned); payload, scales: see
+// PayloadLayout.  Block size B = 128 kRB / kSub (at most one of kRB, kSub differs from 1).
+// One wave per workgroup, one tile per wave: workgroup w of a tensor handles its tile w.
+template <int kRB, int kSub, bool kInterleaved, int kFormat, typename Table>
+__global__ __launch_bounds__(64) void compress_mfma_kernel(Table tab, int count, float tau, float eps, bool rescale) {
     __shared__ uint32_t lds[kCompressLdsDwords];
+    constexpr int kBlock = 128 * kRB / kSub;
     const int lane = threadIdx.x;
-    const int64_t first_tile = static_cast<int64_t>(blockIdx.x) * kTiles;
+    int idx;
+    int64_t tile;
+    tab.locate(blockIdx.x, count, idx, tile);
+    const u32x4* __restrict__ x = static_cast<const u32x4*>(tab.x(idx));
+    const int64_t n = tab.n(idx);
+    const int64_t first_elem = tile * kTileElems;
 
-    u32x4 stage[kTiles][4];
+    u32x4 stage[4];
+    if (first_elem + kTileElems <= n) {
 #pragma unroll
-    for (int p = 0; p < kTiles; ++p) {
-        int64_t t = first_tile + p;
-        if (t >= n_tiles) t = n_tiles - 1;      // ragged last wave: re-read a valid tile, result unused
+        for (int c = 0; c < 4; ++c) stage[c] = load16<true>(&x[tile * 256 + 64 * c + lane]);
+    } else {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) stage[p][c] = load16<true>(&x[t * 256 + 64 * c + lane]);
+        for (int c = 0; c < 4; ++c) stage[c] = load_chunk_guarded(x, first_elem + 8 * (64 * c + lane), n);
     }
+    const int64_t blocks_left = (n - first_elem + kBlock - 1) / kBlock;
 
     const CompressLane<kRB, kSub> cl(lane);
     // Writer: load cp covers tile units 4cp .. 4cp+3; this lane holds chunk j = lane % 16 of unit
     // 4cp + lane / 16.  One base address, the rest are immediates (unit + 4 -> + 528 dwords).
     const int wr_base = CompressLane<kRB, kSub>::lds_slot(lane >> 4, lane & 15);
-
 #pragma unroll
-    for (int p = 0; p < kTiles; ++p) {
-        const int64_t tile = first_tile + p;
-        if (tile >= n_tiles) break;
+    for (int cp = 0; cp < 4; ++cp) {
 #pragma unroll
-        for (int cp = 0; cp < 4; ++cp) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) lds[wr_base + cp * 528 + 4 * c] = stage[p][cp][c];
-        }
-        wave_lds_sync();
-        cl.template tile_from_lds<kInterleaved, kFormat>(lds, tile, tau, eps, rescale, payload, scales);
+        for (int c = 0; c < 4; ++c) lds[wr_base + cp * 528 + 4 * c] = stage[cp][c];
     }
+    wave_lds_sync();
+    cl.template tile_from_lds<kInterleaved, kFormat>(lds, tile, blocks_left, tau, eps, rescale,
+                                                     static_cast<u32x2*>(tab.payload(idx)), static_cast<f32x2*>(tab.scales(idx)));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -395,8 +404,8 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
 // ------------------------------------------------------------------------------------------
 
 // out = bf16( sum_i  H_B (codes_i) * s_i / (alpha_i sqrt(B)) ), fp32 accumulation, i ascending.
-// payloads, scales: see PayloadLayout; out: n_tiles * 2048 bf16.
-// Wave v = blockIdx.x * kWaves + wave-in-workgroup handles output tiles
+// tab: the tensors of the launch (tables.h): k payloads (+ scales) each, see PayloadLayout; out: n bf16.
+// Wave v of a tensor (v = workgroup-in-tensor * kWaves + wave-in-workgroup) handles its output tiles
 // [v * tiles_per_wave, (v+1) * tiles_per_wave) and exits; the waves of a workgroup share nothing
 // (each has its own LDS region, there is no workgroup barrier).  A wave's work is the flattened
 // list of (tile, payload) items, payload fastest; a ring of kRing items is kept in flight in
@@ -404,14 +413,18 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(
 // unit times the block factor; the butterfly across units is linear, so it runs once on the
 // accumulated sums.
 //
+// kFormat: 0 = E4M3 and 1 = E5M2 codes go straight into the FP8 matrix instruction (K = 128, one
+// block row per instruction); 2 = INT8 codes into the 8-bit integer one (K = 64, two per row,
+// exact int32 sums).
+//
 // kRecompress = true turns the kernel into decompress_sum followed by compress of the
 // bf16-rounded sum (the receive side of the reduce-scatter feeding the send side of the
 // all-gather, Section 4.4.2): the finished tile goes to LDS in the compress stage's layout
-// instead of HBM, and `out` is unused.
-template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kWaves = 1, int kFormat = 0>
+// instead of HBM.  The payload tile and the bf16 tile use the SAME LDS region: a wave's LDS
+// accesses execute in order, and the payload tile is dead once its A operand has been read.
+template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kWaves, int kFormat, typename Table>
 __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
-    PayloadTable tab, int k, int64_t n_tiles, int tiles_per_wave, u32x4* __restrict__ out,
-    float tau, float eps, u32x2* __restrict__ payload_out, f32x2* __restrict__ scales_out, bool rescale = true) {
+    Table tab, int count, int k, int tiles_per_wave, float tau, float eps, bool rescale) {
     static_assert((kRB == 1 || kRB == 2 || kRB == 4) && (kSub == 1 || kSub == 2 || kSub == 4) && (kRB == 1 || kSub == 1),
                   "block size must be 32, 64, 128, 256 or 512");
     constexpr int kBlock = 128 * kRB / kSub;
@@ -419,13 +432,13 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
     using Layout = PayloadLayout<kBlock, kInterleaved>;
     constexpr int kLoads = kInterleaved ? 3 : 2;                 // 16-byte loads per lane and item
     constexpr int kExtraChunks = Layout::kTileChunks - 128;      // interleaved: chunks left for the third load
-    // Per wave: one tile of the payload (split layout swizzled, interleaved as it is) and, for the
-    // recompress form, the bf16 tile for the compress stage.
-    __shared__ u32x4 lds_all[kWaves][Layout::kTileChunks];
-    __shared__ uint32_t lds_c_all[kWaves][kRecompress ? kCompressLdsDwords : 1];
+    // Per wave: one tile of the payload (split layout swizzled, interleaved as it is); the recompress
+    // form puts the bf16 tile for the compress stage into the same region afterwards.
+    constexpr int kLdsChunks = kRecompress && kCompressLdsDwords / 4 > Layout::kTileChunks ? kCompressLdsDwords / 4 : Layout::kTileChunks;
+    __shared__ u32x4 lds_all[kWaves][kLdsChunks];
     const int wave = kWaves == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     u32x4* lds = lds_all[wave];
-    uint32_t* lds_c = lds_c_all[wave];
+    uint32_t* lds_c = reinterpret_cast<uint32_t*>(lds);
     const int lane = threadIdx.x & 63;
     const int g = lane >> 4;
     const int n16 = lane & 15;
@@ -435,10 +448,21 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
     const int my_block = kSub == 1 ? unit_of_row<kRB>(4 * g + (n16 & 3)) / kRB
                                    : unit_of_row<kRB>(4 * g + (n16 & 3)) * kSub + ph;
 
-    const int64_t tile_begin = (static_cast<int64_t>(blockIdx.x) * kWaves + wave) * tiles_per_wave;
+    int idx;
+    int64_t group;
+    tab.locate(blockIdx.x, count, idx, group);
+    const int64_t n = tab.n(idx);
+    const int64_t n_tiles = (n + kTileElems - 1) / kTileElems;
+    const int64_t n_blocks = (n + kBlock - 1) / kBlock;
+    // The one tile that may be partial, and how many of its blocks exist (-1: every tile is whole).
+    const int64_t partial_tile = (n % kTileElems) != 0 ? n_tiles - 1 : -1;
+    const int partial_blocks = static_cast<int>(n_blocks - (n_tiles - 1) * kBlocksPerTile);
+    u32x4* __restrict__ out = static_cast<u32x4*>(tab.output(idx));
+
+    const int64_t tile_begin = (group * kWaves + wave) * tiles_per_wave;
     int64_t tile_end = tile_begin + tiles_per_wave;
     if (tile_end > n_tiles) tile_end = n_tiles;
-    if (tile_end <= tile_begin) return;      // a wave past the end (last workgroup only)
+    if (tile_end <= tile_begin) return;      // a wave past the end (last workgroup of a tensor only)
     const int n_items = static_cast<int>(tile_end - tile_begin) * k;
 
     // Ring fill.  (pf_tile, pf_i) walks the item list ahead of the consumer.
@@ -447,13 +471,34 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
     int64_t pf_tile = tile_begin;
     int pf_i = 0;
     auto fetch = [&](int p) {
-        const u32x4* src = static_cast<const u32x4*>(tab.payload[pf_i]) + pf_tile * Layout::kTileChunks;
-        stage[p][0] = load16<true>(&src[lane]);
-        stage[p][1] = load16<true>(&src[64 + lane]);
-        if (kInterleaved) {
-            if (lane < kExtraChunks) stage[p][kLoads - 1] = load16<true>(&src[128 + lane]);
+        const u32x4* src = static_cast<const u32x4*>(tab.payload(idx, k, pf_i)) + pf_tile * Layout::kTileChunks;
+        if (pf_tile != partial_tile) {
+            stage[p][0] = load16<true>(&src[lane]);
+            stage[p][1] = load16<true>(&src[64 + lane]);
+            if (kInterleaved) {
+                if (lane < kExtraChunks) stage[p][kLoads - 1] = load16<true>(&src[128 + lane]);
+            } else {
+                stage_sc[p] = static_cast<const f32x2*>(tab.scales(idx, k, pf_i))[pf_tile * kBlocksPerTile + my_block];
+            }
         } else {
-            stage_sc[p] = static_cast<const f32x2*>(tab.scales[pf_i])[pf_tile * kBlocksPerTile + my_block];
+            // Partial last tile: only the records / codes of the blocks that exist are read, zeros elsewhere.
+            const int words = partial_blocks * Layout::kRecordWords;       // 8-byte words of the tile that exist
+#pragma unroll
+            for (int c = 0; c < kLoads; ++c) {
+                const int chunk = 64 * c + lane;
+                u32x4 v = u32x4{0u, 0u, 0u, 0u};
+                if (2 * chunk + 2 <= words) v = load16<true>(&src[chunk]);
+                else if (2 * chunk + 1 <= words) {
+                    const u32x2 h = *reinterpret_cast<const u32x2*>(&src[chunk]);
+                    v = u32x4{h.x, h.y, 0u, 0u};
+                }
+                stage[p][c] = v;
+            }
+            if (!kInterleaved) {
+                stage_sc[p] = f32x2{1.0f, 0.0f};
+                if (my_block < partial_blocks)
+                    stage_sc[p] = static_cast<const f32x2*>(tab.scales(idx, k, pf_i))[pf_tile * kBlocksPerTile + my_block];
+            }
         }
         if (++pf_i == k) { pf_i = 0; ++pf_tile; }
     };
@@ -462,11 +507,14 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
         if (p < n_items) fetch(p);
     }
 
-    // B operand: 8 column tiles of H_128 in E4M3 (+1 = 0x38, -1 = 0xB8), 32 bytes per lane each.
+    // B operand: 8 column tiles of H_128 as +-1 in the code format's companion (E4M3 +1 = 0x38, -1 = 0xB8
+    // for the two FP8 code books; int8 +1 = 0x01, -1 = 0xFF for INT8), 32 bytes per lane each.
     // Slot (m, b) of lane (n16, g) is element e = 64 m + 16 g + b against position p = 8 n16 + nt:
     // sign = parity(b%8 & nt) ^ (b/8 & n16) ^ parity(g & (n16 >> 1)) ^ (m & n16 >> 3).
     // For kSub > 1 the element's block within the unit is eh (top bits of e: m, then g / 2) and the
     // output's is ph: entries with eh != ph are zero and the eh & ph term of the sign drops out.
+    constexpr uint32_t kPlusOne = kFormat == 2 ? 0x01010101u : 0x38383838u;
+    constexpr uint32_t kNegate = kFormat == 2 ? 0xFEu : 0x80u;              // +1 ^ -1, per byte
     uint32_t hb[8][8];
 #pragma unroll
     for (int d = 0; d < 8; ++d) {
@@ -476,14 +524,14 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
         const bool same_block = kSub == 1 || eh == ph;
         int sgn = (b_hi & n16) ^ parity32(g & (n16 >> 1) & 3) ^ (m & (n16 >> 3));
         if (kSub > 1) sgn ^= parity32(eh & ph);
-        const uint32_t lane_sign = (sgn & 1) ? 0x80808080u : 0u;
+        const uint32_t lane_sign = (sgn & 1) ? kNegate * 0x01010101u : 0u;
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) {
-            uint32_t w = 0x38383838u;
+            uint32_t w = kPlusOne;
 #pragma unroll
             for (int bb = 0; bb < 4; ++bb) {
                 const int b_lo = (4 * (d & 3) + bb) & 7;
-                w ^= static_cast<uint32_t>(__builtin_popcount(b_lo & nt) & 1) << (8 * bb + 7);
+                if (__builtin_popcount(b_lo & nt) & 1) w ^= kNegate << (8 * bb);
             }
             hb[nt][d] = same_block ? (w ^ lane_sign) : 0u;
         }
@@ -515,7 +563,6 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
     }
     if (kInterleaved) sc_byte = my_block * Layout::kRecordBytes + kBlock;
     const float inv_root_b = inv_sqrt_block<kBlock>();
-    const CompressLane<kRB, kSub> cl(lane);    // used by the recompress form only
 
     f32x4 sum[8];
     int64_t tile = tile_begin;
@@ -544,22 +591,36 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
                 a1 = lds[rd_slot[1]];
             }
             wave_lds_sync();
-            // Eq. recon_dequant .. recon_rescale: factor s / (alpha sqrt(B)) for this lane's block.
+            // Eq. recon_dequant .. recon_rescale: factor s / (alpha sqrt(B)) for this lane's block; zero for a
+            // block past the end of the tensor (its codes read as zeros, its scalars are not read at all).
             // Taken before the refill below, so that the slot's old scalars are dead when it is issued.
-            const float factor = sc.y * __builtin_amdgcn_rcpf(sc.x) * inv_root_b;
+            float factor = sc.y * __builtin_amdgcn_rcpf(sc.x) * inv_root_b;
+            if (tile == partial_tile && my_block >= partial_blocks) factor = 0.0f;
             if (q + kRing < n_items) fetch(p);      // refill this ring slot
-            i32x8 av;
-            av[0] = a0.x; av[1] = a0.y; av[2] = a0.z; av[3] = a0.w;
-            av[4] = a1.x; av[5] = a1.y; av[6] = a1.z; av[7] = a1.w;
             f32x4 d[8];
+            if (kFormat == 2) {
+                const i32x4 av0 = __builtin_bit_cast(i32x4, a0), av1 = __builtin_bit_cast(i32x4, a1);
 #pragma unroll
-            for (int nt = 0; nt < 8; ++nt) {
-                i32x8 bv;
+                for (int nt = 0; nt < 8; ++nt) {
+                    const i32x4 b0 = {static_cast<int>(hb[nt][0]), static_cast<int>(hb[nt][1]), static_cast<int>(hb[nt][2]), static_cast<int>(hb[nt][3])};
+                    const i32x4 b1 = {static_cast<int>(hb[nt][4]), static_cast<int>(hb[nt][5]), static_cast<int>(hb[nt][6]), static_cast<int>(hb[nt][7])};
+                    i32x4 di = __builtin_amdgcn_mfma_i32_16x16x64_i8(av0, b0, i32x4{0, 0, 0, 0}, 0, 0, 0);
+                    di = __builtin_amdgcn_mfma_i32_16x16x64_i8(av1, b1, di, 0, 0, 0);
+                    d[nt] = f32x4{static_cast<float>(di[0]), static_cast<float>(di[1]), static_cast<float>(di[2]), static_cast<float>(di[3])};
+                }
+            } else {
+                i32x8 av;
+                av[0] = a0.x; av[1] = a0.y; av[2] = a0.z; av[3] = a0.w;
+                av[4] = a1.x; av[5] = a1.y; av[6] = a1.z; av[7] = a1.w;
 #pragma unroll
-                for (int w = 0; w < 8; ++w) bv[w] = hb[nt][w];
-                // A operand format: 0 = E4M3 codes, 1 = E5M2 codes; the +-1 entries of B stay E4M3.
-                d[nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-                    av, bv, f32x4{0.0f, 0.0f, 0.0f, 0.0f}, kFormat, 0, 0, 0, 0, 0);
+                for (int nt = 0; nt < 8; ++nt) {
+                    i32x8 bv;
+#pragma unroll
+                    for (int w = 0; w < 8; ++w) bv[w] = hb[nt][w];
+                    // A operand format: 0 = E4M3 codes, 1 = E5M2 codes; the +-1 entries of B stay E4M3.
+                    d[nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                        av, bv, f32x4{0.0f, 0.0f, 0.0f, 0.0f}, kFormat, 0, 0, 0, 0, 0);
+                }
             }
             // Row r of this lane belongs to the block whose factor quad lane r computed.
             const float f0 = dpp_f32<kDppQuadBcast(0)>(factor), f1 = dpp_f32<kDppQuadBcast(1)>(factor);
@@ -580,6 +641,7 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
             if (++i == k) {
 #pragma unroll
                 for (int nt = 0; nt < 8; ++nt) units_butterfly<kRB>(sum[nt]);
+                const bool whole = tile != partial_tile;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     u32x4 w;
@@ -588,20 +650,47 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
                     w.z = pack_bf16x2(sum[4][r], sum[5][r]);
                     w.w = pack_bf16x2(sum[6][r], sum[7][r]);
                     const int unit = unit_of_row<kRB>(4 * g + r);
+                    // this lane holds elements e0 .. e0 + 7 of the tensor: chunk j = n16 of the unit
+                    const int64_t e0 = tile * kTileElems + unit * 128 + 8 * n16;
                     if (kRecompress) {
-                        // This lane holds elements 8 n16 .. 8 n16 + 7 of the unit: chunk j = n16.
+                        if (!whole) {
+                            // what lies past the end of the tensor is the zero padding of the compress stage
+                            uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                            for (int h = 0; h < 4; ++h) {
+                                if (e0 + 2 * h >= n) ww[h] = 0u;
+                                else if (e0 + 2 * h + 1 >= n) ww[h] &= 0xFFFFu;
+                            }
+                            w = u32x4{ww[0], ww[1], ww[2], ww[3]};
+                        }
                         const int slot = CompressLane<kRB, kSub>::lds_slot(unit, n16);
                         lds_c[slot] = w.x;
                         lds_c[slot + 4] = w.y;
                         lds_c[slot + 8] = w.z;
                         lds_c[slot + 12] = w.w;
+                    } else if (whole || e0 + 8 <= n) {
+                        store_stream<true>(&out[e0 >> 3], w);
                     } else {
-                        store_stream<true>(&out[tile * 256 + unit * 16 + n16], w);
+                        uint16_t* oe = reinterpret_cast<uint16_t*>(out);
+                        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                        for (int h = 0; h < 8; ++h)
+                            if (e0 + h < n) oe[e0 + h] = static_cast<uint16_t>(ww[h >> 1] >> (16 * (h & 1)));
                     }
                 }
                 if (kRecompress) {
                     wave_lds_sync();
-                    cl.template tile_from_lds<kInterleaved, kFormat>(lds_c, tile, tau, eps, rescale, payload_out, scales_out);
+                    // The compress stage's per-lane constants (16 registers of sign tiles among them) are rebuilt for
+                    // every output tile, a few dozen ALU operations, instead of living through the decode loop: with
+                    // them resident the kernel needs more than 256 registers and only one wave fits a SIMD.  The
+                    // empty asm hides the lane number from the optimiser, which would otherwise hoist the constants
+                    // out of the loop again.
+                    int lane_again = lane;
+                    asm volatile("" : "+v"(lane_again));
+                    const CompressLane<kRB, kSub> cl(lane_again);
+                    cl.template tile_from_lds<kInterleaved, kFormat>(lds_c, tile, n_blocks - tile * kBlocksPerTile, tau, eps, rescale,
+                                                                     static_cast<u32x2*>(tab.payload_output(idx)),
+                                                                     static_cast<f32x2*>(tab.scales_output(idx)));
                 }
                 i = 0;
                 ++tile;

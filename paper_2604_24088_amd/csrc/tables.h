@@ -1,0 +1,98 @@
+// Kernel-argument tables: which tensors a launch works on.
+//
+// Every kernel takes its tensors as one table passed BY VALUE in the kernel-argument segment (no
+// device-side pointer table, nothing to allocate or copy).  The ordinary entry points pass a table
+// of one tensor; the batched entry points pass up to kMaxBatch tensors, so that many small tensors
+// (the shards of one exchange, the tensors of several layers) share the ramp-up and the drain of a
+// single launch.  A workgroup finds its tensor with locate(): a scan over the prefix sums of the
+// tensors' workgroup counts, uniform over the workgroup (scalar loads and compares).
+//
+// Tables are indexed directly (tab.item[i]), never through a pointer to a member, so that the
+// compiler reads them with scalar loads from the argument segment and makes no private copy.
+#pragma once
+
+#include <stdint.h>
+
+namespace taco {
+
+constexpr int kMaxK = 16;             // payloads one decode can add (TACO_MAX_K)
+constexpr int kMaxBatch = 32;         // tensors per batched launch (TACO_MAX_BATCH)
+constexpr int kMaxBatchSources = 128; // payloads of all tensors of a batched decode together
+
+// ---- compress: x -> payload, scales -------------------------------------------------------------
+
+struct CompressItem {
+    const void* x;      // n bf16 values
+    void* payload;      // codes (split layout) or records (interleaved)
+    void* scales;       // {alpha, s} records; unused in the interleaved layout
+    int64_t n;          // elements
+};
+
+struct CompressSingle {
+    CompressItem item;
+    // Workgroup wg of the launch -> (tensor index, workgroup index within that tensor).
+    __device__ __forceinline__ void locate(int64_t wg, int /*count*/, int& idx, int64_t& local) const { idx = 0; local = wg; }
+    __device__ __forceinline__ const void* x(int) const { return item.x; }
+    __device__ __forceinline__ void* payload(int) const { return item.payload; }
+    __device__ __forceinline__ void* scales(int) const { return item.scales; }
+    __device__ __forceinline__ int64_t n(int) const { return item.n; }
+};
+
+struct CompressBatch {
+    CompressItem item[kMaxBatch];
+    int64_t first[kMaxBatch + 1];       // first workgroup of tensor i; first[count] = workgroups of the launch
+    __device__ __forceinline__ void locate(int64_t wg, int count, int& idx, int64_t& local) const {
+        int found = 0;
+        for (int i = 1; i < count; ++i)
+            if (wg >= first[i]) found = i;
+        idx = found;
+        local = wg - first[found];
+    }
+    __device__ __forceinline__ const void* x(int i) const { return item[i].x; }
+    __device__ __forceinline__ void* payload(int i) const { return item[i].payload; }
+    __device__ __forceinline__ void* scales(int i) const { return item[i].scales; }
+    __device__ __forceinline__ int64_t n(int i) const { return item[i].n; }
+};
+
+// ---- decode: k payloads (+ scales) -> bf16 sum, or -> re-compressed payload -----------------------
+
+struct DecodeSingle {
+    const void* src_payload[kMaxK];
+    const void* src_scales[kMaxK];
+    void* out;              // n bf16 values (decompress, decompress_sum)
+    void* payload_out;      // re-compressed result (decompress_sum_compress)
+    void* scales_out;
+    int64_t n_elems;
+    __device__ __forceinline__ void locate(int64_t wg, int /*count*/, int& idx, int64_t& local) const { idx = 0; local = wg; }
+    __device__ __forceinline__ const void* payload(int, int /*k*/, int i) const { return src_payload[i]; }
+    __device__ __forceinline__ const void* scales(int, int /*k*/, int i) const { return src_scales[i]; }
+    __device__ __forceinline__ void* output(int) const { return out; }
+    __device__ __forceinline__ void* payload_output(int) const { return payload_out; }
+    __device__ __forceinline__ void* scales_output(int) const { return scales_out; }
+    __device__ __forceinline__ int64_t n(int) const { return n_elems; }
+};
+
+struct DecodeBatch {
+    const void* src_payload[kMaxBatchSources];      // payload i of tensor t at [t * k + i]
+    const void* src_scales[kMaxBatchSources];
+    void* out[kMaxBatch];
+    void* payload_out[kMaxBatch];
+    void* scales_out[kMaxBatch];
+    int64_t n_elems[kMaxBatch];
+    int64_t first[kMaxBatch + 1];
+    __device__ __forceinline__ void locate(int64_t wg, int count, int& idx, int64_t& local) const {
+        int found = 0;
+        for (int i = 1; i < count; ++i)
+            if (wg >= first[i]) found = i;
+        idx = found;
+        local = wg - first[found];
+    }
+    __device__ __forceinline__ const void* payload(int t, int k, int i) const { return src_payload[t * k + i]; }
+    __device__ __forceinline__ const void* scales(int t, int k, int i) const { return src_scales[t * k + i]; }
+    __device__ __forceinline__ void* output(int t) const { return out[t]; }
+    __device__ __forceinline__ void* payload_output(int t) const { return payload_out[t]; }
+    __device__ __forceinline__ void* scales_output(int t) const { return scales_out[t]; }
+    __device__ __forceinline__ int64_t n(int t) const { return n_elems[t]; }
+};
+
+}  // namespace taco

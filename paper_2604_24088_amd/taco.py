@@ -17,20 +17,34 @@ import torch
 from . import build as _build
 
 TACO_MAX_K = 16
+TACO_MAX_BATCH = 32
+TACO_MAX_BATCH_PAYLOADS = 128
 TACO_FORMAT_E4M3, TACO_FORMAT_E5M2, TACO_FORMAT_INT8 = 0, 1, 2
 TACO_MODE_RESCALE, TACO_MODE_ROTATE, TACO_MODE_POSTSCALE, TACO_MODE_FULL = 1, 2, 4, 7
 TACO_IMPL_AUTO, TACO_IMPL_BUTTERFLY, TACO_IMPL_MFMA = 0, 1, 2
 TACO_LAYOUT_SPLIT, TACO_LAYOUT_INTERLEAVED = 0, 1
 
-EXPORTS = ("taco_default_params", "taco_payload_bytes", "taco_scales_bytes", "taco_compress",
-           "taco_decompress", "taco_decompress_sum", "taco_decompress_sum_compress", "taco_debug_cvt_e4m3", "taco_debug_copy", "taco_debug_traffic", "taco_strerror",
-           "taco_version")
+# every symbol include/taco.h declares, then those of include/taco_debug.h
+EXPORTS = ("taco_default_params", "taco_payload_bytes", "taco_scales_bytes", "taco_compress", "taco_decompress",
+           "taco_decompress_sum", "taco_decompress_sum_compress", "taco_compress_batch", "taco_decompress_sum_batch",
+           "taco_strerror", "taco_version", "taco_build_id")
+DEBUG_EXPORTS = ("taco_debug_cvt_e4m3", "taco_debug_copy", "taco_debug_traffic")
 
 
 class taco_params(ctypes.Structure):
     _fields_ = [("block", ctypes.c_int32), ("tau", ctypes.c_float), ("eps", ctypes.c_float),
                 ("format", ctypes.c_int32), ("impl", ctypes.c_int32), ("layout", ctypes.c_int32),
                 ("mode", ctypes.c_int32)]
+
+
+class taco_compress_item(ctypes.Structure):
+    _fields_ = [("x_bf16", ctypes.c_void_p), ("rows", ctypes.c_int64), ("cols", ctypes.c_int64),
+                ("payload", ctypes.c_void_p), ("scales", ctypes.c_void_p)]
+
+
+class taco_decode_item(ctypes.Structure):
+    _fields_ = [("payloads", ctypes.POINTER(ctypes.c_void_p)), ("scales", ctypes.POINTER(ctypes.c_void_p)),
+                ("rows", ctypes.c_int64), ("cols", ctypes.c_int64), ("out_bf16", ctypes.c_void_p)]
 
 
 class TacoError(RuntimeError):
@@ -72,6 +86,13 @@ def lib() -> ctypes.CDLL:
         L.taco_decompress_sum_compress.argtypes = [c.POINTER(c.c_void_p), c.POINTER(c.c_void_p), c.c_int32,
                                                    c.c_int64, c.c_int64, c.POINTER(taco_params),
                                                    c.c_void_p, c.c_void_p, c.c_void_p]
+        L.taco_compress_batch.restype = c.c_int
+        L.taco_compress_batch.argtypes = [c.POINTER(taco_compress_item), c.c_int32, c.POINTER(taco_params), c.c_void_p]
+        L.taco_decompress_sum_batch.restype = c.c_int
+        L.taco_decompress_sum_batch.argtypes = [c.POINTER(taco_decode_item), c.c_int32, c.c_int32, c.POINTER(taco_params),
+                                                c.c_void_p]
+        L.taco_build_id.restype = c.c_char_p
+        L.taco_build_id.argtypes = []
         L.taco_debug_cvt_e4m3.restype = c.c_int
         L.taco_debug_cvt_e4m3.argtypes = [c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p]
         L.taco_debug_copy.restype = c.c_int
@@ -93,6 +114,11 @@ def taco_strerror(status: int) -> str:
 
 def taco_version() -> str:
     return lib().taco_version().decode()
+
+
+def taco_build_id() -> str:
+    """Digest of the sources the loaded library was built from."""
+    return lib().taco_build_id().decode()
 
 
 def taco_default_params(block: int = 128, tau: float = 1.0, eps: float = 1e-12,
@@ -157,7 +183,7 @@ def _check_buffer(t, dtype, min_bytes: int, name: str, device=None):
 
 def _sizes(n: int, block: int):
     """(payload bytes, scales bytes) as taco_payload_bytes / taco_scales_bytes give them, without the two library calls."""
-    if n <= 0 or block not in (32, 64, 128, 256, 512):
+    if n <= 0 or n > (1 << 36) or block not in (32, 64, 128, 256, 512):
         return 0, 0
     blocks = -(-n // block)
     return blocks * block, blocks * 8
@@ -283,6 +309,60 @@ def taco_decompress_sum_compress(payloads: Sequence[torch.Tensor], scales: Seque
                                             _ptr_or_null(scales_out), _stream_handle(stream))
     _check(st, "taco_decompress_sum_compress")
     return payload_out, scales_out
+
+
+def taco_compress_batch(xs: Sequence[torch.Tensor], params: Optional[taco_params] = None,
+                        payloads: Optional[Sequence[torch.Tensor]] = None,
+                        scales: Optional[Sequence[torch.Tensor]] = None, stream=None):
+    """taco_compress of up to TACO_MAX_BATCH tensors in ONE kernel.  Returns (payloads, scales) lists."""
+    p = params or taco_default_params()
+    count = len(xs)
+    _require(1 <= count <= TACO_MAX_BATCH, f"{count} tensors: between 1 and {TACO_MAX_BATCH}")
+    payloads = list(payloads) if payloads is not None else [None] * count
+    scales = list(scales) if scales is not None else [None] * count
+    _require(len(payloads) == count and len(scales) == count, "as many payloads and scales as tensors")
+    items = (taco_compress_item * count)()
+    for i, x in enumerate(xs):
+        _check_buffer(x, torch.bfloat16, 2, f"x[{i}]")
+        rows, cols = _rows_cols(x.shape)
+        payloads[i], scales[i] = _alloc_outputs(rows * cols, p, x.device, payloads[i], scales[i])
+        _check_payload_args(rows * cols, p, [payloads[i]], [scales[i]], xs[0].device)
+        items[i] = taco_compress_item(x.data_ptr(), rows, cols, payloads[i].data_ptr(), _ptr_or_null(scales[i]))
+    st = lib().taco_compress_batch(items, count, ctypes.byref(p), _stream_handle(stream))
+    _check(st, "taco_compress_batch")
+    return payloads, scales
+
+
+def taco_decompress_sum_batch(payloads: Sequence[Sequence[torch.Tensor]], scales, shapes, params: Optional[taco_params] = None,
+                              outs: Optional[Sequence[torch.Tensor]] = None, stream=None):
+    """taco_decompress_sum of up to TACO_MAX_BATCH tensors in ONE kernel: payloads[t] (and scales[t]) are the k
+    payloads of tensor t, the same k for every tensor.  Returns the list of bf16 outputs."""
+    p = params or taco_default_params()
+    count = len(payloads)
+    _require(1 <= count <= TACO_MAX_BATCH, f"{count} tensors: between 1 and {TACO_MAX_BATCH}")
+    k = len(payloads[0])
+    _require(1 <= k <= TACO_MAX_K and count * k <= TACO_MAX_BATCH_PAYLOADS,
+             f"k = {k}: between 1 and {TACO_MAX_K}, and at most {TACO_MAX_BATCH_PAYLOADS} payloads in all")
+    scales = [list(s) if s is not None else [None] * k for s in (scales if scales is not None else [None] * count)]
+    outs = list(outs) if outs is not None else [None] * count
+    _require(len(scales) == count and len(shapes) == count and len(outs) == count, "one scales list, shape and output per tensor")
+    items = (taco_decode_item * count)()
+    keep = []
+    dev = payloads[0][0].device
+    for t in range(count):
+        _require(len(payloads[t]) == k and len(scales[t]) == k, "every tensor needs the same number of payloads")
+        rows, cols = _rows_cols(tuple(shapes[t]))
+        if outs[t] is None:
+            outs[t] = torch.empty(tuple(shapes[t]), dtype=torch.bfloat16, device=dev)
+        _check_payload_args(rows * cols, p, payloads[t], scales[t], dev)
+        _check_buffer(outs[t], torch.bfloat16, 2 * rows * cols, f"out[{t}]", dev)
+        parr, sarr = _pointer_array(payloads[t], k), _pointer_array(scales[t], k)
+        keep.append((parr, sarr))
+        items[t] = taco_decode_item(ctypes.cast(parr, ctypes.POINTER(ctypes.c_void_p)),
+                                    ctypes.cast(sarr, ctypes.POINTER(ctypes.c_void_p)), rows, cols, outs[t].data_ptr())
+    st = lib().taco_decompress_sum_batch(items, count, k, ctypes.byref(p), _stream_handle(stream))
+    _check(st, "taco_decompress_sum_batch")
+    return outs
 
 
 def taco_debug_cvt_e4m3(values: torch.Tensor, stream=None) -> torch.Tensor:

@@ -12,8 +12,8 @@ from paper_2604_24088_amd import taco
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "taco.h")).read()
+def declared_functions(header="taco.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(taco_[a-z0-9_]+)\s*\(", text)))
 
@@ -24,12 +24,23 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(taco.EXPORTS)
     for name in names:
         assert getattr(L, name) is not None, name
+    debug = declared_functions("taco_debug.h")
+    assert set(debug) == set(taco.DEBUG_EXPORTS)          # the diagnostics have a header of their own
+    for name in debug:
+        assert getattr(L, name) is not None, name
+
+
+def test_library_matches_the_sources():
+    """The loaded library was built from the sources on disk (its embedded digest is theirs)."""
+    from paper_2604_24088_amd import build
+    assert taco.taco_build_id() == build.source_digest() == build.library_digest()
+    assert not build.is_stale()
 
 
 def test_version_and_strerror():
     assert re.fullmatch(r"\d+\.\d+", taco.taco_version())
     assert taco.taco_strerror(0) == "ok"
-    for st in range(-11, 0):
+    for st in range(-13, 0):
         assert taco.taco_strerror(st) not in ("ok", "unknown status")
     assert taco.taco_strerror(-100) == "unknown status"
 
@@ -60,12 +71,12 @@ A = 0x1000  # a fake, 16-byte aligned, non-null "device pointer": never derefere
 
 @pytest.mark.parametrize("args,status", [
     (dict(x=0), -1), (dict(payload=0), -1), (dict(scales=0), -1), (dict(p=None), -1),
-    (dict(rows=0), -2), (dict(cols=-4), -2), (dict(rows=1 << 30, cols=1 << 30), -2),
+    (dict(rows=0), -2), (dict(cols=-4), -2), (dict(rows=1 << 30, cols=1 << 30), -2), (dict(rows=1 << 18, cols=(1 << 18) + 1), -2),
     (dict(p=_params(block=96)), -3), (dict(p=_params(block=1024)), -3),
     (dict(x=A + 2), -4), (dict(payload=A + 8), -4), (dict(scales=A + 4), -4),
     (dict(p=_params(format=3)), -6), (dict(p=_params(format=-1)), -6),
     (dict(p=_params(mode=8)), -11), (dict(p=_params(mode=-1)), -11),
-    (dict(p=_params(impl=2, mode=5)), -8), (dict(p=_params(impl=2, mode=3)), -8), (dict(p=_params(impl=2, format=2)), -8),
+    (dict(p=_params(impl=2, mode=5)), -8), (dict(p=_params(impl=2, mode=3)), -8), (dict(p=_params(impl=2, mode=4, format=2)), -8),
     (dict(p=_params(impl=7)), -8), (dict(p=_params(impl=-1)), -8),
     (dict(p=_params(layout=2)), -10), (dict(p=_params(layout=-1)), -10),
     (dict(p=_params(tau=0.0)), -9), (dict(p=_params(eps=-1.0)), -9), (dict(p=_params(tau=float("nan"))), -9),
@@ -76,6 +87,96 @@ def test_compress_rejects_bad_arguments(args, status):
     a.update(args)
     pp = ctypes.byref(a["p"]) if a["p"] is not None else None
     assert L.taco_compress(a["x"], a["rows"], a["cols"], pp, a["payload"], a["scales"], None) == status
+
+
+B0, B1, B2 = 0x100000, 0x200000, 0x300000      # fake pointers far enough apart for a [4, 512] tensor (4 KiB of bf16)
+
+
+@pytest.mark.parametrize("x,payload,scales,layout", [
+    (B0, B0, B1, 0),                    # output = input
+    (B0, B0 + 4080, B1, 0),             # payload starts inside x (x is 4096 bytes)
+    (B0 + 2032, B0, B1, 0),             # x starts inside the payload (2048 bytes)
+    (B0, B1, B1 + 2032, 0),             # scales start inside the payload
+    (B0, B1, B0 + 4080, 0),             # scales start inside x
+    (B0, B0 + 4080, None, 1),           # interleaved records (2176 bytes) start inside x
+    (B0 + 2160, B0, None, 1),           # x starts inside the records
+])
+def test_compress_rejects_overlapping_buffers(x, payload, scales, layout):
+    L = taco.lib()
+    p = _params(layout=layout)
+    assert L.taco_compress(x, 4, 512, ctypes.byref(p), payload, scales, None) == -12
+
+
+def test_decode_rejects_overlapping_buffers():
+    L = taco.lib()
+    p = _params()
+    pl = (ctypes.c_void_p * 2)(B0, B1)
+    sc = (ctypes.c_void_p * 2)(B2, B2 + 0x1000)
+    # out (4096 bytes) over a payload (2048 bytes), over a scales region (128 bytes), just behind them: the last is fine,
+    # so it is given a misaligned out to stop at the NEXT check instead of launching
+    assert L.taco_decompress_sum(pl, sc, 2, 4, 512, ctypes.byref(p), B1 - 4080, None) == -12
+    assert L.taco_decompress_sum(pl, sc, 2, 4, 512, ctypes.byref(p), B2 + 0x1000 + 112, None) == -12
+    assert L.taco_decompress(B0, B2, 4, 512, ctypes.byref(p), B0 + 2032, None) == -12
+    # the fused form: its outputs against the inputs and against each other
+    assert L.taco_decompress_sum_compress(pl, sc, 2, 4, 512, ctypes.byref(p), B1 + 2032, B2 + 0x2000, None) == -12
+    assert L.taco_decompress_sum_compress(pl, sc, 2, 4, 512, ctypes.byref(p), B2 + 0x2000, B2 + 0x2000 + 2032, None) == -12
+    # inputs may repeat or overlap one another: the same payload twice passes the overlap test (and stops at k)
+    same = (ctypes.c_void_p * 2)(B0, B0)
+    assert L.taco_decompress_sum(same, sc, 17, 4, 512, ctypes.byref(p), B1, None) == -5
+
+
+def _compress_items(entries):
+    items = (taco.taco_compress_item * len(entries))()
+    for i, (x, rows, cols, payload, scales) in enumerate(entries):
+        items[i] = taco.taco_compress_item(x, rows, cols, payload, scales)
+    return items
+
+
+def test_compress_batch_rejects_bad_arguments():
+    L = taco.lib()
+    p = _params()
+    ok = [(B0, 4, 512, B1, B2), (B0 + 0x10000, 4, 512, B1 + 0x10000, B2 + 0x10000)]
+    assert L.taco_compress_batch(None, 1, ctypes.byref(p), None) == -1
+    assert L.taco_compress_batch(_compress_items(ok), 0, ctypes.byref(p), None) == -13
+    assert L.taco_compress_batch(_compress_items(ok * 17), 33, ctypes.byref(p), None) == -13
+    assert L.taco_compress_batch(_compress_items(ok), 2, None, None) == -1
+    assert L.taco_compress_batch(_compress_items(ok), 2, ctypes.byref(_params(block=100)), None) == -3
+    assert L.taco_compress_batch(_compress_items(ok), 2, ctypes.byref(_params(tau=0.0)), None) == -9
+    assert L.taco_compress_batch(_compress_items([ok[0], (0, 4, 512, B1, B2)]), 2, ctypes.byref(p), None) == -1
+    assert L.taco_compress_batch(_compress_items([ok[0], (B0 + 0x10000, 0, 512, B1, B2)]), 2, ctypes.byref(p), None) == -2
+    assert L.taco_compress_batch(_compress_items([ok[0], (B0 + 0x10000, 4, 512, B1 + 0x10008, B2 + 0x10000)]), 2, ctypes.byref(p), None) == -4
+    # the second tensor's payload runs into the first tensor's; the second tensor's scales lie over the first one's input
+    assert L.taco_compress_batch(_compress_items([ok[0], (B0 + 0x10000, 4, 512, B1 + 2032, B2 + 0x10000)]), 2, ctypes.byref(p), None) == -12
+    assert L.taco_compress_batch(_compress_items([ok[0], (B0 + 0x10000, 4, 512, B1 + 0x10000, B0 + 16)]), 2, ctypes.byref(p), None) == -12
+
+
+def test_decompress_sum_batch_rejects_bad_arguments():
+    L = taco.lib()
+    p = _params()
+    pl = (ctypes.c_void_p * 2)(B0, B1)
+    sc = (ctypes.c_void_p * 2)(B2, B2 + 0x1000)
+    cast = lambda a: ctypes.cast(a, ctypes.POINTER(ctypes.c_void_p))
+
+    def items(entries):
+        arr = (taco.taco_decode_item * len(entries))()
+        for i, e in enumerate(entries):
+            arr[i] = taco.taco_decode_item(*e)
+        return arr
+
+    good = (cast(pl), cast(sc), 4, 512, B2 + 0x100000)
+    assert L.taco_decompress_sum_batch(None, 1, 2, ctypes.byref(p), None) == -1
+    assert L.taco_decompress_sum_batch(items([good]), 0, 2, ctypes.byref(p), None) == -13
+    assert L.taco_decompress_sum_batch(items([good] * 33), 33, 2, ctypes.byref(p), None) == -13
+    assert L.taco_decompress_sum_batch(items([good] * 9), 9, 16, ctypes.byref(p), None) == -13      # 144 payloads in all
+    assert L.taco_decompress_sum_batch(items([good]), 1, 0, ctypes.byref(p), None) == -5
+    assert L.taco_decompress_sum_batch(items([good]), 1, 17, ctypes.byref(p), None) == -5
+    assert L.taco_decompress_sum_batch(items([good, (cast(pl), cast(sc), 4, 512, 0)]), 2, 2, ctypes.byref(p), None) == -1
+    assert L.taco_decompress_sum_batch(items([good, (None, cast(sc), 4, 512, B2 + 0x200000)]), 2, 2, ctypes.byref(p), None) == -1
+    assert L.taco_decompress_sum_batch(items([good, (cast(pl), cast(sc), -1, 512, B2 + 0x200000)]), 2, 2, ctypes.byref(p), None) == -2
+    assert L.taco_decompress_sum_batch(items([good, (cast(pl), cast(sc), 4, 512, B2 + 0x200004)]), 2, 2, ctypes.byref(p), None) == -4
+    # the second tensor's output over the first tensor's output, and over a payload
+    assert L.taco_decompress_sum_batch(items([good, (cast(pl), cast(sc), 4, 512, B2 + 0x100000 + 4080)]), 2, 2, ctypes.byref(p), None) == -12
+    assert L.taco_decompress_sum_batch(items([good, (cast(pl), cast(sc), 4, 512, B1 + 16)]), 2, 2, ctypes.byref(p), None) == -12
 
 
 @pytest.mark.parametrize("k,status", [(0, -5), (17, -5), (-1, -5)])
@@ -141,6 +242,7 @@ def test_decompress_rejects_bad_arguments():
     assert L.taco_decompress_sum(None, arr, 1, 4, 512, ctypes.byref(p), A, None) == -1
     assert L.taco_debug_cvt_e4m3(0, 4, A, None) == -1
     assert L.taco_debug_cvt_e4m3(A, 0, A, None) == -2
+    assert L.taco_debug_cvt_e4m3(A, (1 << 31) + 1, A, None) == -2
     with pytest.raises(taco.TacoError):
         taco._check(-3, "x")
 
@@ -160,6 +262,6 @@ def test_binding_rejects_tensors_that_are_not_gpu_buffers():
 
 
 def test_binding_size_formula_matches_the_library():
-    for n in (0, -3, 1, 31, 32, 33, 127, 128, 129, 2048, 2049, 10 ** 9 + 7, 2 ** 40):
+    for n in (0, -3, 1, 31, 32, 33, 127, 128, 129, 2048, 2049, 10 ** 9 + 7, 2 ** 36, 2 ** 36 + 1):
         for b in (16, 32, 64, 100, 128, 256, 512, 1024):
             assert taco._sizes(n, b) == (taco.taco_payload_bytes(n, b), taco.taco_scales_bytes(n, b)), (n, b)

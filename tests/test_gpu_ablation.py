@@ -74,10 +74,10 @@ def test_variant_sum_and_layout(oracle, mode, fmt):
     assert np.array_equal(gp, sp.cpu().numpy()) and np.array_equal(gs, ss.cpu().numpy())
 
 
-@pytest.mark.parametrize("mode,fmt", [(7, 1), (6, 0), (6, 1)])
-@pytest.mark.parametrize("block,layout", [(64, 0), (128, 1), (256, 0), (512, 1)])
+@pytest.mark.parametrize("mode,fmt", [(7, 1), (6, 0), (6, 1), (7, 2), (6, 2)])
+@pytest.mark.parametrize("block,layout", [(64, 0), (128, 1), (256, 0), (512, 1), (32, 0)])
 def test_variants_on_the_matrix_cores(oracle, mode, fmt, block, layout):
-    """The variants the matrix-core kernels cover (E5M2 code book, no adaptive rescaling), forced onto them with
+    """The variants the matrix-core kernels cover (E5M2 and INT8 code books, no adaptive rescaling), forced onto them with
     impl = MFMA: every entry point against the oracle, k = 8 so that the two-waves-per-workgroup form runs too."""
     w = W.WORKLOADS["qwen_act"]
     k, rows = 8, 4                                       # 4 x 5120 elements = 10 tiles per payload

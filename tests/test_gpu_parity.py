@@ -135,8 +135,8 @@ def test_compress_ragged_sizes_other_b(oracle, block, n):
 @pytest.mark.parametrize("n", [1, 127, 128, 129, 2047, 2048, 2049, 5 * 2048 + 300, 37 * 2048 + 128 * 5 + 77])
 @pytest.mark.parametrize("impl", ["auto", "butterfly"])
 def test_compress_ragged_sizes(oracle, n, impl):
-    """Whole tiles go to the matrix-core kernel, the remaining blocks and the zero-padded last
-    block to the butterfly kernel."""
+    """Any length in one kernel: the wave that owns the partial last tile reads zeros past the end (the zero
+    padding of the last block) and stores only the blocks that exist."""
     rng = np.random.default_rng(n)
     x = W.float32_to_bf16_bits((rng.standard_normal(n) * 0.02).astype(np.float32))
     padded = np.concatenate([x, np.zeros((-n) % 8, dtype=np.uint16)])   # keep the device buffer 16-byte sized
