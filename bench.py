@@ -3,25 +3,33 @@
 
 One STEP is one pass of the whole hot path over one batch of synthetic input:
     k x taco_compress  ->  taco_decompress (payload 0)  ->  taco_decompress_sum (all k)
-on the `large_k8` workload (bf16 [16384, 12288], k = 8 payloads, block 128): the largest
-single-GPU configuration, and the one whose buffers (3 GiB of inputs) cannot sit in the
-256 MB last-level cache.  Inputs are resident in HBM before the timed region.
+The headline is the `large_k8` workload (bf16 [16384, 12288], k = 8 payloads, block 128): the largest
+single-GPU configuration, and the one whose buffers (3 GiB of inputs) cannot sit in the 256 MB
+last-level cache.  Inputs are resident in HBM before the timed region.
 
-Prints ONE JSON line.  `value` counts bf16-equivalent
-bytes: 2N per compressed tensor, 2N per decompressed tensor, k*2N for decompress_sum
-(k tensors decoded); `value_out_basis` counts only bf16 bytes that really cross HBM.
-`calls` times each call inside the step (HIP events between the calls); `calls_back_to_back` times
-16 launches of one call in a row, which is what a kernel costs when the host's launch time (6-9 us
-per call through this binding) is not in the way: on the smaller workloads the two differ.
-`mix_yardstick` times memory-only kernels (taco_debug_traffic) that move exactly the bytes of a
-compress and of a decompress_sum call and compute nothing: what the memory system gives that mix.
-The roofline object prices the dominant kernel (compress) by its ALGORITHMIC bytes
-(3.0625 B per element at block 128) over its average launch duration, measured with
-HIP events on the launch stream inside the timed region.
+Prints ONE JSON line.  `value` counts bf16-equivalent bytes: 2N per compressed tensor, 2N per
+decompressed tensor, k*2N for decompress_sum (k tensors decoded); `value_out_basis` counts only bf16
+bytes that really cross HBM; `hbm_frac_step` prices the ALGORITHMIC bytes of the whole step.
+`calls` gives the MEDIAN over the timed steps of each call's duration (HIP events between the calls, on
+the launch stream); `calls_back_to_back` times 16 launches of one call in a row, which is what a kernel
+costs when the host's launch time is not in the way.  `workloads` carries the same two measurements for
+every one of the five benchmark configurations (steps rotate through enough buffer sets to defeat the
+last-level cache).  `mix_yardstick` times memory-only kernels (taco_debug_traffic) that move exactly the
+bytes of each call and compute nothing: what the memory system gives that mix.
+The roofline object prices the dominant kernel (compress) by its ALGORITHMIC bytes (3.0625 B per
+element at block 128) over its average launch duration inside the timed region.
+`cpu_baseline` / `cpu_baseline_1thread`: the CPU oracle, as it stands, on a stated sample of the same
+workload with all host threads and with one.
+
+Before the warm-up steps the step loop runs untimed for `--settle-ms` (default 60 ms): from a cold start
+the GPU's power management runs the first two steps at boost clocks, then drops (the decode kernels run
+up to 35 % slower around the third to fifth step) and needs about 25 steps to settle; `--cold-trace N`
+prints that transient (per-step call times from a cold start) instead of the benchmark.
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -37,7 +45,6 @@ MEASURED_TRAFFIC_BYTES = {
     # fetch 393250 KiB + write 208896 KiB per compress launch: profiles/mfma_kernels_large_k8.txt
     ("large_k8", 128, "auto"): 616597437,
 }
-
 
 # Share of time the matrix cores are busy in the dominant kernel (SQ_VALU_MFMA_BUSY_CYCLES over SIMD-cycles,
 # rocprofv3 --pmc run summarised in the same profile); the Hadamard rotation is an MFMA contraction there.
@@ -59,15 +66,36 @@ def parse():
                     help="issue every call in row chunks of about this many MB of bf16 (0 = whole tensor): the overlap "
                          "granularity of Section 4.4.2")
     ap.add_argument("--streams", type=int, default=1, help="streams the chunks are dealt to in turn (with --chunk-mb)")
+    ap.add_argument("--batch", action="store_true",
+                    help="use the batched entry points: the k compress calls of a step, and with --chunk-mb all chunks of a "
+                         "call, go out as ONE launch each")
     ap.add_argument("--rotate", type=int, default=0,
                     help="buffer sets the steps rotate through (0 = as many as it takes, up to 64, for the sets to exceed "
                          "1 GiB together, so that workloads smaller than the 256 MB last-level cache are still timed from HBM)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the three parts of the step into HIP graphs and time their replays (takes the "
                          "host's launch cost out of chunked runs)")
+    ap.add_argument("--settle-ms", type=float, default=60.0,
+                    help="untimed run of the step loop before the warm-up steps, so that the GPU's clocks have settled")
+    ap.add_argument("--cold-trace", type=int, default=0,
+                    help="print the per-step call times of this many steps from a cold start and exit")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-workloads", action="store_true", help="skip the per-configuration table (headline workload only)")
     ap.add_argument("--gen-threads", type=int, default=16)
     return ap.parse_args()
+
+
+def oracle_step(w, block, rows):
+    """One step's call mix on the first `rows` tokens of every payload, on the oracle; returns (seconds, results)."""
+    from oracle import taco_ref
+    from paper_2604_24088_amd import workloads as W
+    xs = [W.generate_rows(w, i, 0, rows) for i in range(w.payloads)]
+    n = rows * w.hidden
+    t0 = time.perf_counter()
+    enc = [taco_ref.compress(x, block=block) for x in xs]
+    taco_ref.decompress(enc[0][0], enc[0][1], n, block=block)
+    total = taco_ref.decompress_sum([e[0] for e in enc], [e[1] for e in enc], n, block=block)
+    return time.perf_counter() - t0, enc, total
 
 
 def cpu_baseline(w, block, rows, gpu=None):
@@ -78,14 +106,8 @@ def cpu_baseline(w, block, rows, gpu=None):
     every payload, and decompress_sum of the ORACLE's payloads on the GPU against the oracle's own sum."""
     import numpy as np
     from oracle import taco_ref
-    from paper_2604_24088_amd import workloads as W
-    xs = [W.generate_rows(w, i, 0, rows) for i in range(w.payloads)]
+    dt, enc, total = oracle_step(w, block, rows)
     n = rows * w.hidden
-    t0 = time.perf_counter()
-    enc = [taco_ref.compress(x, block=block) for x in xs]
-    taco_ref.decompress(enc[0][0], enc[0][1], n, block=block)
-    total = taco_ref.decompress_sum([e[0] for e in enc], [e[1] for e in enc], n, block=block)
-    dt = time.perf_counter() - t0
     k = w.payloads
     bf16_bytes = (k + 1 + k) * 2 * n
     base = {"value": bf16_bytes / dt / 1e9, "unit": "GB/s", "cores": taco_ref.threads(), "kind": "oracle",
@@ -132,13 +154,278 @@ def cpu_baseline(w, block, rows, gpu=None):
     return base, parity
 
 
+def cpu_baseline_one_thread(w, block, rows):
+    from oracle import taco_ref
+    before = taco_ref.threads()
+    taco_ref.set_threads(1)
+    try:
+        dt, _, _ = oracle_step(w, block, rows)
+    finally:
+        taco_ref.set_threads(before)
+    k, n = w.payloads, rows * w.hidden
+    return {"value": (k + 1 + k) * 2 * n / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {rows} of {w.tokens} tokens of each of the {k} payloads, same call mix as one step ({dt:.1f} s)"}
+
+
+class Bench:
+    """Buffers and calls of one workload under one parameter set."""
+
+    def __init__(self, args, name, params, taco, torch, W, rotate=0, chunk_mb=0.0, streams=1, graph=False, batch=False):
+        import numpy as np
+        self.taco, self.torch = taco, torch
+        self.w = w = W.WORKLOADS[name]
+        self.params, self.B = params, params.block
+        self.k, self.n = w.payloads, w.numel
+        k, n, B = self.k, self.n, self.B
+        dev = torch.device("cuda:0")
+        self.interleaved = params.layout == taco.TACO_LAYOUT_INTERLEAVED
+        host = np.empty((w.tokens, w.hidden), dtype=np.uint16)
+        xs = []
+        for i in range(k):
+            W.generate(w, i, threads=args.gen_threads, out=host)
+            xs.append(torch.from_numpy(host.view(np.int16)).to(dev).view(torch.bfloat16))
+        del host
+        if self.interleaved:
+            payloads = [torch.empty(taco.taco_payload_bytes(n, B) + taco.taco_scales_bytes(n, B), dtype=torch.uint8, device=dev)
+                        for _ in range(k)]
+            scales = [None] * k
+        else:
+            payloads = [torch.empty(taco.taco_payload_bytes(n, B), dtype=torch.uint8, device=dev) for _ in range(k)]
+            scales = [torch.empty((taco.taco_scales_bytes(n, B) // 8, 2), dtype=torch.float32, device=dev) for _ in range(k)]
+        out1 = torch.empty((w.tokens, w.hidden), dtype=torch.bfloat16, device=dev)
+        outk = torch.empty((w.tokens, w.hidden), dtype=torch.bfloat16, device=dev)
+        # Buffer sets: copies of everything a step touches; step j works on set j mod R.
+        set_bytes = sum(t.numel() * t.element_size() for t in xs + payloads + [t for t in scales if t is not None] + [out1, outk])
+        self.n_sets = rotate if rotate > 0 else max(1, min(64, -(-(1 << 30) // set_bytes)))
+        if graph:
+            self.n_sets = 1                 # a captured graph replays on the buffers it was captured with
+        self.sets = [(xs, payloads, scales, out1, outk)]
+        for _ in range(self.n_sets - 1):
+            self.sets.append(tuple([t.clone() if t is not None else None for t in group] if isinstance(group, list) else group.clone()
+                                   for group in self.sets[0]))
+        self.cur = self.sets[0]
+        self.step_no = 0
+        self.stream = torch.cuda.current_stream()
+        # Row chunks (whole rows, so every chunk is a whole number of blocks and tiles when hidden is a multiple of
+        # 2048) dealt to `streams` streams in turn; each call joins them back into `stream`.
+        self.rows_per_chunk = w.tokens
+        if chunk_mb > 0:
+            self.rows_per_chunk = max(1, min(w.tokens, int(chunk_mb * (1 << 20)) // (2 * w.hidden)))
+            assert (self.rows_per_chunk * w.hidden) % 2048 == 0, "chunks must be whole tiles"
+        self.bounds = [(r, min(r + self.rows_per_chunk, w.tokens)) for r in range(0, w.tokens, self.rows_per_chunk)]
+        self.side = [torch.cuda.Stream() for _ in range(streams)] if chunk_mb > 0 and streams > 1 and not batch else []
+        self.batch = batch
+        self.rec = (B + 8) if self.interleaved else B       # payload bytes per block
+        self.bpr = w.hidden // B                            # blocks per row
+        self.parts = [self.part_compress, self.part_decompress, self.part_sum]
+        if graph:
+            for part in self.parts:
+                part()                      # first launches (module load) outside the capture
+            torch.cuda.synchronize()
+            graphs = []
+            for part in self.parts:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    self.stream = torch.cuda.current_stream()        # the capturing stream: chunked() forks from and joins it
+                    part()
+                graphs.append(g)
+            self.stream = torch.cuda.current_stream()
+            self.parts = [g.replay for g in graphs]
+
+    # ---- the three parts of a step --------------------------------------------------------------
+    @staticmethod
+    def rows_of(t, r0, r1, per_row):
+        return None if t is None else t[r0 * per_row:r1 * per_row]
+
+    def chunked(self, fn):
+        """fn(r0, r1, stream) for every chunk; whole-tensor calls go straight to the stream."""
+        if len(self.bounds) == 1:
+            fn(0, self.w.tokens, self.stream)
+            return
+        for s_ in self.side:
+            s_.wait_stream(self.stream)
+        for c, (r0, r1) in enumerate(self.bounds):
+            fn(r0, r1, self.side[c % len(self.side)] if self.side else self.stream)
+        for s_ in self.side:
+            self.stream.wait_stream(s_)
+
+    def part_compress(self):
+        xs, payloads, scales, _, _ = self.cur
+        taco, rows_of, bpr, rec = self.taco, self.rows_of, self.bpr, self.rec
+        if self.batch:
+            # every chunk of every tensor in launches of at most TACO_MAX_BATCH items
+            items = [(i, r0, r1) for i in range(self.k) for (r0, r1) in self.bounds]
+            for a in range(0, len(items), taco.TACO_MAX_BATCH):
+                part = items[a:a + taco.TACO_MAX_BATCH]
+                taco.taco_compress_batch([xs[i][r0:r1] for i, r0, r1 in part], self.params,
+                                         [rows_of(payloads[i], r0, r1, bpr * rec) for i, r0, r1 in part],
+                                         [rows_of(scales[i], r0, r1, bpr) for i, r0, r1 in part], self.stream)
+            return
+        for i in range(self.k):
+            self.chunked(lambda r0, r1, st, i=i: taco.taco_compress(xs[i][r0:r1], self.params, rows_of(payloads[i], r0, r1, bpr * rec),
+                                                                    rows_of(scales[i], r0, r1, bpr), st))
+
+    def decode(self, srcs_p, srcs_s, out):
+        taco, rows_of, bpr, rec = self.taco, self.rows_of, self.bpr, self.rec
+        if self.batch and len(self.bounds) > 1:
+            kk = len(srcs_p)
+            per = max(1, min(taco.TACO_MAX_BATCH, taco.TACO_MAX_BATCH_PAYLOADS // kk))
+            for a in range(0, len(self.bounds), per):
+                part = self.bounds[a:a + per]
+                taco.taco_decompress_sum_batch([[rows_of(t, r0, r1, bpr * rec) for t in srcs_p] for r0, r1 in part],
+                                               [[rows_of(t, r0, r1, bpr) for t in srcs_s] for r0, r1 in part],
+                                               [out[r0:r1].shape for r0, r1 in part], self.params,
+                                               [out[r0:r1] for r0, r1 in part], self.stream)
+            return
+        self.chunked(lambda r0, r1, st: taco.taco_decompress_sum([rows_of(t, r0, r1, bpr * rec) for t in srcs_p],
+                                                                 [rows_of(t, r0, r1, bpr) for t in srcs_s],
+                                                                 out[r0:r1].shape, self.params, out[r0:r1], st))
+
+    def part_decompress(self):
+        _, payloads, scales, out1, _ = self.cur
+        self.decode(payloads[:1], scales[:1], out1)
+
+    def part_sum(self):
+        _, payloads, scales, _, outk = self.cur
+        self.decode(payloads, scales, outk)
+
+    def step(self, ev=None):
+        self.cur = self.sets[self.step_no % self.n_sets]
+        self.step_no += 1
+        for j, part in enumerate(self.parts):
+            if ev:
+                ev[j].record(self.stream)
+            part()
+        if ev:
+            ev[3].record(self.stream)
+
+    # ---- measurements -------------------------------------------------------------------------
+    def bytes_of(self):
+        per_elem = 1.0 + 8.0 / self.B                    # payload bytes per element: code + two fp32 per block
+        n, k = self.n, self.k
+        return {"compress": (2.0 + per_elem) * n, "decompress": (per_elem + 2.0) * n, "sum": (k * per_elem + 2.0) * n,
+                "fused": (k + 1) * per_elem * n}
+
+    def settle(self, ms):
+        """Untimed steps for about `ms` milliseconds of GPU time: lets the clocks settle."""
+        if ms <= 0:
+            return
+        torch = self.torch
+        t0 = time.perf_counter()
+        while (time.perf_counter() - t0) * 1e3 < ms:
+            for _ in range(8):
+                self.step()
+            torch.cuda.synchronize()
+
+    def timed_steps(self, steps, warmup):
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(steps):
+            self.step(events[s])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        per = [[e[j].elapsed_time(e[j + 1]) for e in events] for j in range(3)]
+        per[0] = [v / self.k for v in per[0]]            # per compress launch
+        return wall, per
+
+    def back_to_back(self, fn, alg_bytes):
+        """16 launches in a row (after 3 untimed), launch r on buffer set r mod R: no events or other kernels between."""
+        torch = self.torch
+        yev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        for r in range(3):
+            fn(r, self.sets[r % self.n_sets])
+        yev[0].record(self.stream)
+        for r in range(16):
+            fn(r, self.sets[r % self.n_sets])
+        yev[1].record(self.stream)
+        torch.cuda.synchronize()
+        ms = yev[0].elapsed_time(yev[1]) / 16
+        return {"ms": round(ms, 4), "moved_GBps": round(alg_bytes / ms / 1e6, 1),
+                "hbm_frac": round(alg_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+
+    def back_to_back_calls(self):
+        taco, p, k, st = self.taco, self.params, self.k, self.stream
+        by = self.bytes_of()
+        return {"compress": self.back_to_back(lambda r, S: taco.taco_compress(S[0][r % k], p, S[1][r % k], S[2][r % k], st), by["compress"]),
+                # source payload r mod k, so that a launch does not find its input in the last-level cache
+                "decompress": self.back_to_back(lambda r, S: taco.taco_decompress(S[1][r % k], S[2][r % k], S[3].shape, p, S[3], st),
+                                                by["decompress"]),
+                f"decompress_sum_k{k}": self.back_to_back(lambda r, S: taco.taco_decompress_sum(S[1], S[2], S[4].shape, p, S[4], st),
+                                                          by["sum"])}
+
+    def yardsticks(self):
+        """Memory-only kernels with the traffic of each call (set layout: xs, payloads, scales, out1, outk; the bf16
+        buffers serve as sources and sinks of the right sizes)."""
+        taco, k, B, st = self.taco, self.k, self.B, self.stream
+        chunks = (2048 + 8 * (2048 // B)) // 16           # 16-byte words of one tile's payload
+        n_tiles = self.n // 2048
+        if n_tiles == 0:
+            return {}
+        per = (1.0 + 8.0 / B) * n_tiles * 2048
+        raw = 2.0 * n_tiles * 2048
+        return {"compress": self.back_to_back(lambda r, S: taco.taco_debug_traffic([S[0][r % k]], 256, S[4], chunks, n_tiles, st), raw + per),
+                "decompress": self.back_to_back(lambda r, S: taco.taco_debug_traffic([S[0][r % k]], chunks, S[3], 256, n_tiles, st), raw + per),
+                f"decompress_sum_k{k}": self.back_to_back(lambda r, S: taco.taco_debug_traffic(S[0], chunks, S[3], 256, n_tiles, st),
+                                                          k * per + raw)}
+
+    def fused_call(self):
+        taco, torch, st = self.taco, self.torch, self.stream
+        xs, payloads, scales, out1, outk = self.sets[0]
+        fev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        fp = torch.empty_like(payloads[0])
+        fs = torch.empty_like(scales[0]) if scales[0] is not None else None
+        for _ in range(3):
+            taco.taco_decompress_sum_compress(payloads, scales, outk.shape, self.params, fp, fs, st)
+        fev[0].record(st)
+        for _ in range(10):
+            taco.taco_decompress_sum_compress(payloads, scales, outk.shape, self.params, fp, fs, st)
+        fev[1].record(st)
+        torch.cuda.synchronize()
+        return fev[0].elapsed_time(fev[1]) / 10
+
+
+def call_entry(ms, alg_bytes, bf16_bytes):
+    return {"ms": round(ms, 4), "moved_GBps": round(alg_bytes / ms / 1e6, 1),
+            "bf16_GBps": round(bf16_bytes / ms / 1e6, 1), "hbm_frac": round(alg_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+
+
+def workload_entry(b, steps, warmup, settle_ms):
+    """In-step medians and back-to-back times of one workload (k compress + 1 decompress + 1 decompress_sum(k))."""
+    b.settle(settle_ms)
+    wall, per = b.timed_steps(steps, warmup)
+    by, k, n = b.bytes_of(), b.k, b.n
+    med = [statistics.median(v) for v in per]
+    moved = k * by["compress"] + by["decompress"] + by["sum"]
+    ms_step = wall * 1e3 / steps
+    return {"shape": [b.w.tokens, b.w.hidden], "payloads": k, "buffer_sets": b.n_sets,
+            "ms_per_step": round(ms_step, 4), "hbm_frac_step": round(moved / (ms_step * 1e6) / HBM_PEAK_GBPS, 4),
+            "in_step_median": {"compress": call_entry(med[0], by["compress"], 2.0 * n),
+                               "decompress": call_entry(med[1], by["decompress"], 2.0 * n),
+                               f"decompress_sum_k{k}": call_entry(med[2], by["sum"], k * 2.0 * n)},
+            "back_to_back": b.back_to_back_calls()}
+
+
+def cold_trace(args, taco, torch, W, params):
+    """Per-step call times from a cold start: nothing is launched before the first traced step."""
+    b = Bench(args, args.workload, params, taco, torch, W, rotate=args.rotate)
+    torch.cuda.synchronize()
+    _, per = b.timed_steps(args.cold_trace, 0)
+    print(json.dumps({"cold_trace_us": {"workload": b.w.name, "block": b.B,
+                                        "compress": [round(v * 1e3, 1) for v in per[0]],
+                                        "decompress": [round(v * 1e3, 1) for v in per[1]],
+                                        f"decompress_sum_k{b.k}": [round(v * 1e3, 1) for v in per[2]]}}))
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the operator is block-local, so it shards on any block "
               "boundary without an exchange, and nothing here uses a second device); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
-    import numpy as np
     import torch
     from paper_2604_24088_amd import taco
     from paper_2604_24088_amd import workloads as W
@@ -147,128 +434,29 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     from paper_2604_24088_amd import build as hip_build
-    hip_build.ensure_built()   # load what is built; build only if nothing is
+    hip_build.ensure_built()   # the library that matches the sources on disk (built if missing or stale)
     taco.lib()                 # fails loudly if the HIP library cannot be loaded
-    dev = torch.device("cuda:0")
-    w = W.WORKLOADS[args.workload]
-    k, n, B = w.payloads, w.numel, args.block
+    B = args.block
     impl = {"auto": taco.TACO_IMPL_AUTO, "butterfly": taco.TACO_IMPL_BUTTERFLY, "mfma": taco.TACO_IMPL_MFMA}[args.impl]
     layout = taco.TACO_LAYOUT_INTERLEAVED if args.layout == "interleaved" else taco.TACO_LAYOUT_SPLIT
     fmt = {"e4m3": taco.TACO_FORMAT_E4M3, "e5m2": taco.TACO_FORMAT_E5M2, "int8": taco.TACO_FORMAT_INT8}[args.format]
     params = taco.taco_default_params(block=B, impl=impl, layout=layout, mode=args.mode, fmt=fmt)
     variant = args.mode != taco.TACO_MODE_FULL or fmt != taco.TACO_FORMAT_E4M3
+    on_mfma = args.impl != "butterfly" and args.mode in (6, 7)
 
-    # ---- synthetic inputs, resident in HBM
-    host = np.empty((w.tokens, w.hidden), dtype=np.uint16)
-    xs = []
-    for i in range(k):
-        W.generate(w, i, threads=args.gen_threads, out=host)
-        xs.append(torch.from_numpy(host.view(np.int16)).to(dev).view(torch.bfloat16))
-    del host
-    if args.layout == "interleaved":
-        payloads = [torch.empty(taco.taco_payload_bytes(n, B) + taco.taco_scales_bytes(n, B), dtype=torch.uint8, device=dev)
-                    for _ in range(k)]
-        scales = [None] * k
-    else:
-        payloads = [torch.empty(taco.taco_payload_bytes(n, B), dtype=torch.uint8, device=dev) for _ in range(k)]
-        scales = [torch.empty((taco.taco_scales_bytes(n, B) // 8, 2), dtype=torch.float32, device=dev) for _ in range(k)]
-    out1 = torch.empty((w.tokens, w.hidden), dtype=torch.bfloat16, device=dev)
-    outk = torch.empty((w.tokens, w.hidden), dtype=torch.bfloat16, device=dev)
-    # Buffer sets: copies of everything a step touches; step j works on set j mod R.
-    set_bytes = sum(t.numel() * t.element_size() for t in xs + payloads + [t for t in scales if t is not None] + [out1, outk])
-    n_sets = args.rotate if args.rotate > 0 else max(1, min(64, -(-(1 << 30) // set_bytes)))
-    if args.graph:
-        n_sets = 1                      # a captured graph replays on the buffers it was captured with
-    sets = [(xs, payloads, scales, out1, outk)]
-    for _ in range(n_sets - 1):
-        sets.append(tuple([t.clone() if t is not None else None for t in group] if isinstance(group, list) else group.clone()
-                          for group in sets[0]))
-    step_no = 0
-    stream = torch.cuda.current_stream()
+    if args.cold_trace > 0:
+        cold_trace(args, taco, torch, W, params)
+        return
 
-    # Row chunks (whole rows, so every chunk is a whole number of blocks and tiles when hidden is a multiple of
-    # 2048) dealt to `--streams` streams in turn; each call joins them back into `stream`.
-    rows_per_chunk = w.tokens
-    if args.chunk_mb > 0:
-        rows_per_chunk = max(1, min(w.tokens, int(args.chunk_mb * (1 << 20)) // (2 * w.hidden)))
-        assert (rows_per_chunk * w.hidden) % 2048 == 0, "chunks must be whole tiles"
-    bounds = [(r, min(r + rows_per_chunk, w.tokens)) for r in range(0, w.tokens, rows_per_chunk)]
-    side = [torch.cuda.Stream() for _ in range(args.streams)] if args.chunk_mb > 0 and args.streams > 1 else []
-    rec = (B + 8) if args.layout == "interleaved" else B       # payload bytes per block
-
-    def rows_of(t, r0, r1, per_row):
-        return None if t is None else t[r0 * per_row:r1 * per_row]
-
-    def chunked(fn):
-        """fn(r0, r1, stream) for every chunk; whole-tensor calls go straight to `stream`."""
-        if len(bounds) == 1:
-            fn(0, w.tokens, stream)
-            return
-        for s_ in side:
-            s_.wait_stream(stream)
-        for c, (r0, r1) in enumerate(bounds):
-            fn(r0, r1, side[c % len(side)] if side else stream)
-        for s_ in side:
-            stream.wait_stream(s_)
-
-    bpr = w.hidden // B                                          # blocks per row
-
-    def compress_rows(i):
-        return lambda r0, r1, st: taco.taco_compress(xs[i][r0:r1], params, rows_of(payloads[i], r0, r1, bpr * rec),
-                                                     rows_of(scales[i], r0, r1, bpr), st)
-
-    def decode_rows(srcs_p, srcs_s, out):
-        return lambda r0, r1, st: taco.taco_decompress_sum([rows_of(t, r0, r1, bpr * rec) for t in srcs_p],
-                                                           [rows_of(t, r0, r1, bpr) for t in srcs_s],
-                                                           out[r0:r1].shape, params, out[r0:r1], st)
-
-    def part_compress():
-        for i in range(k):
-            chunked(compress_rows(i))
-
-    def part_decompress():
-        chunked(decode_rows(payloads[:1], scales[:1], out1))
-
-    def part_sum():
-        chunked(decode_rows(payloads, scales, outk))
-
-    parts = [part_compress, part_decompress, part_sum]
-    if args.graph:
-        for part in parts:
-            part()                      # first launches (module load) outside the capture
-        torch.cuda.synchronize()
-        graphs = []
-        for part in parts:
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                stream = torch.cuda.current_stream()        # the capturing stream: chunked() forks from and joins it
-                part()
-            graphs.append(g)
-        stream = torch.cuda.current_stream()
-        parts = [g.replay for g in graphs]
-
-    def step(ev=None):
-        nonlocal xs, payloads, scales, out1, outk, step_no
-        xs, payloads, scales, out1, outk = sets[step_no % n_sets]
-        step_no += 1
-        for j, part in enumerate(parts):
-            if ev:
-                ev[j].record(stream)
-            part()
-        if ev:
-            ev[3].record(stream)
-
-    for _ in range(args.warmup):
-        step()
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        step(events[s])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    b = Bench(args, args.workload, params, taco, torch, W, rotate=args.rotate, chunk_mb=args.chunk_mb, streams=args.streams,
+              graph=args.graph, batch=args.batch)
+    w, k, n = b.w, b.k, b.n
+    b.settle(args.settle_ms)
+    wall, per = b.timed_steps(args.steps, args.warmup)
 
     # ---- yardstick outside the timed region: plain copy of 1 GiB (reads 1 GiB, writes 1 GiB)
+    xs = b.sets[0][0]
+    stream = b.stream
     src = xs[0].view(torch.uint8)[: 1 << 30] if xs[0].numel() * 2 >= (1 << 30) else xs[0].view(torch.uint8)
     dst = torch.empty_like(src)
     cev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
@@ -282,75 +470,21 @@ def main():
     copy_gbps = 2.0 * src.numel() * 10 / (cev[0].elapsed_time(cev[1]) * 1e6)
     del dst
 
-    # ---- yardsticks outside the timed region: memory-only kernels with the traffic of compress (reads one
-    # bf16 tensor, writes one payload) and of decompress_sum (reads k payloads, writes one bf16 tensor)
-    chunks = (2048 + 8 * (2048 // B)) // 16           # 16-byte words of one tile's payload
-    n_tiles = n // 2048
-    per_elem_y = 1.0 + 8.0 / B
-
-    def back_to_back(fn, alg_bytes):
-        """16 launches in a row (after 3 untimed), launch r on buffer set r mod R: no events or other kernels between."""
-        yev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        for r in range(3):
-            fn(r, sets[r % n_sets])
-        yev[0].record(stream)
-        for r in range(16):
-            fn(r, sets[r % n_sets])
-        yev[1].record(stream)
-        torch.cuda.synchronize()
-        ms = yev[0].elapsed_time(yev[1]) / 16
-        return {"ms": round(ms, 4), "moved_GBps": round(alg_bytes / ms / 1e6, 1),
-                "hbm_frac": round(alg_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4)}
-
-    mix, b2b = {}, {}
-    if n_tiles > 0:
-        # set layout: (xs, payloads, scales, out1, outk); the bf16 buffers serve as sources and sinks of the right sizes
-        mix = {"compress": back_to_back(lambda r, S: taco.taco_debug_traffic([S[0][r % k]], 256, S[4], chunks, n_tiles, stream),
-                                        (2.0 + per_elem_y) * n_tiles * 2048),
-               f"decompress_sum_k{k}": back_to_back(lambda r, S: taco.taco_debug_traffic(S[0], chunks, S[3], 256, n_tiles, stream),
-                                                    (k * per_elem_y + 2.0) * n_tiles * 2048)}
-    b2b = {"compress": back_to_back(lambda r, S: taco.taco_compress(S[0][r % k], params, S[1][r % k], S[2][r % k], stream),
-                                    (2.0 + per_elem_y) * n),
-           "decompress": back_to_back(lambda r, S: taco.taco_decompress(S[1][0], S[2][0], S[3].shape, params, S[3], stream),
-                                      (2.0 + per_elem_y) * n),
-           f"decompress_sum_k{k}": back_to_back(lambda r, S: taco.taco_decompress_sum(S[1], S[2], S[4].shape, params, S[4], stream),
-                                                (k * per_elem_y + 2.0) * n)}
-
-    # ---- outside the timed region: the fused decompress_sum -> compress call (reduce-scatter receive
-    # side feeding the all-gather send side) on the same payloads
-    fev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    fp = torch.empty_like(payloads[0])
-    fs = torch.empty_like(scales[0]) if scales[0] is not None else None
-    for _ in range(3):
-        taco.taco_decompress_sum_compress(payloads, scales, outk.shape, params, fp, fs, stream)
-    fev[0].record(stream)
-    for _ in range(10):
-        taco.taco_decompress_sum_compress(payloads, scales, outk.shape, params, fp, fs, stream)
-    fev[1].record(stream)
-    torch.cuda.synchronize()
-    t_fused = fev[0].elapsed_time(fev[1]) / 10
-    del fp, fs
+    mix = b.yardsticks()
+    b2b = b.back_to_back_calls()
+    t_fused = b.fused_call()
 
     ms_step = wall * 1e3 / args.steps
-    t_comp = sum(e[0].elapsed_time(e[1]) for e in events) / (args.steps * k)   # ms per compress launch
-    t_dec = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
-    t_sum = sum(e[2].elapsed_time(e[3]) for e in events) / args.steps
-
-    per_elem = 1.0 + 8.0 / B                         # payload bytes per element: code + two fp32 per block
-    bytes_comp = (2.0 + per_elem) * n                # algorithmic bytes of one compress launch
-    bytes_dec = (per_elem + 2.0) * n
-    bytes_sum = (k * per_elem + 2.0) * n
-    equiv = (k + 1 + k) * 2.0 * n                    # bf16-equivalent bytes per step
-    real_bf16 = (k + 1 + 1) * 2.0 * n                # bf16 bytes that cross HBM per step
-    moved = k * bytes_comp + bytes_dec + bytes_sum
-
-    def call(ms, alg_bytes, bf16_bytes):
-        return {"ms": round(ms, 4), "moved_GBps": round(alg_bytes / ms / 1e6, 1),
-                "bf16_GBps": round(bf16_bytes / ms / 1e6, 1), "hbm_frac": round(alg_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4)}
-
-    achieved = bytes_comp / t_comp / 1e6
+    t_comp_avg = sum(per[0]) / len(per[0])               # ms per compress launch, average over the timed region
+    med = [statistics.median(v) for v in per]
+    by = b.bytes_of()
+    equiv = (k + 1 + k) * 2.0 * n                        # bf16-equivalent bytes per step
+    real_bf16 = (k + 1 + 1) * 2.0 * n                    # bf16 bytes that cross HBM per step
+    moved = k * by["compress"] + by["decompress"] + by["sum"]
+    achieved = by["compress"] / t_comp_avg / 1e6
+    il = args.layout == "interleaved"
     result = {
-        "metric": "compress+decompress GB/s of bf16 input and % of HBM peak, 1\u00d7MI355X",
+        "metric": "compress+decompress GB/s of bf16 input and % of HBM peak, 1×MI355X",
         "value": round(equiv / (ms_step * 1e6), 1),
         "unit": "GB/s",
         "n_gpus": 1,
@@ -360,42 +494,64 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "bf16",
+        "arithmetic": "bf16 and FP8 matrix-core operands (exact products), fp32 accumulation and block scalars",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: bf16 [{w.tokens}, {w.hidden}] x {k} payloads, block {B}, "
                                f"step = {k} compress + 1 decompress + 1 decompress_sum(k={k})",
                    "impl": args.impl, "block": B, "layout": args.layout,
-                   "chunk_rows": rows_per_chunk if len(bounds) > 1 else None, "chunks_per_call": len(bounds),
-                   "streams": max(len(side), 1), "hip_graph": bool(args.graph),
-                   "buffer_sets": n_sets, "format": args.format, "mode": args.mode},
+                   "chunk_rows": b.rows_per_chunk if len(b.bounds) > 1 else None, "chunks_per_call": len(b.bounds),
+                   "streams": max(len(b.side), 1), "hip_graph": bool(args.graph), "batched_calls": bool(args.batch),
+                   "buffer_sets": b.n_sets, "format": args.format, "mode": args.mode, "settle_ms": args.settle_ms,
+                   "library_build_id": taco.taco_build_id()},
         "value_out_basis": round(real_bf16 / (ms_step * 1e6), 1),
         "moved_GBps": round(moved / (ms_step * 1e6), 1),
         "hbm_frac_step": round(moved / (ms_step * 1e6) / HBM_PEAK_GBPS, 4),
         "copy_yardstick_GBps": round(copy_gbps, 1),
         "mix_yardstick": mix,
         "calls_back_to_back": b2b,
-        "calls": {"compress": call(t_comp, bytes_comp, 2.0 * n),
-                  "decompress": call(t_dec, bytes_dec, 2.0 * n),
-                  f"decompress_sum_k{k}": call(t_sum, bytes_sum, k * 2.0 * n),
-                  f"decompress_sum_compress_k{k} (not in the step)": call(t_fused, (k + 1) * per_elem * n, k * 2.0 * n)},
-        "roofline": {"kernel": (f"compress_mfma_kernel<{max(B // 128, 1)},{max(128 // B, 1)},1,"
-                                f"{'true' if args.layout == 'interleaved' else 'false'},{1 if args.format == 'e5m2' else 0}>")
-                     if args.impl != "butterfly" and args.mode in (6, 7) and args.format != "int8"
-                     else f"compress_butterfly_kernel<{B}>",
+        "calls": {"compress": call_entry(med[0], by["compress"], 2.0 * n),
+                  "decompress": call_entry(med[1], by["decompress"], 2.0 * n),
+                  f"decompress_sum_k{k}": call_entry(med[2], by["sum"], k * 2.0 * n),
+                  f"decompress_sum_compress_k{k} (not in the step)": call_entry(t_fused, by["fused"], k * 2.0 * n)},
+        "roofline": {"kernel": (f"compress_mfma_kernel<{max(B // 128, 1)},{max(128 // B, 1)},{'true' if il else 'false'},"
+                                f"{ {'e4m3': 0, 'e5m2': 1, 'int8': 2}[args.format] },CompressSingle>")
+                     if on_mfma else f"compress_butterfly_kernel<{B},CompressSingle>",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, B, args.impl)) if args.layout == "split" and not variant else None,
-                     "alg_bytes_per_launch": bytes_comp, "avg_launch_ms": round(t_comp, 4),
-                     "mfma_busy_frac": MEASURED_MFMA_BUSY.get((w.name, B, args.impl)) if args.layout == "split" and not variant else None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, B, args.impl)) if not il and not variant else None,
+                     "alg_bytes_per_launch": by["compress"], "avg_launch_ms": round(t_comp_avg, 4),
+                     "mfma_busy_frac": MEASURED_MFMA_BUSY.get((w.name, B, args.impl)) if not il and not variant else None},
     }
+    payloads0, scales0 = b.sets[0][1], b.sets[0][2]
+    plain = not (variant or il or args.chunk_mb > 0 or args.graph or args.batch)
+    if not args.no_workloads and plain:
+        # the other benchmark configurations, each with its own buffers (freed before the next)
+        table = {w.name: {"shape": [w.tokens, w.hidden], "payloads": k, "buffer_sets": b.n_sets, "ms_per_step": round(ms_step, 4),
+                          "hbm_frac_step": result["hbm_frac_step"], "in_step_median": {kk: vv for kk, vv in result["calls"].items()
+                                                                                      if "not in the step" not in kk},
+                          "back_to_back": b2b}}
+        keep = (payloads0, scales0)
+        del b, xs, src
+        torch.cuda.empty_cache()
+        for name in ("tiny", "gpt_rowpar", "qwen_act", "bwd_grad"):
+            if name == w.name:
+                continue
+            other = Bench(args, name, params, taco, torch, W)
+            table[name] = workload_entry(other, 30, 10, 20.0)
+            del other
+            torch.cuda.empty_cache()
+        result["workloads"] = {name: table[name] for name in ("tiny", "gpt_rowpar", "qwen_act", "bwd_grad", "large_k8") if name in table}
+        payloads0, scales0 = keep
     if not args.no_cpu_baseline and variant:
         print("bench.py: the CPU baseline is timed for the method itself (mode 7, E4M3) only; skipped", file=sys.stderr)
     if not args.no_cpu_baseline and not variant:
-        gpu = (sets[0][1], sets[0][2], params, taco) if (args.layout == "split" and impl != taco.TACO_IMPL_BUTTERFLY
-                                                         and not variant) else None
+        gpu = (payloads0, scales0, params, taco) if (args.layout == "split" and impl != taco.TACO_IMPL_BUTTERFLY) else None
         result["cpu_baseline"], parity = cpu_baseline(w, B, rows=w.tokens, gpu=gpu)
         if parity is not None:
             result["parity_full_size"] = parity
+        # one thread: 1/16 of the tokens, so that it takes about as long as the all-threads run on 16 cores
+        result["cpu_baseline_1thread"] = cpu_baseline_one_thread(w, B, rows=max(64, w.tokens // 16))
     print(json.dumps(result))
 
 

@@ -246,6 +246,18 @@ int taco_ref_threads(void) {
 #endif
 }
 
+// Sets the number of threads the block loops use from now on (no arithmetic depends on it: blocks are
+// independent and each is computed by one thread); returns the number in effect.
+int taco_ref_set_threads(int threads) {
+#ifdef _OPENMP
+    if (threads >= 1) omp_set_num_threads(threads);
+    return omp_get_max_threads();
+#else
+    (void)threads;
+    return 1;
+#endif
+}
+
 double taco_ref_e4m3_decode(uint8_t code) { return e4m3_decode(code); }
 double taco_ref_format_decode(int32_t format, uint8_t code) { return format_decode(format, code); }
 uint8_t taco_ref_format_encode(int32_t format, double v) { return format_encode(format, v); }

@@ -25,6 +25,8 @@ def lib():
         c = ctypes
         L.taco_ref_threads.restype = c.c_int
         L.taco_ref_threads.argtypes = []
+        L.taco_ref_set_threads.restype = c.c_int
+        L.taco_ref_set_threads.argtypes = [c.c_int]
         L.taco_ref_e4m3_decode.restype = c.c_double
         L.taco_ref_e4m3_decode.argtypes = [c.c_uint8]
         L.taco_ref_e4m3_encode.restype = c.c_uint8
@@ -64,6 +66,11 @@ def _ptr(a):
 
 def threads() -> int:
     return int(lib().taco_ref_threads())
+
+
+def set_threads(threads: int) -> int:
+    """Threads the block loops use from now on (results do not depend on it); returns the number in effect."""
+    return int(lib().taco_ref_set_threads(int(threads)))
 
 
 def e4m3_decode(code: int) -> float:

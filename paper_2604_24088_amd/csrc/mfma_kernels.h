@@ -422,22 +422,17 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(Table tab, int count,
 // all-gather, Section 4.4.2): the finished tile goes to LDS in the compress stage's layout
 // instead of HBM.  The payload tile and the bf16 tile use the SAME LDS region: a wave's LDS
 // accesses execute in order, and the payload tile is dead once its A operand has been read.
-template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kWaves, int kFormat, typename Table>
-__global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
-    Table tab, int count, int k, int tiles_per_wave, float tau, float eps, bool rescale) {
-    static_assert((kRB == 1 || kRB == 2 || kRB == 4) && (kSub == 1 || kSub == 2 || kSub == 4) && (kRB == 1 || kSub == 1),
-                  "block size must be 32, 64, 128, 256 or 512");
+// The work of one wave: output tiles [tile_begin, tile_end) of tensor idx.  kGuarded = true is the copy that the
+// one wave owning a partial last tile runs (bounds-checked loads and stores for that tile); every other wave runs
+// the kGuarded = false copy, in which all of those checks are compiled out.
+template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kFormat, bool kGuarded, typename Table>
+__device__ __forceinline__ void decode_wave(const Table& tab, int idx, int k, int64_t n, int64_t tile_begin, int64_t tile_end,
+                                            u32x4* lds, float tau, float eps, bool rescale) {
     constexpr int kBlock = 128 * kRB / kSub;
     constexpr int kBlocksPerTile = 2048 / kBlock;
     using Layout = PayloadLayout<kBlock, kInterleaved>;
     constexpr int kLoads = kInterleaved ? 3 : 2;                 // 16-byte loads per lane and item
     constexpr int kExtraChunks = Layout::kTileChunks - 128;      // interleaved: chunks left for the third load
-    // Per wave: one tile of the payload (split layout swizzled, interleaved as it is); the recompress
-    // form puts the bf16 tile for the compress stage into the same region afterwards.
-    constexpr int kLdsChunks = kRecompress && kCompressLdsDwords / 4 > Layout::kTileChunks ? kCompressLdsDwords / 4 : Layout::kTileChunks;
-    __shared__ u32x4 lds_all[kWaves][kLdsChunks];
-    const int wave = kWaves == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    u32x4* lds = lds_all[wave];
     uint32_t* lds_c = reinterpret_cast<uint32_t*>(lds);
     const int lane = threadIdx.x & 63;
     const int g = lane >> 4;
@@ -448,21 +443,11 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
     const int my_block = kSub == 1 ? unit_of_row<kRB>(4 * g + (n16 & 3)) / kRB
                                    : unit_of_row<kRB>(4 * g + (n16 & 3)) * kSub + ph;
 
-    int idx;
-    int64_t group;
-    tab.locate(blockIdx.x, count, idx, group);
-    const int64_t n = tab.n(idx);
-    const int64_t n_tiles = (n + kTileElems - 1) / kTileElems;
     const int64_t n_blocks = (n + kBlock - 1) / kBlock;
-    // The one tile that may be partial, and how many of its blocks exist (-1: every tile is whole).
-    const int64_t partial_tile = (n % kTileElems) != 0 ? n_tiles - 1 : -1;
-    const int partial_blocks = static_cast<int>(n_blocks - (n_tiles - 1) * kBlocksPerTile);
+    // The one tile that may be partial, and how many of its blocks exist (-1: every tile of this wave is whole).
+    const int64_t partial_tile = kGuarded ? tile_end - 1 : -1;
+    const int partial_blocks = kGuarded ? static_cast<int>(n_blocks - (tile_end - 1) * kBlocksPerTile) : kBlocksPerTile;
     u32x4* __restrict__ out = static_cast<u32x4*>(tab.output(idx));
-
-    const int64_t tile_begin = (group * kWaves + wave) * tiles_per_wave;
-    int64_t tile_end = tile_begin + tiles_per_wave;
-    if (tile_end > n_tiles) tile_end = n_tiles;
-    if (tile_end <= tile_begin) return;      // a wave past the end (last workgroup of a tensor only)
     const int n_items = static_cast<int>(tile_end - tile_begin) * k;
 
     // Ring fill.  (pf_tile, pf_i) walks the item list ahead of the consumer.
@@ -697,6 +682,32 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
             }
         }
     }
+}
+
+template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kWaves, int kFormat, typename Table>
+__global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
+    Table tab, int count, int k, int tiles_per_wave, float tau, float eps, bool rescale) {
+    static_assert((kRB == 1 || kRB == 2 || kRB == 4) && (kSub == 1 || kSub == 2 || kSub == 4) && (kRB == 1 || kSub == 1),
+                  "block size must be 32, 64, 128, 256 or 512");
+    using Layout = PayloadLayout<128 * kRB / kSub, kInterleaved>;
+    // Per wave: one tile of the payload (split layout swizzled, interleaved as it is); the recompress
+    // form puts the bf16 tile for the compress stage into the same region afterwards.
+    constexpr int kLdsChunks = kRecompress && kCompressLdsDwords / 4 > Layout::kTileChunks ? kCompressLdsDwords / 4 : Layout::kTileChunks;
+    __shared__ u32x4 lds_all[kWaves][kLdsChunks];
+    const int wave = kWaves == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int idx;
+    int64_t group;
+    tab.locate(blockIdx.x, count, idx, group);
+    const int64_t n = tab.n(idx);
+    const int64_t n_tiles = (n + kTileElems - 1) / kTileElems;
+    const int64_t tile_begin = (group * kWaves + wave) * tiles_per_wave;
+    int64_t tile_end = tile_begin + tiles_per_wave;
+    if (tile_end > n_tiles) tile_end = n_tiles;
+    if (tile_end <= tile_begin) return;      // a wave past the end (last workgroup of a tensor only)
+    if (tile_end == n_tiles && (n % kTileElems) != 0)
+        decode_wave<kRB, kSub, kRing, kInterleaved, kRecompress, kFormat, true>(tab, idx, k, n, tile_begin, tile_end, lds_all[wave], tau, eps, rescale);
+    else
+        decode_wave<kRB, kSub, kRing, kInterleaved, kRecompress, kFormat, false>(tab, idx, k, n, tile_begin, tile_end, lds_all[wave], tau, eps, rescale);
 }
 
 }  // namespace taco
