@@ -68,8 +68,7 @@ typedef enum taco_status {
     TACO_ERR_K = -5,      /* k outside 1..TACO_MAX_K                                  */
     TACO_ERR_FORMAT = -6, /* params->format is not one of TACO_FORMAT_*               */
     TACO_ERR_LAUNCH = -7, /* the HIP runtime refused this call's launch               */
-    TACO_ERR_IMPL = -8,   /* params->impl is not one of TACO_IMPL_*, or MFMA was forced
-                             for an ablation variant                                  */
+    TACO_ERR_IMPL = -8,   /* params->impl is not one of TACO_IMPL_*                   */
     TACO_ERR_PARAM = -9,  /* tau <= 0, eps < 0, or a non-finite parameter             */
     TACO_ERR_LAYOUT = -10,/* params->layout is not one of TACO_LAYOUT_*               */
     TACO_ERR_MODE = -11,  /* params->mode is outside 0..TACO_MODE_FULL                */
@@ -86,16 +85,14 @@ enum { TACO_FORMAT_E4M3 = 0, TACO_FORMAT_E5M2 = 1, TACO_FORMAT_INT8 = 2 };
 /* Stages of the method, for the paper's component ablations (Section 5.2.2, Section 5.3): a bit
  * mask.  Without RESCALE alpha_k = 1; without ROTATE Z_k = alpha_k G_k; without POSTSCALE s_k = 1
  * and Z_k itself is converted, saturating at +-Q_max.  FULL (7) is the method; 0 is the direct
- * cast, 4 dual scale only, 2 the standard Hadamard transform, 3 ASH without DS.  The matrix-core
- * kernels cover the variants that keep the method's structure (rotation and post-rotation scale
- * on, i.e. modes 7 and 6, with any of the three code books); every other variant runs on the
- * butterfly kernels. */
+ * cast, 4 dual scale only, 2 the standard Hadamard transform, 3 ASH without DS.  Every variant, with
+ * any of the three code books, runs on either kernel family. */
 enum { TACO_MODE_RESCALE = 1, TACO_MODE_ROTATE = 2, TACO_MODE_POSTSCALE = 4, TACO_MODE_FULL = 7 };
 
-/* Kernel selection.  AUTO runs the matrix-core kernels where the variant allows it (see above) and
- * the butterfly kernels otherwise; MFMA is AUTO that fails with TACO_ERR_IMPL for a variant the
- * matrix-core kernels do not cover; BUTTERFLY runs the butterfly kernels (kept for tests and
- * benchmarks that compare the two).  Either family handles any n in its one kernel. */
+/* Kernel selection.  AUTO and MFMA run the matrix-core kernels (the rotation as a dense product on
+ * the matrix cores; without the rotation, a product with the identity); BUTTERFLY runs the second
+ * family, an in-register butterfly (kept for tests and benchmarks that compare the two).  Either
+ * family handles any n, any mode and any code book in its one kernel. */
 enum { TACO_IMPL_AUTO = 0, TACO_IMPL_BUTTERFLY = 1, TACO_IMPL_MFMA = 2 };
 
 /* Where the two scalars of a block travel (Section 4.4.2 of the paper places them directly

@@ -21,71 +21,65 @@ constexpr int kB = TACO_BLOCK;
 constexpr int kRB = kB > 128 ? kB / 128 : 1;      // units of 128 per block
 constexpr int kSub = kB < 128 ? 128 / kB : 1;     // blocks per unit
 
-// Calls f(kInterleaved, kFormat) with the two as compile-time constants and returns its result.
+// Calls f(kInterleaved, kFormat, kGeneric) with the three as compile-time constants and returns its result.
+// kGeneric = false: the method and its no-rescaling variant (modes 7 and 6), the lean instantiation.
 template <typename F>
-int with_layout_and_format(const Call& call, F&& f) {
+int with_variant(const Call& call, F&& f) {
     using std::integral_constant;
+    auto with_generic = [&](auto layout, auto fmt) {
+        return (call.mode & 6) == 6 ? f(layout, fmt, std::false_type{}) : f(layout, fmt, std::true_type{});
+    };
     auto with_format = [&](auto layout) {
-        if (call.format == 1) return f(layout, integral_constant<int, 1>{});
-        if (call.format == 2) return f(layout, integral_constant<int, 2>{});
-        return f(layout, integral_constant<int, 0>{});
+        if (call.format == 1) return with_generic(layout, integral_constant<int, 1>{});
+        if (call.format == 2) return with_generic(layout, integral_constant<int, 2>{});
+        return with_generic(layout, integral_constant<int, 0>{});
     };
     return call.interleaved ? with_format(std::true_type{}) : with_format(std::false_type{});
 }
 
-template <typename Table>
-int compress(const Table& tab, int count, int64_t workgroups, const Call& call, hipStream_t st) {
+int compress(const CompressTable& tab, int count, int64_t workgroups, const Call& call, hipStream_t st) {
     const dim3 grid(static_cast<unsigned>(workgroups)), block(64);
     if (call.mfma) {
-        const bool rescale = (call.mode & 1) != 0;
-        return with_layout_and_format(call, [&](auto layout, auto fmt) {
-            return launch(compress_mfma_kernel<kRB, kSub, decltype(layout)::value, decltype(fmt)::value, Table>, grid, block, st, tab,
-                          count, call.tau, call.eps, rescale);
+        return with_variant(call, [&](auto layout, auto fmt, auto generic) {
+            return launch(compress_mfma_kernel<kRB, kSub, decltype(layout)::value, decltype(fmt)::value, decltype(generic)::value>, grid,
+                          block, st, tab, count, call.tau, call.eps, call.mode);
         });
     }
-    return launch(compress_butterfly_kernel<kB, Table>, grid, block, st, tab, count, call.tau, call.eps, call.interleaved,
+    return launch(compress_butterfly_kernel<kB>, grid, block, st, tab, count, call.tau, call.eps, call.interleaved,
                   Variant{call.mode, call.format});
 }
 
-template <typename Table>
-int decode(const Table& tab, int count, int k, int64_t workgroups, const Call& call, bool recompress, bool wide, int tiles_per_wave,
+int decode(const DecodeTable& tab, int count, int k, int64_t workgroups, const Call& call, bool recompress, bool wide, int tiles_per_wave,
            hipStream_t st) {
     const dim3 grid(static_cast<unsigned>(workgroups));
     if (call.mfma) {
-        const bool rescale = (call.mode & 1) != 0;
-        return with_layout_and_format(call, [&](auto layout, auto fmt) {
-            constexpr bool kIl = decltype(layout)::value;
+        return with_variant(call, [&](auto layout, auto fmt, auto generic) {
+            constexpr bool kIl = decltype(layout)::value, kGen = decltype(generic)::value;
             constexpr int kFmt = decltype(fmt)::value;
             if (recompress)
-                return launch(decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, true, 1, kFmt, Table>, grid, dim3(64), st, tab, count, k,
-                              tiles_per_wave, call.tau, call.eps, rescale);
+                return launch(decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, true, 1, kFmt, kGen>, grid, dim3(64), st, tab, count, k,
+                              tiles_per_wave, call.tau, call.eps, call.mode);
+            // the plain decode differs between the flavours only in how its sign table is built: one instantiation
             if (wide)
-                return launch(decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 2, kFmt, Table>, grid, dim3(128), st, tab, count, k,
-                              tiles_per_wave, 0.0f, 0.0f, true);
-            return launch(decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 1, kFmt, Table>, grid, dim3(64), st, tab, count, k,
-                          tiles_per_wave, 0.0f, 0.0f, true);
+                return launch(decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 2, kFmt, true>, grid, dim3(128), st, tab, count, k,
+                              tiles_per_wave, 0.0f, 0.0f, call.mode);
+            return launch(decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 1, kFmt, true>, grid, dim3(64), st, tab, count, k,
+                          tiles_per_wave, 0.0f, 0.0f, call.mode);
         });
     }
     const Variant var{call.mode, call.format};
     if (recompress)
-        return launch(decompress_sum_compress_butterfly_kernel<kB, Table>, grid, dim3(64), st, tab, count, k, call.tau, call.eps,
+        return launch(decompress_sum_compress_butterfly_kernel<kB>, grid, dim3(64), st, tab, count, k, call.tau, call.eps,
                       call.interleaved, var);
-    return launch(decompress_sum_butterfly_kernel<kB, Table>, grid, dim3(64), st, tab, count, k, call.interleaved, var);
+    return launch(decompress_sum_butterfly_kernel<kB>, grid, dim3(64), st, tab, count, k, call.interleaved, var);
 }
 
 }  // namespace
 
-template <> int launch_compress_b<kB>(const CompressSingle& tab, int count, int64_t workgroups, const Call& call, hipStream_t st) {
+template <> int launch_compress_b<kB>(const CompressTable& tab, int count, int64_t workgroups, const Call& call, hipStream_t st) {
     return compress(tab, count, workgroups, call, st);
 }
-template <> int launch_compress_b<kB>(const CompressBatch& tab, int count, int64_t workgroups, const Call& call, hipStream_t st) {
-    return compress(tab, count, workgroups, call, st);
-}
-template <> int launch_decode_b<kB>(const DecodeSingle& tab, int count, int k, int64_t workgroups, const Call& call, bool recompress,
-                                    bool wide, int tiles_per_wave, hipStream_t st) {
-    return decode(tab, count, k, workgroups, call, recompress, wide, tiles_per_wave, st);
-}
-template <> int launch_decode_b<kB>(const DecodeBatch& tab, int count, int k, int64_t workgroups, const Call& call, bool recompress,
+template <> int launch_decode_b<kB>(const DecodeTable& tab, int count, int k, int64_t workgroups, const Call& call, bool recompress,
                                     bool wide, int tiles_per_wave, hipStream_t st) {
     return decode(tab, count, k, workgroups, call, recompress, wide, tiles_per_wave, st);
 }

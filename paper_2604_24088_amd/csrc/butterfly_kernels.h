@@ -231,8 +231,8 @@ __device__ __forceinline__ void unpack_chunk(u32x4 w, float (&v)[8]) {
 }
 
 // Sender side of Algorithm 1: workgroup w of a tensor (one wave) handles its tile w.
-template <int B, typename Table>
-__global__ __launch_bounds__(64) void compress_butterfly_kernel(Table tab, int count, float tau, float eps,
+template <int B>
+__global__ __launch_bounds__(64) void compress_butterfly_kernel(CompressTable tab, int count, float tau, float eps,
                                                                 bool interleaved, Variant var) {
     const int lane = threadIdx.x;
     int idx;
@@ -266,8 +266,8 @@ __global__ __launch_bounds__(64) void compress_butterfly_kernel(Table tab, int c
 // k > 1 the codes are first combined with their block factors s / (alpha sqrt(B)) and rotated
 // once; for k = 1 the raw codes are rotated (exact partial sums) and the factor is applied
 // afterwards.  Lanes whose block lies past the end of the tensor read nothing and carry zeros.
-template <int B, typename Table>
-__device__ __forceinline__ void decode_sum_group_butterfly(const Table& tab, int idx, int k, int64_t group, int lane,
+template <int B>
+__device__ __forceinline__ void decode_sum_group_butterfly(const DecodeTable& tab, int idx, int k, int64_t group, int lane,
                                                            int64_t n_blocks_total, float (&v)[8], bool interleaved,
                                                            Variant var) {
     const LaneSlot<B> slot(group, lane);
@@ -311,8 +311,8 @@ __device__ __forceinline__ void decode_sum_group_butterfly(const Table& tab, int
 }
 
 // Receiver side of Algorithm 1 and the local reduction: workgroup w of a tensor (one wave) handles its tile w.
-template <int B, typename Table>
-__global__ __launch_bounds__(64) void decompress_sum_butterfly_kernel(Table tab, int count, int k, bool interleaved, Variant var) {
+template <int B>
+__global__ __launch_bounds__(64) void decompress_sum_butterfly_kernel(DecodeTable tab, int count, int k, bool interleaved, Variant var) {
     const int lane = threadIdx.x;
     int idx;
     int64_t tile;
@@ -342,8 +342,8 @@ __global__ __launch_bounds__(64) void decompress_sum_butterfly_kernel(Table tab,
 
 // decompress_sum followed by compress of the bf16-rounded sum, group by group, without the
 // bf16 tensor leaving the registers.
-template <int B, typename Table>
-__global__ __launch_bounds__(64) void decompress_sum_compress_butterfly_kernel(Table tab, int count, int k, float tau, float eps,
+template <int B>
+__global__ __launch_bounds__(64) void decompress_sum_compress_butterfly_kernel(DecodeTable tab, int count, int k, float tau, float eps,
                                                                                bool interleaved, Variant var) {
     const int lane = threadIdx.x;
     int idx;

@@ -68,6 +68,14 @@ __device__ __forceinline__ uint32_t pack_codes4(float v0, float v1, float v2, fl
     if (kFormat == 1) return pack_e5m2x4(v0 * f, v1 * f, v2 * f, v3 * f);
     return pack_int8x4_scaled(v0, v1, v2, v3, f);
 }
+// The same for values that may lie outside the code book's range (the variants without the post-rotation
+// scale): v_i * f is clamped to +-Q_max first.
+template <int kFormat>
+__device__ __forceinline__ uint32_t pack_codes4_clamped(float v0, float v1, float v2, float v3, float f) {
+    constexpr float kQ = kFormat == 0 ? 448.0f : kFormat == 1 ? 57344.0f : 127.0f;
+    return pack_codes4<kFormat>(__builtin_amdgcn_fmed3f(v0 * f, -kQ, kQ), __builtin_amdgcn_fmed3f(v1 * f, -kQ, kQ),
+                                __builtin_amdgcn_fmed3f(v2 * f, -kQ, kQ), __builtin_amdgcn_fmed3f(v3 * f, -kQ, kQ), 1.0f);
+}
 template <int kFormat>
 __device__ __forceinline__ constexpr float format_qmax() { return kFormat == 0 ? 448.0f : kFormat == 1 ? 57344.0f : 127.0f; }
 

@@ -38,12 +38,9 @@ int launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream,
 }
 
 // `workgroups` = size of the grid; the tables say which tensors it covers (tables.h).
-template <int B> int launch_compress_b(const CompressSingle& tab, int count, int64_t workgroups, const Call& call, hipStream_t st);
-template <int B> int launch_compress_b(const CompressBatch& tab, int count, int64_t workgroups, const Call& call, hipStream_t st);
+template <int B> int launch_compress_b(const CompressTable& tab, int count, int64_t workgroups, const Call& call, hipStream_t st);
 // recompress: decompress_sum followed by compress; wide: two waves per workgroup (matrix-core kernels only).
-template <int B> int launch_decode_b(const DecodeSingle& tab, int count, int k, int64_t workgroups, const Call& call, bool recompress,
-                                     bool wide, int tiles_per_wave, hipStream_t st);
-template <int B> int launch_decode_b(const DecodeBatch& tab, int count, int k, int64_t workgroups, const Call& call, bool recompress,
+template <int B> int launch_decode_b(const DecodeTable& tab, int count, int k, int64_t workgroups, const Call& call, bool recompress,
                                      bool wide, int tiles_per_wave, hipStream_t st);
 
 }  // namespace taco

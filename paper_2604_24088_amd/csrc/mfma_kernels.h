@@ -238,14 +238,23 @@ struct CompressLane {
     // (measured: 142 us instead of 99 us per compress of the bench tensor).  The tile's records are
     // therefore assembled in LDS (the input buffer is free once the A operands are read) and
     // leave as contiguous 16-byte chunks.
-    // kFormat: 0 = E4M3, 1 = E5M2, 2 = INT8 (format ablation).  rescale = false is the component ablation
-    // without the adaptive rescaling ("standard Hadamard" with the post-rotation scale): alpha = 1.
+    // kFormat: 0 = E4M3, 1 = E5M2, 2 = INT8 (format ablation).  mode: the component ablations as a bit mask
+    // (1 adaptive rescaling, 2 rotation, 4 post-rotation scale; 7 is the method).  Without the rescaling
+    // alpha = 1.  Without the rotation the matrix cores multiply by the IDENTITY instead of H (8 of the 32
+    // products, the rest would be zero): the tile takes the same way from the load layout to the store layout,
+    // and everything after it is shared.  Without the post-rotation scale s = 1 and Z = alpha W / sqrt(B)
+    // itself is converted, clamped to +-Q_max.
     // blocks_left: blocks of the tensor from this tile's first block on; only the first
     // min(blocks_left, kBlocksPerTile) blocks of the tile exist and are stored.
-    template <bool kInterleaved, int kFormat>
+    // kGeneric = false is the method itself and its no-rescaling variant (rotation and post-rotation scale on:
+    // the other two bits of `mode` are not looked at and their code is compiled out); kGeneric = true handles
+    // any mode at run time, at the price of some twenty more registers.
+    template <bool kInterleaved, int kFormat, bool kGeneric>
     __device__ __forceinline__ void tile_from_lds(uint32_t* lds, int64_t tile, int64_t blocks_left, float tau, float eps,
-                                                  bool rescale, u32x2* __restrict__ payload, f32x2* __restrict__ scales) const {
+                                                  int mode, u32x2* __restrict__ payload, f32x2* __restrict__ scales) const {
         constexpr float kQ = format_qmax<kFormat>();
+        const bool rescale = (mode & 1) != 0;
+        const bool rotate = kGeneric ? (mode & 2) != 0 : true, postscale = kGeneric ? (mode & 4) != 0 : true;
         using Layout = PayloadLayout<kBlock, kInterleaved>;
         u32x2* records = reinterpret_cast<u32x2*>(lds);     // interleaved: the tile's records, 8-byte words
         u32x4 a[4];
@@ -259,20 +268,40 @@ struct CompressLane {
         f32x4 gram = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) acc[nt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (rotate) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const bf16x8 av = __builtin_bit_cast(bf16x8, a[c]);
-            if (kSub == 1) gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, av, gram, 0, 0, 0);
+            for (int c = 0; c < 4; ++c) {
+                const bf16x8 av = __builtin_bit_cast(bf16x8, a[c]);
+                if (kSub == 1) gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, av, gram, 0, 0, 0);
 #pragma unroll
-            for (int nt = 0; nt < 8; ++nt) {
-                const int sign = __builtin_popcount(c & (nt >> 1)) & 1;
-                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                    av, __builtin_bit_cast(bf16x8, hb[nt & 1][sign]), acc[nt], 0, 0, 0);
+                for (int nt = 0; nt < 8; ++nt) {
+                    const int sign = __builtin_popcount(c & (nt >> 1)) & 1;
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        av, __builtin_bit_cast(bf16x8, hb[nt & 1][sign]), acc[nt], 0, 0, 0);
+                }
+            }
+            // W = H_B G for blocks of more than one unit: butterfly across the block's units.
+#pragma unroll
+            for (int nt = 0; nt < 8; ++nt) units_butterfly<kRB>(acc[nt]);
+        } else {
+            // W = G.  Identity entries: element e = 8 (4g + m) + 2c + y meets position p = 8 n + nt where
+            // 4g + m = n and 2c + y = nt, so output tile nt needs step c = nt / 2 only, with a 1.0 in half
+            // y = nt % 2 of register m of the lanes whose chunk 4g + m is the column n.
+            u32x4 id[2];
+#pragma unroll
+            for (int mm = 0; mm < 4; ++mm) {
+                const bool hit = 4 * g + mm == n16;
+                id[0][mm] = hit ? 0x00003F80u : 0u;
+                id[1][mm] = hit ? 0x3F800000u : 0u;
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const bf16x8 av = __builtin_bit_cast(bf16x8, a[c]);
+                if (kSub == 1) gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, av, gram, 0, 0, 0);
+                acc[2 * c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, id[0]), acc[2 * c], 0, 0, 0);
+                acc[2 * c + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, id[1]), acc[2 * c + 1], 0, 0, 0);
             }
         }
-        // W = H_B G for blocks of more than one unit: butterfly across the block's units.
-#pragma unroll
-        for (int nt = 0; nt < 8; ++nt) units_butterfly<kRB>(acc[nt]);
 
         // max|W| of each block.
         float m[4];
@@ -284,16 +313,23 @@ struct CompressLane {
             m[r] = v;
         }
         const float wmax = kSub == 1 ? row16_block_max<kRB>(m, n16) : sub_block_max<kSub>(m, n16);
-        // Z / s = W * Q_max / max|W| in exact arithmetic (Eq. post_scale, Eq. quantization).
-        const float to_code = wmax > 0.0f ? kQ * __builtin_amdgcn_rcpf(wmax) : 0.0f;
-
-        // Energy of the owned block: own Gram diagonal plus those of the block's other units,
-        // which sit in the neighbouring lanes of the quad.
+        // Energy of the block whose factor this lane supplies (row 4g + q; kRB = 2: block q % 2 of the lane
+        // group; kRB = 4: the group's one block).  The Gram diagonal of row i sits in lane (i, i / 4), register
+        // i % 4, i.e. in quad n16 / 4 == g of each DPP row: summed over the block's units there, then handed
+        // to the other three quads (they add zeros).
+        // Only the lane that stores the block's scalars needs it, unless the codes themselves depend on alpha
+        // (no post-rotation scale: kGeneric).
         float energy;
         if (kSub == 1) {
             energy = q == 0 ? gram[0] : q == 1 ? gram[1] : q == 2 ? gram[2] : gram[3];
+            if (kGeneric && (n16 >> 2) != g) energy = 0.0f;
             if (kRB >= 2) energy += dpp_f32<0xB1>(energy);
             if (kRB == 4) energy += dpp_f32<0x4E>(energy);
+            if (kGeneric) {
+                if (kRB == 2) energy = dpp_f32<0x88>(energy);          // quad_perm [0,2,0,2]: block q % 2 sits in lanes 2 (q % 2)
+                energy += dpp_f32<kDppRowRor(4)>(energy);
+                energy += dpp_f32<kDppRowRor(8)>(energy);
+            }
         } else {
             // A-layout lane (i, g) holds elements 32g .. 32g+31 of unit row i: one block for
             // B = 32, half a block for B = 64 (the other half is 16 lanes away).
@@ -310,10 +346,20 @@ struct CompressLane {
             if (kSub == 2) energy += __shfl_xor(energy, 16, 64);
             energy = __shfl(energy, energy_src, 64);
         }
+        const float alpha = rescale ? tau * __builtin_amdgcn_rsqf(energy * (1.0f / kBlock) + eps) : 1.0f;   // Eq. ash_sigma, ash_alpha
+        const float norm = rotate ? inv_sqrt_block<kBlock>() : 1.0f;
+        // With the post-rotation scale: Z / s = W * Q_max / max|W| in exact arithmetic (Eq. post_scale,
+        // Eq. quantization), s = max|Z| / Q_max; an all-zero block stores s = 0 whatever alpha is (with
+        // eps = 0 it is infinite).  Without it: s = 1 and the codes are those of Z = alpha W / sqrt(B).
+        float to_code, s;
+        if (postscale) {
+            to_code = wmax > 0.0f ? kQ * __builtin_amdgcn_rcpf(wmax) : 0.0f;
+            s = wmax > 0.0f ? (wmax * alpha) * (norm / kQ) : 0.0f;
+        } else {
+            to_code = alpha * norm;
+            s = 1.0f;
+        }
         if (owns_scales && my_block < blocks_left) {
-            const float alpha = rescale ? tau * __builtin_amdgcn_rsqf(energy * (1.0f / kBlock) + eps) : 1.0f;   // Eq. ash_sigma, ash_alpha
-            // max|Z| / Q_max; an all-zero block stores s = 0 whatever alpha is (with eps = 0 it is infinite)
-            const float s = wmax > 0.0f ? (wmax * alpha) * (inv_sqrt_block<kBlock>() / kQ) : 0.0f;
             if (kInterleaved)
                 records[Layout::scale_word(0, my_block)] = __builtin_bit_cast(u32x2, f32x2{alpha, s});
             else
@@ -328,8 +374,13 @@ struct CompressLane {
         {                                                                                      \
             const float f = dpp_f32<kDppQuadBcast(kRB == 1 ? R : kRB == 2 ? R / 2 : 0)>(to_code); \
             u32x2 w;                                                                           \
-            w.x = pack_codes4<kFormat>(acc[0][R], acc[1][R], acc[2][R], acc[3][R], f);          \
-            w.y = pack_codes4<kFormat>(acc[4][R], acc[5][R], acc[6][R], acc[7][R], f);          \
+            if (postscale) {                                                                   \
+                w.x = pack_codes4<kFormat>(acc[0][R], acc[1][R], acc[2][R], acc[3][R], f);      \
+                w.y = pack_codes4<kFormat>(acc[4][R], acc[5][R], acc[6][R], acc[7][R], f);      \
+            } else {                                                                           \
+                w.x = pack_codes4_clamped<kFormat>(acc[0][R], acc[1][R], acc[2][R], acc[3][R], f); \
+                w.y = pack_codes4_clamped<kFormat>(acc[4][R], acc[5][R], acc[6][R], acc[7][R], f); \
+            }                                                                                  \
             const int unit = unit_of_row<kRB>(4 * g + R);                                      \
             const int blk = kSub == 1 ? unit / kRB : unit * kSub + n16 / (16 / kSub);          \
             const int word = kSub == 1 ? 16 * (unit % kRB) + n16 : n16 % (16 / kSub);          \
@@ -363,8 +414,8 @@ struct CompressLane {
 // tab: the tensors of the launch (tables.h): x = n bf16 values (16-byte aligned); payload, scales: see
 // PayloadLayout.  Block size B = 128 kRB / kSub (at most one of kRB, kSub differs from 1).
 // One wave per workgroup, one tile per wave: workgroup w of a tensor handles its tile w.
-template <int kRB, int kSub, bool kInterleaved, int kFormat, typename Table>
-__global__ __launch_bounds__(64) void compress_mfma_kernel(Table tab, int count, float tau, float eps, bool rescale) {
+template <int kRB, int kSub, bool kInterleaved, int kFormat, bool kGeneric>
+__global__ __launch_bounds__(64) void compress_mfma_kernel(CompressTable tab, int count, float tau, float eps, int mode) {
     __shared__ uint32_t lds[kCompressLdsDwords];
     constexpr int kBlock = 128 * kRB / kSub;
     const int lane = threadIdx.x;
@@ -395,7 +446,7 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(Table tab, int count,
         for (int c = 0; c < 4; ++c) lds[wr_base + cp * 528 + 4 * c] = stage[cp][c];
     }
     wave_lds_sync();
-    cl.template tile_from_lds<kInterleaved, kFormat>(lds, tile, blocks_left, tau, eps, rescale,
+    cl.template tile_from_lds<kInterleaved, kFormat, kGeneric>(lds, tile, blocks_left, tau, eps, mode,
                                                      static_cast<u32x2*>(tab.payload(idx)), static_cast<f32x2*>(tab.scales(idx)));
 }
 
@@ -417,6 +468,9 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(Table tab, int count,
 // block row per instruction); 2 = INT8 codes into the 8-bit integer one (K = 64, two per row,
 // exact int32 sums).
 //
+// mode: the component ablations (bit 2 = rotation: without it the product is with the identity and the
+// butterfly across units is skipped; the other two bits only matter to the recompress form).
+//
 // kRecompress = true turns the kernel into decompress_sum followed by compress of the
 // bf16-rounded sum (the receive side of the reduce-scatter feeding the send side of the
 // all-gather, Section 4.4.2): the finished tile goes to LDS in the compress stage's layout
@@ -425,9 +479,9 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(Table tab, int count,
 // The work of one wave: output tiles [tile_begin, tile_end) of tensor idx.  kGuarded = true is the copy that the
 // one wave owning a partial last tile runs (bounds-checked loads and stores for that tile); every other wave runs
 // the kGuarded = false copy, in which all of those checks are compiled out.
-template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kFormat, bool kGuarded, typename Table>
-__device__ __forceinline__ void decode_wave(const Table& tab, int idx, int k, int64_t n, int64_t tile_begin, int64_t tile_end,
-                                            u32x4* lds, float tau, float eps, bool rescale) {
+template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kFormat, bool kGeneric, bool kGuarded>
+__device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int k, int64_t n, int64_t tile_begin, int64_t tile_end,
+                                            u32x4* lds, float tau, float eps, int mode) {
     constexpr int kBlock = 128 * kRB / kSub;
     constexpr int kBlocksPerTile = 2048 / kBlock;
     using Layout = PayloadLayout<kBlock, kInterleaved>;
@@ -498,8 +552,11 @@ __device__ __forceinline__ void decode_wave(const Table& tab, int idx, int k, in
     // sign = parity(b%8 & nt) ^ (b/8 & n16) ^ parity(g & (n16 >> 1)) ^ (m & n16 >> 3).
     // For kSub > 1 the element's block within the unit is eh (top bits of e: m, then g / 2) and the
     // output's is ph: entries with eh != ph are zero and the eh & ph term of the sign drops out.
+    // Variants without the rotation (mode bit 2 clear) multiply by the identity instead: entry 1 where
+    // e = p, i.e. 64 m + 16 g + b = 8 n16 + nt, zero elsewhere.
     constexpr uint32_t kPlusOne = kFormat == 2 ? 0x01010101u : 0x38383838u;
     constexpr uint32_t kNegate = kFormat == 2 ? 0xFEu : 0x80u;              // +1 ^ -1, per byte
+    const bool rotate = kGeneric ? (mode & 2) != 0 : true;
     uint32_t hb[8][8];
 #pragma unroll
     for (int d = 0; d < 8; ++d) {
@@ -510,6 +567,7 @@ __device__ __forceinline__ void decode_wave(const Table& tab, int idx, int k, in
         int sgn = (b_hi & n16) ^ parity32(g & (n16 >> 1) & 3) ^ (m & (n16 >> 3));
         if (kSub > 1) sgn ^= parity32(eh & ph);
         const uint32_t lane_sign = (sgn & 1) ? kNegate * 0x01010101u : 0u;
+        const int e0 = 64 * m + 16 * g + 4 * (d & 3);      // element of byte 0 of this dword
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) {
             uint32_t w = kPlusOne;
@@ -518,7 +576,10 @@ __device__ __forceinline__ void decode_wave(const Table& tab, int idx, int k, in
                 const int b_lo = (4 * (d & 3) + bb) & 7;
                 if (__builtin_popcount(b_lo & nt) & 1) w ^= kNegate << (8 * bb);
             }
-            hb[nt][d] = same_block ? (w ^ lane_sign) : 0u;
+            const uint32_t hadamard = same_block ? (w ^ lane_sign) : 0u;
+            const int hit = 8 * n16 + nt - e0;              // byte of this dword that is on the diagonal, if 0..3
+            const uint32_t identity = (hit >= 0 && hit < 4) ? (kPlusOne & 0xFFu) << (8 * hit) : 0u;
+            hb[nt][d] = rotate ? hadamard : identity;
         }
     }
 
@@ -547,7 +608,7 @@ __device__ __forceinline__ void decode_wave(const Table& tab, int idx, int k, in
         }
     }
     if (kInterleaved) sc_byte = my_block * Layout::kRecordBytes + kBlock;
-    const float inv_root_b = inv_sqrt_block<kBlock>();
+    const float inv_root_b = rotate ? inv_sqrt_block<kBlock>() : 1.0f;
 
     f32x4 sum[8];
     int64_t tile = tile_begin;
@@ -625,7 +686,9 @@ __device__ __forceinline__ void decode_wave(const Table& tab, int idx, int k, in
             }
             if (++i == k) {
 #pragma unroll
-                for (int nt = 0; nt < 8; ++nt) units_butterfly<kRB>(sum[nt]);
+                for (int nt = 0; nt < 8; ++nt) {
+                    if (rotate) units_butterfly<kRB>(sum[nt]);
+                }
                 const bool whole = tile != partial_tile;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -673,7 +736,7 @@ __device__ __forceinline__ void decode_wave(const Table& tab, int idx, int k, in
                     int lane_again = lane;
                     asm volatile("" : "+v"(lane_again));
                     const CompressLane<kRB, kSub> cl(lane_again);
-                    cl.template tile_from_lds<kInterleaved, kFormat>(lds_c, tile, n_blocks - tile * kBlocksPerTile, tau, eps, rescale,
+                    cl.template tile_from_lds<kInterleaved, kFormat, kGeneric>(lds_c, tile, n_blocks - tile * kBlocksPerTile, tau, eps, mode,
                                                                      static_cast<u32x2*>(tab.payload_output(idx)),
                                                                      static_cast<f32x2*>(tab.scales_output(idx)));
                 }
@@ -684,9 +747,9 @@ __device__ __forceinline__ void decode_wave(const Table& tab, int idx, int k, in
     }
 }
 
-template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kWaves, int kFormat, typename Table>
+template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kWaves, int kFormat, bool kGeneric>
 __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
-    Table tab, int count, int k, int tiles_per_wave, float tau, float eps, bool rescale) {
+    DecodeTable tab, int count, int k, int tiles_per_wave, float tau, float eps, int mode) {
     static_assert((kRB == 1 || kRB == 2 || kRB == 4) && (kSub == 1 || kSub == 2 || kSub == 4) && (kRB == 1 || kSub == 1),
                   "block size must be 32, 64, 128, 256 or 512");
     using Layout = PayloadLayout<128 * kRB / kSub, kInterleaved>;
@@ -705,9 +768,9 @@ __global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
     if (tile_end > n_tiles) tile_end = n_tiles;
     if (tile_end <= tile_begin) return;      // a wave past the end (last workgroup of a tensor only)
     if (tile_end == n_tiles && (n % kTileElems) != 0)
-        decode_wave<kRB, kSub, kRing, kInterleaved, kRecompress, kFormat, true>(tab, idx, k, n, tile_begin, tile_end, lds_all[wave], tau, eps, rescale);
+        decode_wave<kRB, kSub, kRing, kInterleaved, kRecompress, kFormat, kGeneric, true>(tab, idx, k, n, tile_begin, tile_end, lds_all[wave], tau, eps, mode);
     else
-        decode_wave<kRB, kSub, kRing, kInterleaved, kRecompress, kFormat, false>(tab, idx, k, n, tile_begin, tile_end, lds_all[wave], tau, eps, rescale);
+        decode_wave<kRB, kSub, kRing, kInterleaved, kRecompress, kFormat, kGeneric, false>(tab, idx, k, n, tile_begin, tile_end, lds_all[wave], tau, eps, mode);
 }
 
 }  // namespace taco

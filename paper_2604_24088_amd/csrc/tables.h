@@ -1,11 +1,12 @@
 // Kernel-argument tables: which tensors a launch works on.
 //
 // Every kernel takes its tensors as one table passed BY VALUE in the kernel-argument segment (no
-// device-side pointer table, nothing to allocate or copy).  The ordinary entry points pass a table
-// of one tensor; the batched entry points pass up to kMaxBatch tensors, so that many small tensors
-// (the shards of one exchange, the tensors of several layers) share the ramp-up and the drain of a
-// single launch.  A workgroup finds its tensor with locate(): a scan over the prefix sums of the
-// tensors' workgroup counts, uniform over the workgroup (scalar loads and compares).
+// device-side pointer table, nothing to allocate or copy).  The ordinary entry points fill in one
+// tensor; the batched entry points up to kMaxBatch, so that many small tensors (the shards of one
+// exchange, the tensors of several layers) share the ramp-up and the drain of a single launch.  A
+// workgroup finds its tensor with locate(): a scan over the prefix sums of the tensors' workgroup
+// counts, uniform over the workgroup (scalar loads and compares; no iteration for one tensor).
+// Only the entries a kernel reads are ever fetched from the argument segment.
 //
 // Tables are indexed directly (tab.item[i]), never through a pointer to a member, so that the
 // compiler reads them with scalar loads from the argument segment and makes no private copy.
@@ -28,17 +29,7 @@ struct CompressItem {
     int64_t n;          // elements
 };
 
-struct CompressSingle {
-    CompressItem item;
-    // Workgroup wg of the launch -> (tensor index, workgroup index within that tensor).
-    __device__ __forceinline__ void locate(int64_t wg, int /*count*/, int& idx, int64_t& local) const { idx = 0; local = wg; }
-    __device__ __forceinline__ const void* x(int) const { return item.x; }
-    __device__ __forceinline__ void* payload(int) const { return item.payload; }
-    __device__ __forceinline__ void* scales(int) const { return item.scales; }
-    __device__ __forceinline__ int64_t n(int) const { return item.n; }
-};
-
-struct CompressBatch {
+struct CompressTable {
     CompressItem item[kMaxBatch];
     int64_t first[kMaxBatch + 1];       // first workgroup of tensor i; first[count] = workgroups of the launch
     __device__ __forceinline__ void locate(int64_t wg, int count, int& idx, int64_t& local) const {
@@ -56,23 +47,7 @@ struct CompressBatch {
 
 // ---- decode: k payloads (+ scales) -> bf16 sum, or -> re-compressed payload -----------------------
 
-struct DecodeSingle {
-    const void* src_payload[kMaxK];
-    const void* src_scales[kMaxK];
-    void* out;              // n bf16 values (decompress, decompress_sum)
-    void* payload_out;      // re-compressed result (decompress_sum_compress)
-    void* scales_out;
-    int64_t n_elems;
-    __device__ __forceinline__ void locate(int64_t wg, int /*count*/, int& idx, int64_t& local) const { idx = 0; local = wg; }
-    __device__ __forceinline__ const void* payload(int, int /*k*/, int i) const { return src_payload[i]; }
-    __device__ __forceinline__ const void* scales(int, int /*k*/, int i) const { return src_scales[i]; }
-    __device__ __forceinline__ void* output(int) const { return out; }
-    __device__ __forceinline__ void* payload_output(int) const { return payload_out; }
-    __device__ __forceinline__ void* scales_output(int) const { return scales_out; }
-    __device__ __forceinline__ int64_t n(int) const { return n_elems; }
-};
-
-struct DecodeBatch {
+struct DecodeTable {
     const void* src_payload[kMaxBatchSources];      // payload i of tensor t at [t * k + i]
     const void* src_scales[kMaxBatchSources];
     void* out[kMaxBatch];

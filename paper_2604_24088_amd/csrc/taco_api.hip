@@ -37,12 +37,8 @@ constexpr int64_t kTileElems = 2048;      // elements per workgroup of the opera
 bool block_ok(int32_t b) { return b == 32 || b == 64 || b == 128 || b == 256 || b == 512; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// The matrix-core kernels implement the method itself and the variants that keep its structure
-// (rotation and post-rotation scale on): the full method and the "standard Hadamard" ablation (no
-// adaptive rescaling), with any code book.  Everything else runs on the butterfly kernels.
-bool mfma_capable(const taco_params* p) {
-    return p->mode == TACO_MODE_FULL || p->mode == (TACO_MODE_ROTATE | TACO_MODE_POSTSCALE);
-}
+// The matrix-core kernels implement the method and every ablation variant (any mode, any code book);
+// the butterfly kernels, a second and independent family, run only when asked for.
 
 int check_params(const taco_params* p) {
     if (!p) return TACO_ERR_NULL;
@@ -51,7 +47,6 @@ int check_params(const taco_params* p) {
     if (p->mode < 0 || p->mode > TACO_MODE_FULL) return TACO_ERR_MODE;
     if (p->impl != TACO_IMPL_AUTO && p->impl != TACO_IMPL_BUTTERFLY && p->impl != TACO_IMPL_MFMA) return TACO_ERR_IMPL;
     if (p->layout != TACO_LAYOUT_SPLIT && p->layout != TACO_LAYOUT_INTERLEAVED) return TACO_ERR_LAYOUT;
-    if (p->impl == TACO_IMPL_MFMA && !mfma_capable(p)) return TACO_ERR_IMPL;
     return TACO_OK;
 }
 
@@ -66,7 +61,7 @@ bool params_ok_for_compress(const taco_params* p) {
     return p->tau > 0.0f && p->eps >= 0.0f && std::isfinite(p->tau) && std::isfinite(p->eps);
 }
 
-bool use_mfma(const taco_params* p) { return p->impl != TACO_IMPL_BUTTERFLY && mfma_capable(p); }
+bool use_mfma(const taco_params* p) { return p->impl != TACO_IMPL_BUTTERFLY; }
 
 taco::Call call_of(const taco_params* p) {
     return taco::Call{p->format, p->mode, p->layout == TACO_LAYOUT_INTERLEAVED, use_mfma(p), p->tau, p->eps};
@@ -119,8 +114,7 @@ int64_t tiles_of(int64_t n) { return (n + kTileElems - 1) / kTileElems; }
 
 // One workgroup (one wave) per tile of 2048 elements in either family: measured best on MI355X at every
 // block size and in both layouts (2 tiles per wave cost 4-5 % on the largest tensors, 4 more).
-template <typename Table>
-int launch_compress(const Table& tab, int count, int64_t workgroups, const taco_params* p, hipStream_t st) {
+int launch_compress(const taco::CompressTable& tab, int count, int64_t workgroups, const taco_params* p, hipStream_t st) {
     const taco::Call call = call_of(p);
     switch (p->block) {
         case 32: return taco::launch_compress_b<32>(tab, count, workgroups, call, st);
@@ -170,8 +164,7 @@ int64_t decode_groups(int64_t n, const DecodeShape& shape) {
     return (tiles_of(n) + shape.tiles_per_group - 1) / shape.tiles_per_group;
 }
 
-template <typename Table>
-int launch_decode(const Table& tab, int count, int k, int64_t workgroups, const taco_params* p, bool recompress, hipStream_t st) {
+int launch_decode(const taco::DecodeTable& tab, int count, int k, int64_t workgroups, const taco_params* p, bool recompress, hipStream_t st) {
     const taco::Call call = call_of(p);
     const DecodeShape shape = decode_shape(p, k, recompress);
     switch (p->block) {
@@ -215,7 +208,7 @@ int decode_single(const void* const* payloads, const void* const* scales, int32_
         return TACO_ERR_NULL;
     }
     RangeSet ranges;
-    taco::DecodeSingle tab{};
+    taco::DecodeTable tab{};
     if (int rc = check_sources(payloads, scales, k, n, p, &ranges, [&](int i, const void* pl, const void* sc) {
             tab.src_payload[i] = pl;
             tab.src_scales[i] = sc;
@@ -230,11 +223,13 @@ int decode_single(const void* const* payloads, const void* const* scales, int32_
         ranges.add_out(out_bf16, 2u * static_cast<uint64_t>(n));
     }
     if (ranges.clash()) return TACO_ERR_OVERLAP;
-    tab.out = out_bf16;
-    tab.payload_out = payload_out;
-    tab.scales_out = il ? nullptr : scales_out;
-    tab.n_elems = n;
-    return launch_decode(tab, 1, k, decode_groups(n, decode_shape(p, k, recompress)), p, recompress, static_cast<hipStream_t>(stream));
+    tab.out[0] = out_bf16;
+    tab.payload_out[0] = payload_out;
+    tab.scales_out[0] = il ? nullptr : scales_out;
+    tab.n_elems[0] = n;
+    const int64_t workgroups = decode_groups(n, decode_shape(p, k, recompress));
+    tab.first[1] = workgroups;
+    return launch_decode(tab, 1, k, workgroups, p, recompress, static_cast<hipStream_t>(stream));
 }
 
 }  // namespace
@@ -272,7 +267,9 @@ int taco_compress(const void* x_bf16, int64_t rows, int64_t cols, const taco_par
     if (!params_ok_for_compress(p)) return TACO_ERR_PARAM;
     if (ranges.clash()) return TACO_ERR_OVERLAP;
     const bool il = p->layout == TACO_LAYOUT_INTERLEAVED;
-    const taco::CompressSingle tab{taco::CompressItem{x_bf16, payload, il ? nullptr : scales, n}};
+    taco::CompressTable tab{};
+    tab.item[0] = taco::CompressItem{x_bf16, payload, il ? nullptr : scales, n};
+    tab.first[1] = tiles_of(n);
     return launch_compress(tab, 1, tiles_of(n), p, static_cast<hipStream_t>(stream));
 }
 
@@ -283,7 +280,7 @@ int taco_compress_batch(const taco_compress_item* items, int32_t count, const ta
     if (!params_ok_for_compress(p)) return TACO_ERR_PARAM;
     const bool il = p->layout == TACO_LAYOUT_INTERLEAVED;
     RangeSet ranges;
-    taco::CompressBatch tab{};
+    taco::CompressTable tab{};
     int64_t workgroups = 0;
     for (int i = 0; i < count; ++i) {
         int64_t n = 0;
@@ -326,7 +323,7 @@ int taco_decompress_sum_batch(const taco_decode_item* items, int32_t count, int3
     if (int rc = check_params(p)) return rc;
     const DecodeShape shape = decode_shape(p, k, false);
     RangeSet ranges;
-    taco::DecodeBatch tab{};
+    taco::DecodeTable tab{};
     int64_t workgroups = 0;
     for (int t = 0; t < count; ++t) {
         int64_t n = 0;
@@ -401,7 +398,7 @@ const char* taco_strerror(int status) {
         case TACO_ERR_K: return "k must be between 1 and 16";
         case TACO_ERR_FORMAT: return "bad format: must be E4M3, E5M2 or INT8";
         case TACO_ERR_LAUNCH: return "kernel launch failed";
-        case TACO_ERR_IMPL: return "bad kernel selection (the matrix-core kernels cover modes 7 and 6)";
+        case TACO_ERR_IMPL: return "bad kernel selection: must be AUTO, BUTTERFLY or MFMA";
         case TACO_ERR_PARAM: return "bad parameter: tau must be positive and eps non-negative, both finite";
         case TACO_ERR_LAYOUT: return "bad layout: must be split or interleaved";
         case TACO_ERR_MODE: return "bad mode: must be a combination of the three TACO_MODE_* bits";

@@ -76,7 +76,6 @@ A = 0x1000  # a fake, 16-byte aligned, non-null "device pointer": never derefere
     (dict(x=A + 2), -4), (dict(payload=A + 8), -4), (dict(scales=A + 4), -4),
     (dict(p=_params(format=3)), -6), (dict(p=_params(format=-1)), -6),
     (dict(p=_params(mode=8)), -11), (dict(p=_params(mode=-1)), -11),
-    (dict(p=_params(impl=2, mode=5)), -8), (dict(p=_params(impl=2, mode=3)), -8), (dict(p=_params(impl=2, mode=4, format=2)), -8),
     (dict(p=_params(impl=7)), -8), (dict(p=_params(impl=-1)), -8),
     (dict(p=_params(layout=2)), -10), (dict(p=_params(layout=-1)), -10),
     (dict(p=_params(tau=0.0)), -9), (dict(p=_params(eps=-1.0)), -9), (dict(p=_params(tau=float("nan"))), -9),

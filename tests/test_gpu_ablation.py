@@ -24,14 +24,17 @@ def bits_of(t):
     return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
+@pytest.mark.parametrize("impl", [taco.TACO_IMPL_MFMA, taco.TACO_IMPL_BUTTERFLY])
 @pytest.mark.parametrize("mode,fmt", VARIANTS)
 @pytest.mark.parametrize("block", [128, 256, 32])
 @pytest.mark.parametrize("name", ["tiny", "bwd_grad"])
-def test_variant_parity(oracle, mode, fmt, block, name):
+def test_variant_parity(oracle, mode, fmt, block, name, impl):
+    """Every mode x code book on both kernel families (the matrix-core kernels multiply by the identity where the
+    variant has no rotation)."""
     w = W.WORKLOADS[name]
     x = W.generate_rows(w, 0, 0, 16 if name == "tiny" else 2)
     n = x.size
-    p = taco.taco_default_params(block=block, mode=mode, fmt=fmt)
+    p = taco.taco_default_params(block=block, mode=mode, fmt=fmt, impl=impl)
     payload, scales = taco.taco_compress(to_dev(x), p)
     torch.cuda.synchronize()
     rp, rs, z = oracle.compress(x, block=block, mode=mode, fmt=fmt, want_z=True)
@@ -45,11 +48,12 @@ def test_variant_parity(oracle, mode, fmt, block, name):
     P.check_recon(bits_of(out), ref, block, f"mode={mode} fmt={fmt}", min_exact=P.RECON_EXACT_MIN_SUM)
 
 
-@pytest.mark.parametrize("mode,fmt", [(7, 1), (4, 0), (7, 2), (2, 0)])
-def test_variant_sum_and_layout(oracle, mode, fmt):
+@pytest.mark.parametrize("mode,fmt", [(7, 1), (4, 0), (7, 2), (2, 0), (0, 1), (5, 2), (3, 0), (1, 0)])
+@pytest.mark.parametrize("block", [128, 512, 64])
+def test_variant_sum_and_layout(oracle, mode, fmt, block):
     """decompress_sum, the fused sum -> compress and the interleaved layout go through the same variant code."""
     rng = np.random.default_rng(mode * 10 + fmt)
-    n, block = 128 * 37 + 19, 128
+    n = 2048 * 2 + 128 * 5 + 19
     xs = [W.float32_to_bf16_bits((rng.standard_normal(n) * 0.02 * (i + 1)).astype(np.float32)) for i in range(3)]
     enc = [oracle.compress(x, block=block, mode=mode, fmt=fmt) for x in xs]
     ref = oracle.decompress_sum([e[0] for e in enc], [e[1] for e in enc], n, block=block, mode=mode, fmt=fmt)
@@ -74,11 +78,11 @@ def test_variant_sum_and_layout(oracle, mode, fmt):
     assert np.array_equal(gp, sp.cpu().numpy()) and np.array_equal(gs, ss.cpu().numpy())
 
 
-@pytest.mark.parametrize("mode,fmt", [(7, 1), (6, 0), (6, 1), (7, 2), (6, 2)])
+@pytest.mark.parametrize("mode,fmt", [(7, 1), (6, 0), (6, 1), (7, 2), (6, 2), (4, 0), (0, 0), (2, 1), (5, 2), (3, 0)])
 @pytest.mark.parametrize("block,layout", [(64, 0), (128, 1), (256, 0), (512, 1), (32, 0)])
 def test_variants_on_the_matrix_cores(oracle, mode, fmt, block, layout):
-    """The variants the matrix-core kernels cover (E5M2 and INT8 code books, no adaptive rescaling), forced onto them with
-    impl = MFMA: every entry point against the oracle, k = 8 so that the two-waves-per-workgroup form runs too."""
+    """Variants on the matrix-core kernels (impl = MFMA), every entry point against the oracle, k = 8 so that the
+    two-waves-per-workgroup form runs too."""
     w = W.WORKLOADS["qwen_act"]
     k, rows = 8, 4                                       # 4 x 5120 elements = 10 tiles per payload
     xs = [W.generate_rows(w, 0, rows * i, rows) for i in range(k)]
@@ -90,7 +94,8 @@ def test_variants_on_the_matrix_cores(oracle, mode, fmt, block, layout):
     torch.cuda.synchronize()
     gp, gs = P.deinterleave(buf.cpu().numpy(), block) if layout else (buf.cpu().numpy(), sc.cpu().numpy())
     P.check_scales(gs, enc[0][1], f"mfma mode={mode} fmt={fmt}")
-    P.check_codes(gp, enc[0][0], enc[0][1], block, f"mfma mode={mode} fmt={fmt}", fmt=fmt, z=z0)
+    P.check_codes(gp, enc[0][0], enc[0][1], block, f"mfma mode={mode} fmt={fmt}", fmt=fmt, z=z0,
+                  min_match=P.CODE_MATCH_MIN if mode & 2 else P.CODE_MATCH_MIN_UNROTATED)
     if layout:
         dp, ds = [torch.from_numpy(P.interleave(e[0], e[1], block)).to(DEV) for e in enc], [None] * k
     else:
@@ -110,7 +115,8 @@ def test_variants_on_the_matrix_cores(oracle, mode, fmt, block, layout):
     bb, bs = taco.taco_compress(to_dev(xs[0]), pb)
     torch.cuda.synchronize()
     bp, bsc = P.deinterleave(bb.cpu().numpy(), block) if layout else (bb.cpu().numpy(), bs.cpu().numpy())
-    P.check_codes(bp, enc[0][0], enc[0][1], block, f"butterfly mode={mode} fmt={fmt}", fmt=fmt, z=z0)
+    P.check_codes(bp, enc[0][0], enc[0][1], block, f"butterfly mode={mode} fmt={fmt}", fmt=fmt, z=z0,
+                  min_match=P.CODE_MATCH_MIN if mode & 2 else P.CODE_MATCH_MIN_UNROTATED)
 
 
 def test_error_report(oracle, capsys):
