@@ -56,12 +56,19 @@ int decode(const DecodeTable& tab, int count, int k, int64_t workgroups, const C
         return with_variant(call, [&](auto layout, auto fmt, auto generic) {
             constexpr bool kIl = decltype(layout)::value, kGen = decltype(generic)::value;
             constexpr int kFmt = decltype(fmt)::value;
+            // the fused form of the variants keeps three items in flight instead of four: with four it needs more than
+            // 256 registers and only one wave fits a SIMD (measured: 465 us instead of 333 us on the bench tensors)
             if (recompress)
-                return launch(decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, true, 1, kFmt, kGen>, grid, dim3(64), st, tab, count, k,
+                return launch(decompress_sum_mfma_kernel<kRB, kSub, kGen ? 3 : 4, kIl, true, 1, kFmt, kGen>, grid, dim3(64), st, tab, count, k,
                               tiles_per_wave, call.tau, call.eps, call.mode);
-            // the plain decode differs between the flavours only in how its sign table is built: one instantiation
+            // Plain decode.  One payload of the method itself: the lean kernel (one running sign tile, three
+            // (tile, payload) items in flight per wave, three waves per SIMD).  Otherwise the kernel with the
+            // sign table (four items, two waves per SIMD), which also knows the variants without the rotation.
             if (wide)
                 return launch(decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 2, kFmt, true>, grid, dim3(128), st, tab, count, k,
+                              tiles_per_wave, 0.0f, 0.0f, call.mode);
+            if (!kGen && k == 1)
+                return launch(decompress_sum_mfma_kernel<kRB, kSub, 3, kIl, false, 1, kFmt, false>, grid, dim3(64), st, tab, count, k,
                               tiles_per_wave, 0.0f, 0.0f, call.mode);
             return launch(decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 1, kFmt, true>, grid, dim3(64), st, tab, count, k,
                           tiles_per_wave, 0.0f, 0.0f, call.mode);

@@ -554,10 +554,21 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
     // output's is ph: entries with eh != ph are zero and the eh & ph term of the sign drops out.
     // Variants without the rotation (mode bit 2 clear) multiply by the identity instead: entry 1 where
     // e = p, i.e. 64 m + 16 g + b = 8 n16 + nt, zero elsewhere.
+    //
+    // All 8 tiles in registers take 64 of them.  The lean plain decode (kGray) keeps ONE: the sign splits into parity(b%8 & nt), the same for every lane, and a part that does not depend
+    // on nt, so tile nt is tile 0 with fixed bytes negated, and walking nt through a Gray code
+    // (0 1 3 2 6 7 5 4) takes one XOR mask per step: bit 0 of nt negates bytes 1 and 3 of every dword, bit 1
+    // bytes 2 and 3, bit 2 every byte of the odd dwords.  The 52 XORs per (tile, payload) item run in the
+    // shadow of the matrix instructions; the 56 registers saved let a third wave share the SIMD.  Measured on
+    // MI355X this pays for one payload (decompress: 2-3 % faster) and costs 3 % from two payloads on, where more
+    // waves in flight mean more open DRAM pages per stream; the host side picks the flavour accordingly.
     constexpr uint32_t kPlusOne = kFormat == 2 ? 0x01010101u : 0x38383838u;
     constexpr uint32_t kNegate = kFormat == 2 ? 0xFEu : 0x80u;              // +1 ^ -1, per byte
+    constexpr uint32_t kFlipMask[3] = {kNegate << 8 | kNegate << 24, kNegate << 16 | kNegate << 24, kNegate * 0x01010101u};
+    constexpr bool kGray = !kGeneric && !kRecompress;
     const bool rotate = kGeneric ? (mode & 2) != 0 : true;
-    uint32_t hb[8][8];
+    uint32_t hb[kGray ? 1 : 8][8];
+    uint32_t live_half[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};     // lean flavour, kSub > 1: all ones where half m of the operand is not zero
 #pragma unroll
     for (int d = 0; d < 8; ++d) {
         const int m = d >> 2;
@@ -568,8 +579,9 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
         if (kSub > 1) sgn ^= parity32(eh & ph);
         const uint32_t lane_sign = (sgn & 1) ? kNegate * 0x01010101u : 0u;
         const int e0 = 64 * m + 16 * g + 4 * (d & 3);      // element of byte 0 of this dword
+        if (!same_block) live_half[m] = 0u;
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt) {
+        for (int nt = 0; nt < (kGray ? 1 : 8); ++nt) {
             uint32_t w = kPlusOne;
 #pragma unroll
             for (int bb = 0; bb < 4; ++bb) {
@@ -644,28 +656,47 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
             if (tile == partial_tile && my_block >= partial_blocks) factor = 0.0f;
             if (q + kRing < n_items) fetch(p);      // refill this ring slot
             f32x4 d[8];
-            if (kFormat == 2) {
-                const i32x4 av0 = __builtin_bit_cast(i32x4, a0), av1 = __builtin_bit_cast(i32x4, a1);
+            // The B operand of column tile nt: from the table, or (lean flavour) the running tile, which starts
+            // every item as tile 0 and is stepped along the Gray code.  The empty asm keeps the optimiser from
+            // recognising the stepped tiles as loop invariants and holding all eight in registers again.
+            uint32_t cur[8];
 #pragma unroll
-                for (int nt = 0; nt < 8; ++nt) {
-                    const i32x4 b0 = {static_cast<int>(hb[nt][0]), static_cast<int>(hb[nt][1]), static_cast<int>(hb[nt][2]), static_cast<int>(hb[nt][3])};
-                    const i32x4 b1 = {static_cast<int>(hb[nt][4]), static_cast<int>(hb[nt][5]), static_cast<int>(hb[nt][6]), static_cast<int>(hb[nt][7])};
+            for (int w = 0; w < 8; ++w) {
+                cur[w] = hb[0][w];
+                if (kGray) asm volatile("" : "+v"(cur[w]));
+            }
+#pragma unroll
+            for (int step = 0; step < 8; ++step) {
+                const int nt = kGray ? (step ^ (step >> 1)) : step;           // Gray code: 0 1 3 2 6 7 5 4
+                if (!kGray) {
+#pragma unroll
+                    for (int w = 0; w < 8; ++w) cur[w] = hb[nt][w];
+                }
+                if (kFormat == 2) {
+                    const i32x4 av0 = __builtin_bit_cast(i32x4, a0), av1 = __builtin_bit_cast(i32x4, a1);
+                    const i32x4 b0 = {static_cast<int>(cur[0]), static_cast<int>(cur[1]), static_cast<int>(cur[2]), static_cast<int>(cur[3])};
+                    const i32x4 b1 = {static_cast<int>(cur[4]), static_cast<int>(cur[5]), static_cast<int>(cur[6]), static_cast<int>(cur[7])};
                     i32x4 di = __builtin_amdgcn_mfma_i32_16x16x64_i8(av0, b0, i32x4{0, 0, 0, 0}, 0, 0, 0);
                     di = __builtin_amdgcn_mfma_i32_16x16x64_i8(av1, b1, di, 0, 0, 0);
                     d[nt] = f32x4{static_cast<float>(di[0]), static_cast<float>(di[1]), static_cast<float>(di[2]), static_cast<float>(di[3])};
-                }
-            } else {
-                i32x8 av;
-                av[0] = a0.x; av[1] = a0.y; av[2] = a0.z; av[3] = a0.w;
-                av[4] = a1.x; av[5] = a1.y; av[6] = a1.z; av[7] = a1.w;
+                } else {
+                    i32x8 av, bv;
+                    av[0] = a0.x; av[1] = a0.y; av[2] = a0.z; av[3] = a0.w;
+                    av[4] = a1.x; av[5] = a1.y; av[6] = a1.z; av[7] = a1.w;
 #pragma unroll
-                for (int nt = 0; nt < 8; ++nt) {
-                    i32x8 bv;
-#pragma unroll
-                    for (int w = 0; w < 8; ++w) bv[w] = hb[nt][w];
+                    for (int w = 0; w < 8; ++w) bv[w] = cur[w];
                     // A operand format: 0 = E4M3 codes, 1 = E5M2 codes; the +-1 entries of B stay E4M3.
                     d[nt] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
                         av, bv, f32x4{0.0f, 0.0f, 0.0f, 0.0f}, kFormat, 0, 0, 0, 0, 0);
+                }
+                if (kGray && step < 7) {
+                    const int next = (step + 1) ^ ((step + 1) >> 1);
+                    const int bit = (nt ^ next) == 1 ? 0 : (nt ^ next) == 2 ? 1 : 2;
+#pragma unroll
+                    for (int w = 0; w < 8; ++w) {
+                        if (bit == 2 && (w & 1) == 0) continue;
+                        cur[w] ^= kSub == 1 ? kFlipMask[bit] : (kFlipMask[bit] & live_half[w >> 2]);
+                    }
                 }
             }
             // Row r of this lane belongs to the block whose factor quad lane r computed.
@@ -747,8 +778,11 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
     }
 }
 
+// The lean plain decode is held to the register budget of three waves per SIMD (168), which it needs a few
+// registers less than it would otherwise take for.
 template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kWaves, int kFormat, bool kGeneric>
-__global__ __launch_bounds__(64 * kWaves) void decompress_sum_mfma_kernel(
+__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu((kGeneric || kRecompress || kSub > 1) ? 1 : 3)))
+void decompress_sum_mfma_kernel(
     DecodeTable tab, int count, int k, int tiles_per_wave, float tau, float eps, int mode) {
     static_assert((kRB == 1 || kRB == 2 || kRB == 4) && (kSub == 1 || kSub == 2 || kSub == 4) && (kRB == 1 || kSub == 1),
                   "block size must be 32, 64, 128, 256 or 512");

@@ -20,6 +20,20 @@ constexpr int kMaxK = 16;             // payloads one decode can add (TACO_MAX_K
 constexpr int kMaxBatch = 32;         // tensors per batched launch (TACO_MAX_BATCH)
 constexpr int kMaxBatchSources = 128; // payloads of all tensors of a batched decode together
 
+// Largest i < count with first[i] <= wg (first[0] = 0): binary search, five dependent scalar loads at most
+// (a linear scan over 32 entries costs a one-shot workgroup a fifth of its life).
+__device__ __forceinline__ int last_not_above(const int64_t (&first)[kMaxBatch + 1], int count, int64_t wg) {
+    int lo = 0;
+    if (count > 1) {
+#pragma unroll
+        for (int step = kMaxBatch / 2; step >= 1; step >>= 1) {
+            const int mid = lo + step;
+            if (mid < count && wg >= first[mid]) lo = mid;
+        }
+    }
+    return lo;
+}
+
 // ---- compress: x -> payload, scales -------------------------------------------------------------
 
 struct CompressItem {
@@ -33,11 +47,8 @@ struct CompressTable {
     CompressItem item[kMaxBatch];
     int64_t first[kMaxBatch + 1];       // first workgroup of tensor i; first[count] = workgroups of the launch
     __device__ __forceinline__ void locate(int64_t wg, int count, int& idx, int64_t& local) const {
-        int found = 0;
-        for (int i = 1; i < count; ++i)
-            if (wg >= first[i]) found = i;
-        idx = found;
-        local = wg - first[found];
+        idx = last_not_above(first, count, wg);
+        local = wg - first[idx];
     }
     __device__ __forceinline__ const void* x(int i) const { return item[i].x; }
     __device__ __forceinline__ void* payload(int i) const { return item[i].payload; }
@@ -56,11 +67,8 @@ struct DecodeTable {
     int64_t n_elems[kMaxBatch];
     int64_t first[kMaxBatch + 1];
     __device__ __forceinline__ void locate(int64_t wg, int count, int& idx, int64_t& local) const {
-        int found = 0;
-        for (int i = 1; i < count; ++i)
-            if (wg >= first[i]) found = i;
-        idx = found;
-        local = wg - first[found];
+        idx = last_not_above(first, count, wg);
+        local = wg - first[idx];
     }
     __device__ __forceinline__ const void* payload(int t, int k, int i) const { return src_payload[t * k + i]; }
     __device__ __forceinline__ const void* scales(int t, int k, int i) const { return src_scales[t * k + i]; }
