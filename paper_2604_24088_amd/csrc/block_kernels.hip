@@ -61,16 +61,17 @@ int decode(const DecodeTable& tab, int count, int k, int64_t workgroups, const C
             if (recompress)
                 return launch(decompress_sum_mfma_kernel<kRB, kSub, kGen ? 3 : 4, kIl, true, 1, kFmt, kGen>, grid, dim3(64), st, tab, count, k,
                               tiles_per_wave, call.tau, call.eps, call.mode);
-            // Plain decode.  One payload of the method itself: the lean kernel (one running sign tile, three
-            // (tile, payload) items in flight per wave, three waves per SIMD).  Otherwise the kernel with the
-            // sign table (four items, two waves per SIMD), which also knows the variants without the rotation.
+            // Plain decode of the method itself (kGen = false): one payload goes to the kernel with one running sign
+            // tile (three (tile, payload) items in flight per wave, three waves per SIMD), more to the kernel with
+            // the sign table (four items, two waves per SIMD).  The variants (kGen = true) use the table kernel
+            // that also knows how to leave the rotation out.
             if (wide)
-                return launch(decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 2, kFmt, true>, grid, dim3(128), st, tab, count, k,
+                return launch(decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 2, kFmt, kGen>, grid, dim3(128), st, tab, count, k,
                               tiles_per_wave, 0.0f, 0.0f, call.mode);
             if (!kGen && k == 1)
-                return launch(decompress_sum_mfma_kernel<kRB, kSub, 3, kIl, false, 1, kFmt, false>, grid, dim3(64), st, tab, count, k,
+                return launch(decompress_sum_mfma_kernel<kRB, kSub, 3, kIl, false, 1, kFmt, false, true>, grid, dim3(64), st, tab, count, k,
                               tiles_per_wave, 0.0f, 0.0f, call.mode);
-            return launch(decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 1, kFmt, true>, grid, dim3(64), st, tab, count, k,
+            return launch(decompress_sum_mfma_kernel<kRB, kSub, 4, kIl, false, 1, kFmt, kGen>, grid, dim3(64), st, tab, count, k,
                           tiles_per_wave, 0.0f, 0.0f, call.mode);
         });
     }

@@ -397,14 +397,22 @@ struct CompressLane {
             const u32x4* chunks = reinterpret_cast<const u32x4*>(lds);
             u32x4* dst = reinterpret_cast<u32x4*>(payload) + tile * Layout::kTileChunks;
             const int lane = 16 * g + n16;
-            // 8-byte words of the tile that exist (records are a whole number of words, not of chunks)
-            const int words = blocks_left >= kBlocksPerTile ? Layout::kTileWords : static_cast<int>(blocks_left) * Layout::kRecordWords;
+            if (blocks_left >= kBlocksPerTile) {
 #pragma unroll
-            for (int c = 0; c < (Layout::kTileChunks + 63) / 64; ++c) {
-                const int chunk = 64 * c + lane;
-                if (2 * chunk + 2 <= words) store_stream<true>(&dst[chunk], chunks[chunk]);
-                else if (2 * chunk + 1 <= words)
-                    store_stream<true>(reinterpret_cast<u32x2*>(&dst[chunk]), u32x2{chunks[chunk].x, chunks[chunk].y});
+                for (int c = 0; c < (Layout::kTileChunks + 63) / 64; ++c) {
+                    const int chunk = 64 * c + lane;
+                    if (chunk < Layout::kTileChunks) store_stream<true>(&dst[chunk], chunks[chunk]);
+                }
+            } else {
+                // partial last tile: only the 8-byte words of the records that exist (a whole number of words, not of chunks)
+                const int words = static_cast<int>(blocks_left) * Layout::kRecordWords;
+#pragma unroll
+                for (int c = 0; c < (Layout::kTileChunks + 63) / 64; ++c) {
+                    const int chunk = 64 * c + lane;
+                    if (2 * chunk + 2 <= words) store_stream<true>(&dst[chunk], chunks[chunk]);
+                    else if (2 * chunk + 1 <= words)
+                        store_stream<true>(reinterpret_cast<u32x2*>(&dst[chunk]), u32x2{chunks[chunk].x, chunks[chunk].y});
+                }
             }
             wave_lds_sync();
         }
@@ -479,7 +487,7 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(CompressTable tab, in
 // The work of one wave: output tiles [tile_begin, tile_end) of tensor idx.  kGuarded = true is the copy that the
 // one wave owning a partial last tile runs (bounds-checked loads and stores for that tile); every other wave runs
 // the kGuarded = false copy, in which all of those checks are compiled out.
-template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kFormat, bool kGeneric, bool kGuarded>
+template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kFormat, bool kGeneric, bool kGray, bool kGuarded>
 __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int k, int64_t n, int64_t tile_begin, int64_t tile_end,
                                             u32x4* lds, float tau, float eps, int mode) {
     constexpr int kBlock = 128 * kRB / kSub;
@@ -565,7 +573,7 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
     constexpr uint32_t kPlusOne = kFormat == 2 ? 0x01010101u : 0x38383838u;
     constexpr uint32_t kNegate = kFormat == 2 ? 0xFEu : 0x80u;              // +1 ^ -1, per byte
     constexpr uint32_t kFlipMask[3] = {kNegate << 8 | kNegate << 24, kNegate << 16 | kNegate << 24, kNegate * 0x01010101u};
-    constexpr bool kGray = !kGeneric && !kRecompress;
+    static_assert(!(kGray && (kGeneric || kRecompress)), "the running sign tile serves the lean plain decode only");
     const bool rotate = kGeneric ? (mode & 2) != 0 : true;
     uint32_t hb[kGray ? 1 : 8][8];
     uint32_t live_half[2] = {0xFFFFFFFFu, 0xFFFFFFFFu};     // lean flavour, kSub > 1: all ones where half m of the operand is not zero
@@ -764,9 +772,7 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
                     // them resident the kernel needs more than 256 registers and only one wave fits a SIMD.  The
                     // empty asm hides the lane number from the optimiser, which would otherwise hoist the constants
                     // out of the loop again.
-                    int lane_again = lane;
-                    asm volatile("" : "+v"(lane_again));
-                    const CompressLane<kRB, kSub> cl(lane_again);
+                    const CompressLane<kRB, kSub> cl(lane);
                     cl.template tile_from_lds<kInterleaved, kFormat, kGeneric>(lds_c, tile, n_blocks - tile * kBlocksPerTile, tau, eps, mode,
                                                                      static_cast<u32x2*>(tab.payload_output(idx)),
                                                                      static_cast<f32x2*>(tab.scales_output(idx)));
@@ -778,10 +784,10 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
     }
 }
 
-// The lean plain decode is held to the register budget of three waves per SIMD (168), which it needs a few
-// registers less than it would otherwise take for.
-template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kWaves, int kFormat, bool kGeneric>
-__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu((kGeneric || kRecompress || kSub > 1) ? 1 : 3)))
+// kGray: the lean plain decode with one running sign tile; it is held to the register budget of three waves per
+// SIMD (168), which it needs a few registers less than it would otherwise take for.
+template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kWaves, int kFormat, bool kGeneric, bool kGray = false>
+__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu((kGray && kSub == 1) ? 3 : 1)))
 void decompress_sum_mfma_kernel(
     DecodeTable tab, int count, int k, int tiles_per_wave, float tau, float eps, int mode) {
     static_assert((kRB == 1 || kRB == 2 || kRB == 4) && (kSub == 1 || kSub == 2 || kSub == 4) && (kRB == 1 || kSub == 1),
@@ -801,10 +807,12 @@ void decompress_sum_mfma_kernel(
     int64_t tile_end = tile_begin + tiles_per_wave;
     if (tile_end > n_tiles) tile_end = n_tiles;
     if (tile_end <= tile_begin) return;      // a wave past the end (last workgroup of a tensor only)
+    // The guarded copy runs in one wave per tensor; it keeps two items in flight instead of kRing so that its extra
+    // bookkeeping does not raise the register count of the kernel (which every wave pays for in occupancy).
     if (tile_end == n_tiles && (n % kTileElems) != 0)
-        decode_wave<kRB, kSub, kRing, kInterleaved, kRecompress, kFormat, kGeneric, true>(tab, idx, k, n, tile_begin, tile_end, lds_all[wave], tau, eps, mode);
+        decode_wave<kRB, kSub, 2, kInterleaved, kRecompress, kFormat, kGeneric, kGray, true>(tab, idx, k, n, tile_begin, tile_end, lds_all[wave], tau, eps, mode);
     else
-        decode_wave<kRB, kSub, kRing, kInterleaved, kRecompress, kFormat, kGeneric, false>(tab, idx, k, n, tile_begin, tile_end, lds_all[wave], tau, eps, mode);
+        decode_wave<kRB, kSub, kRing, kInterleaved, kRecompress, kFormat, kGeneric, kGray, false>(tab, idx, k, n, tile_begin, tile_end, lds_all[wave], tau, eps, mode);
 }
 
 }  // namespace taco
