@@ -15,7 +15,9 @@ the launch stream); `calls_back_to_back` times 16 launches of one call in a row,
 costs when the host's launch time is not in the way.  `workloads` carries the same two measurements for
 every one of the five benchmark configurations (steps rotate through enough buffer sets to defeat the
 last-level cache).  `mix_yardstick` times memory-only kernels (taco_debug_traffic) that move exactly the
-bytes of each call and compute nothing: what the memory system gives that mix.
+bytes of each call and compute nothing: what the memory system gives that mix.  `calls_same_payload_k_times`
+is the opposite cut: the decode calls with one payload given k times, so that the reads come from cache and
+the time left is what the kernel needs for everything but HBM.
 The roofline object prices the dominant kernel (compress) by its ALGORITHMIC bytes (3.0625 B per
 element at block 128) over its average launch duration inside the timed region.
 `cpu_baseline` / `cpu_baseline_1thread`: the CPU oracle, as it stands, on a stated sample of the same
@@ -42,13 +44,13 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
 # WRITE_SIZE runs, scaled by a copy kernel of known size); None until measured.  The summary
 # the number comes from is committed under profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    # fetch 393250 KiB + write 208896 KiB per compress launch: profiles/mfma_kernels_large_k8.txt
-    ("large_k8", 128, "auto"): 616597437,
+    # fetch 393251 KiB + write 208896 KiB per compress launch: profiles/mfma_kernels_large_k8.txt
+    ("large_k8", 128, "auto"): 616598479,
 }
 
 # Share of time the matrix cores are busy in the dominant kernel (SQ_VALU_MFMA_BUSY_CYCLES over SIMD-cycles,
 # rocprofv3 --pmc run summarised in the same profile); the Hadamard rotation is an MFMA contraction there.
-MEASURED_MFMA_BUSY = {("large_k8", 128, "auto"): 0.203}
+MEASURED_MFMA_BUSY = {("large_k8", 128, "auto"): 0.206}
 
 
 def parse():
@@ -370,7 +372,24 @@ class Bench:
         return {"compress": self.back_to_back(lambda r, S: taco.taco_debug_traffic([S[0][r % k]], 256, S[4], chunks, n_tiles, st), raw + per),
                 "decompress": self.back_to_back(lambda r, S: taco.taco_debug_traffic([S[0][r % k]], chunks, S[3], 256, n_tiles, st), raw + per),
                 f"decompress_sum_k{k}": self.back_to_back(lambda r, S: taco.taco_debug_traffic(S[0], chunks, S[3], 256, n_tiles, st),
-                                                          k * per + raw)}
+                                                          k * per + raw),
+                f"decompress_sum_compress_k{k}": self.back_to_back(lambda r, S: taco.taco_debug_traffic(S[0], chunks, S[3], chunks, n_tiles, st),
+                                                                   (k + 1) * per)}
+
+    def same_payload_calls(self):
+        """decompress_sum and the fused call with payload 0 given k times: the reads then come from cache (an eighth of
+        the HBM read traffic), so the time left is what the kernel needs for everything but HBM."""
+        taco, p, k, st = self.taco, self.params, self.k, self.stream
+        by = self.bytes_of()
+        fp = self.torch.empty_like(self.sets[0][1][0])
+        fs = self.torch.empty_like(self.sets[0][2][0]) if self.sets[0][2][0] is not None else None
+        out = {f"decompress_sum_k{k}": self.back_to_back(lambda r, S: taco.taco_decompress_sum([S[1][0]] * k, [S[2][0]] * k, S[4].shape, p, S[4], st),
+                                                           by["sum"]),
+               f"decompress_sum_compress_k{k}": self.back_to_back(
+                   lambda r, S: taco.taco_decompress_sum_compress([S[1][0]] * k, [S[2][0]] * k, S[4].shape, p, fp, fs, st), by["fused"])}
+        for e in out.values():
+            del e["moved_GBps"], e["hbm_frac"]           # the bytes do not cross HBM: only the time means something
+        return out
 
     def fused_call(self):
         taco, torch, st = self.taco, self.torch, self.stream
@@ -473,6 +492,7 @@ def main():
     mix = b.yardsticks()
     b2b = b.back_to_back_calls()
     t_fused = b.fused_call()
+    same = b.same_payload_calls() if k > 1 else {}
 
     ms_step = wall * 1e3 / args.steps
     t_comp_avg = sum(per[0]) / len(per[0])               # ms per compress launch, average over the timed region
@@ -510,6 +530,7 @@ def main():
         "copy_yardstick_GBps": round(copy_gbps, 1),
         "mix_yardstick": mix,
         "calls_back_to_back": b2b,
+        "calls_same_payload_k_times": same,
         "calls": {"compress": call_entry(med[0], by["compress"], 2.0 * n),
                   "decompress": call_entry(med[1], by["decompress"], 2.0 * n),
                   f"decompress_sum_k{k}": call_entry(med[2], by["sum"], k * 2.0 * n),

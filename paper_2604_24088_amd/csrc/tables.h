@@ -4,8 +4,8 @@
 // device-side pointer table, nothing to allocate or copy).  The ordinary entry points fill in one
 // tensor; the batched entry points up to kMaxBatch, so that many small tensors (the shards of one
 // exchange, the tensors of several layers) share the ramp-up and the drain of a single launch.  A
-// workgroup finds its tensor with locate(): a scan over the prefix sums of the tensors' workgroup
-// counts, uniform over the workgroup (scalar loads and compares; no iteration for one tensor).
+// workgroup finds its tensor with locate(): a binary search over the prefix sums of the tensors'
+// workgroup counts, uniform over the workgroup (scalar loads and compares; none for one tensor).
 // Only the entries a kernel reads are ever fetched from the argument segment.
 //
 // Tables are indexed directly (tab.item[i]), never through a pointer to a member, so that the

@@ -12,6 +12,9 @@
   --pmc DIR     output directory of any other   rocprofv3 --pmc <counters> ...   run: mean of every counter per kernel
   --elements / --block / --k   when given, the algorithmic bytes of compress, decompress, decompress_sum(k) and the fused
                 call on a tensor of N elements are printed beside the traffic, with the ratio
+  --bench FILE ...   JSON lines printed by bench.py (one file per run): one table row per run with the step and each
+                call's time and share of the HBM peak (in step, back to back, memory-only yardstick), and with
+                --workloads the per-configuration table of the default run
 
 Only the standard library is used; nothing here touches the GPU.
 """
@@ -56,6 +59,58 @@ def counters(directory: str):
     return {k: (n, v / n) for k, (n, v) in agg.items()}
 
 
+def load_bench(path: str):
+    import json
+    for line in open(path):
+        line = line.strip()
+        if line.startswith("{"):
+            return json.loads(line)
+    raise SystemExit(f"no JSON line in {path}")
+
+
+def bench_rows(paths, workloads: bool):
+    """One row per bench.py run: us and share of the 8 TB/s HBM peak (algorithmic bytes / time) per call."""
+    def cell(e):
+        return f"{e['ms'] * 1e3:7.1f} {e['hbm_frac']:.3f}" if e else "      -     -"
+
+    print("== bench.py runs: per call  us  share-of-HBM-peak;  step = ms per step and share for the whole step")
+    print(f"  {'run':44s} {'step':>13s} | in step: {'compress':>13s} {'decompress':>13s} {'sum(k)':>13s} {'sum->compress':>13s} | "
+          f"back to back: {'compress':>13s} {'decompress':>13s} {'sum(k)':>13s} | yardstick: {'compress':>13s} {'decompress':>13s} {'sum(k)':>13s} "
+          f"{'sum->compress':>13s}")
+    for path in paths:
+        r = load_bench(path)
+        c = r["config"]
+        tag = (f"{c['workload'].split(':')[0]} B={c['block']} {c['layout']} {c['impl']} fmt={c['format']} mode={c['mode']}"
+               + (f" chunks={c['chunks_per_call']}x{c['streams']}" if c.get("chunks_per_call", 1) > 1 else "")
+               + (" batch" if c.get("batched_calls") else "") + (" graph" if c.get("hip_graph") else ""))
+        calls = list(r["calls"].values())
+        b2b = list(r.get("calls_back_to_back", {}).values()) + [None] * 3
+        mix = r.get("mix_yardstick", {})
+        mixv = [mix.get("compress"), mix.get("decompress"),
+                next((v for k, v in mix.items() if k.startswith("decompress_sum_k")), None),
+                next((v for k, v in mix.items() if k.startswith("decompress_sum_compress")), None)]
+        print(f"  {tag:44s} {r['ms_per_step']:7.4f} {r['hbm_frac_step']:.3f} |          {cell(calls[0])} {cell(calls[1])} {cell(calls[2])} "
+              f"{cell(calls[3]) if len(calls) > 3 else cell(None)} |               {cell(b2b[0])} {cell(b2b[1])} {cell(b2b[2])} |            "
+              f"{cell(mixv[0])} {cell(mixv[1])} {cell(mixv[2])} {cell(mixv[3])}")
+        if workloads and "workloads" in r:
+            print("  per configuration (steps rotate through `sets` buffer sets so that cache-sized tensors are still timed from HBM):")
+            print(f"    {'workload':12s} {'shape':>16s} {'k':>2s} {'sets':>4s} {'ms/step':>8s} | in step (median): {'compress':>13s} {'decompress':>13s} "
+                  f"{'sum(k)':>13s} | back to back: {'compress':>13s} {'decompress':>13s} {'sum(k)':>13s}")
+            for name, e in r["workloads"].items():
+                i = list(e["in_step_median"].values())
+                b = list(e["back_to_back"].values())
+                print(f"    {name:12s} {str(e['shape']):>16s} {e['payloads']:2d} {e['buffer_sets']:4d} {e['ms_per_step']:8.4f} |                   "
+                      f"{cell(i[0])} {cell(i[1])} {cell(i[2])} |               {cell(b[0])} {cell(b[1])} {cell(b[2])}")
+        if r.get("calls_same_payload_k_times"):
+            print("    one payload given k times (reads from cache): " +
+                  ", ".join(f"{k} {v['ms'] * 1e3:.1f} us" for k, v in r["calls_same_payload_k_times"].items()))
+        for key in ("cpu_baseline", "cpu_baseline_1thread"):
+            if key in r:
+                e = r[key]
+                print(f"    {key}: {e['value']:.4f} {e['unit']} on {e['cores']} thread(s); {e['sample']}")
+    print()
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--stats")
@@ -65,7 +120,11 @@ def main():
     ap.add_argument("--elements", type=int, default=0)
     ap.add_argument("--block", type=int, default=128)
     ap.add_argument("--k", type=int, default=8)
+    ap.add_argument("--bench", nargs="*", default=[])
+    ap.add_argument("--workloads", action="store_true")
     a = ap.parse_args()
+    if a.bench:
+        bench_rows(a.bench, a.workloads)
     if a.stats:
         print("== kernel stats (rocprofv3 --kernel-trace --stats): calls, average / min / max duration in ns, share of GPU time")
         for name, calls, avg, mn, mx, pct in kernel_stats(a.stats):
@@ -103,12 +162,13 @@ def main():
         tab = counters(directory)
         names = sorted({c for (_, _, c) in tab})
         print(f"== counters from {os.path.basename(os.path.normpath(directory))}: mean per dispatch, summed over the chip")
-        print("  " + " " * 78 + " " + "      grid " + " ".join(f"{c:>26s}" for c in names))
         for kname, grid in sorted({(kn, g) for (kn, g, _) in tab}):
-            vals = " ".join(f"{tab.get((kname, grid, c), (0, float('nan')))[1]:26.1f}" for c in names)
-            print(f"  {kname:78s} {grid:>10s} {vals}")
+            print(f"  {kname}  grid={grid}")
+            cells = [f"{c} {tab[(kname, grid, c)][1]:.0f}" for c in names if (kname, grid, c) in tab]
+            for i in range(0, len(cells), 4):
+                print("      " + "   ".join(f"{x:38s}" for x in cells[i:i + 4]).rstrip())
         print()
-    if not (a.stats or a.fetch or a.write or a.pmc):
+    if not (a.stats or a.fetch or a.write or a.pmc or a.bench):
         ap.print_help()
         sys.exit(1)
 
