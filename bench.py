@@ -10,8 +10,13 @@ last-level cache.  Inputs are resident in HBM before the timed region.
 Prints ONE JSON line.  `value` counts bf16-equivalent bytes: 2N per compressed tensor, 2N per
 decompressed tensor, k*2N for decompress_sum (k tensors decoded); `value_out_basis` counts only bf16
 bytes that really cross HBM; `hbm_frac_step` prices the ALGORITHMIC bytes of the whole step.
-`calls` gives the MEDIAN over the timed steps of each call's duration (HIP events between the calls, on
-the launch stream); `calls_back_to_back` times 16 launches of one call in a row, which is what a kernel
+The timed region brackets only the k compress launches of a step with HIP events (the roofline's launch
+duration comes from them); `calls` gives the MEDIAN of each call's duration over the same number of steps
+run once more with events between all calls, on the launch stream.  A launch that follows an event record
+waits about 6 us for the event's marker packet (the kernel trace shows the gap, and kernel durations equal
+to the back-to-back ones), so the in-step times of the two decode calls contain one such gap each, the
+compress time an eighth of one; `ms_per_step_with_events_between_calls` is the step with them.
+`calls_back_to_back` times 16 launches of one call in a row, which is what a kernel
 costs when the host's launch time is not in the way.  `workloads` carries the same two measurements for
 every one of the five benchmark configurations (steps rotate through enough buffer sets to defeat the
 last-level cache).  `mix_yardstick` times memory-only kernels (taco_debug_traffic) that move exactly the
@@ -291,14 +296,15 @@ class Bench:
         _, payloads, scales, _, outk = self.cur
         self.decode(payloads, scales, outk)
 
-    def step(self, ev=None):
+    def step(self, ev=None, split=True):
+        """ev: four events; all are recorded around the three parts when `split`, else only the two around the compress group."""
         self.cur = self.sets[self.step_no % self.n_sets]
         self.step_no += 1
         for j, part in enumerate(self.parts):
-            if ev:
+            if ev and (split or j < 2):
                 ev[j].record(self.stream)
             part()
-        if ev:
+        if ev and split:
             ev[3].record(self.stream)
 
     # ---- measurements -------------------------------------------------------------------------
@@ -319,7 +325,10 @@ class Bench:
                 self.step()
             torch.cuda.synchronize()
 
-    def timed_steps(self, steps, warmup):
+    def timed_steps(self, steps, warmup, split=True):
+        """Wall time of `steps` steps and the HIP-event times per call.  With split = False only the compress group of a step
+        is bracketed by events (per[1], per[2] come back empty): a launch that follows an event record waits about 6 us for the
+        event's marker packet, which a caller who records no events between its calls does not pay."""
         torch = self.torch
         for _ in range(warmup):
             self.step()
@@ -327,10 +336,10 @@ class Bench:
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for s in range(steps):
-            self.step(events[s])
+            self.step(events[s], split)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-        per = [[e[j].elapsed_time(e[j + 1]) for e in events] for j in range(3)]
+        per = [[e[j].elapsed_time(e[j + 1]) for e in events] for j in range(3 if split else 1)]
         per[0] = [v / self.k for v in per[0]]            # per compress launch
         return wall, per
 
@@ -358,6 +367,42 @@ class Bench:
                                                 by["decompress"]),
                 f"decompress_sum_k{k}": self.back_to_back(lambda r, S: taco.taco_decompress_sum(S[1], S[2], S[4].shape, p, S[4], st),
                                                           by["sum"])}
+
+    def batched_calls(self):
+        """The same calls through the batched entry points: ONE launch covers the tensors of up to 32 buffer sets (one ramp-up
+        and one drain for all of them); the time is per tensor."""
+        taco, p, k, st, torch = self.taco, self.params, self.k, self.stream, self.torch
+        by = self.bytes_of()
+        sets = self.sets[:max(1, min(self.n_sets, taco.TACO_MAX_BATCH // k, taco.TACO_MAX_BATCH_PAYLOADS // k))]
+        R = len(sets)
+        if R == 1 and k == 1:
+            return {}
+
+        def run(fn, count, alg_bytes):
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            for _ in range(2):
+                fn()
+            ev[0].record(st)
+            for _ in range(8):
+                fn()
+            ev[1].record(st)
+            torch.cuda.synchronize()
+            ms = ev[0].elapsed_time(ev[1]) / 8 / count
+            return {"tensors_per_launch": count, "ms": round(ms, 4), "moved_GBps": round(alg_bytes / ms / 1e6, 1),
+                    "hbm_frac": round(alg_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4)}
+
+        xs = [x for S in sets for x in S[0]]
+        pl = [x for S in sets for x in S[1]]
+        sc = [x for S in sets for x in S[2]]
+        out = {"compress": run(lambda: taco.taco_compress_batch(xs, p, pl, sc, st), len(xs), by["compress"])}
+        if R > 1:
+            out["decompress"] = run(lambda: taco.taco_decompress_sum_batch([[S[1][0]] for S in sets], [[S[2][0]] for S in sets],
+                                                                          [S[3].shape for S in sets], p, [S[3] for S in sets], st),
+                                    R, by["decompress"])
+            out[f"decompress_sum_k{k}"] = run(lambda: taco.taco_decompress_sum_batch([S[1] for S in sets], [S[2] for S in sets],
+                                                                                   [S[4].shape for S in sets], p, [S[4] for S in sets], st),
+                                              R, by["sum"])
+        return out
 
     def yardsticks(self):
         """Memory-only kernels with the traffic of each call (set layout: xs, payloads, scales, out1, outk; the bf16
@@ -415,7 +460,8 @@ def call_entry(ms, alg_bytes, bf16_bytes):
 def workload_entry(b, steps, warmup, settle_ms):
     """In-step medians and back-to-back times of one workload (k compress + 1 decompress + 1 decompress_sum(k))."""
     b.settle(settle_ms)
-    wall, per = b.timed_steps(steps, warmup)
+    wall, _ = b.timed_steps(steps, warmup, split=False)
+    _, per = b.timed_steps(steps, 0)
     by, k, n = b.bytes_of(), b.k, b.n
     med = [statistics.median(v) for v in per]
     moved = k * by["compress"] + by["decompress"] + by["sum"]
@@ -425,7 +471,7 @@ def workload_entry(b, steps, warmup, settle_ms):
             "in_step_median": {"compress": call_entry(med[0], by["compress"], 2.0 * n),
                                "decompress": call_entry(med[1], by["decompress"], 2.0 * n),
                                f"decompress_sum_k{k}": call_entry(med[2], by["sum"], k * 2.0 * n)},
-            "back_to_back": b.back_to_back_calls()}
+            "back_to_back": b.back_to_back_calls(), "batched": b.batched_calls()}
 
 
 def cold_trace(args, taco, torch, W, params):
@@ -471,7 +517,8 @@ def main():
               graph=args.graph, batch=args.batch)
     w, k, n = b.w, b.k, b.n
     b.settle(args.settle_ms)
-    wall, per = b.timed_steps(args.steps, args.warmup)
+    wall, per_timed = b.timed_steps(args.steps, args.warmup, split=False)       # THE timed region
+    wall_split, per = b.timed_steps(args.steps, 0)                              # the same steps again with events between all calls
 
     # ---- yardstick outside the timed region: plain copy of 1 GiB (reads 1 GiB, writes 1 GiB)
     xs = b.sets[0][0]
@@ -495,7 +542,7 @@ def main():
     same = b.same_payload_calls() if k > 1 else {}
 
     ms_step = wall * 1e3 / args.steps
-    t_comp_avg = sum(per[0]) / len(per[0])               # ms per compress launch, average over the timed region
+    t_comp_avg = sum(per_timed[0]) / len(per_timed[0])   # ms per compress launch, average over the timed region
     med = [statistics.median(v) for v in per]
     by = b.bytes_of()
     equiv = (k + 1 + k) * 2.0 * n                        # bf16-equivalent bytes per step
@@ -511,6 +558,7 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_step, 4),
+        "ms_per_step_with_events_between_calls": round(wall_split * 1e3 / args.steps, 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -536,8 +584,8 @@ def main():
                   f"decompress_sum_k{k}": call_entry(med[2], by["sum"], k * 2.0 * n),
                   f"decompress_sum_compress_k{k} (not in the step)": call_entry(t_fused, by["fused"], k * 2.0 * n)},
         "roofline": {"kernel": (f"compress_mfma_kernel<{max(B // 128, 1)},{max(128 // B, 1)},{'true' if il else 'false'},"
-                                f"{ {'e4m3': 0, 'e5m2': 1, 'int8': 2}[args.format] },CompressSingle>")
-                     if on_mfma else f"compress_butterfly_kernel<{B},CompressSingle>",
+                                f"{ {'e4m3': 0, 'e5m2': 1, 'int8': 2}[args.format] },{'false' if (args.mode & 6) == 6 else 'true'}>")
+                     if on_mfma else f"compress_butterfly_kernel<{B}>",
                      "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, B, args.impl)) if not il and not variant else None,
@@ -551,7 +599,7 @@ def main():
         table = {w.name: {"shape": [w.tokens, w.hidden], "payloads": k, "buffer_sets": b.n_sets, "ms_per_step": round(ms_step, 4),
                           "hbm_frac_step": result["hbm_frac_step"], "in_step_median": {kk: vv for kk, vv in result["calls"].items()
                                                                                       if "not in the step" not in kk},
-                          "back_to_back": b2b}}
+                          "back_to_back": b2b, "batched": b.batched_calls()}}
         keep = (payloads0, scales0)
         del b, xs, src
         torch.cuda.empty_cache()

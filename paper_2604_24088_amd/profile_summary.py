@@ -1,6 +1,6 @@
 """Turns rocprofv3 CSV output into the short text tables kept under profiles/.
 
-    python -m paper_2604_24088_amd.profile_summary [--stats DIR] [--fetch DIR] [--write DIR] [--pmc DIR ...]
+    python -m paper_2604_24088_amd.profile_summary [--stats DIR] [--trace DIR] [--fetch DIR] [--write DIR] [--pmc DIR ...]
                                                    [--elements N --block B --k K]
 
   --stats DIR   output directory of   rocprofv3 --kernel-trace --stats --output-format csv -d DIR -o bench -- python3 bench.py ...
@@ -12,6 +12,9 @@
   --pmc DIR     output directory of any other   rocprofv3 --pmc <counters> ...   run: mean of every counter per kernel
   --elements / --block / --k   when given, the algorithmic bytes of compress, decompress, decompress_sum(k) and the fused
                 call on a tensor of N elements are printed beside the traffic, with the ratio
+  --trace DIR   the same directory as --stats (it holds the kernel trace): per kernel, the median duration and the median idle gap
+                before it, apart for launches that follow another kernel (as in a bench step) and launches that follow the same
+                kernel (back-to-back runs); the gap is what HIP-event times between calls contain beside the kernel itself
   --bench FILE ...   JSON lines printed by bench.py (one file per run): one table row per run with the step and each
                 call's time and share of the HBM peak (in step, back to back, memory-only yardstick), and with
                 --workloads the per-configuration table of the default run
@@ -59,6 +62,28 @@ def counters(directory: str):
     return {k: (n, v / n) for k, (n, v) in agg.items()}
 
 
+def trace_split(directory: str):
+    """Median duration and preceding idle gap per kernel, split by whether the previous kernel on the device was the same one."""
+    import statistics
+    rows = list(csv.DictReader(open(find_csv(directory, "kernel_trace.csv"))))
+    seq = sorted((int(r["Start_Timestamp"]), int(r["End_Timestamp"]), short(r["Kernel_Name"])) for r in rows)
+    groups = collections.defaultdict(lambda: ([], []))
+    for (s0, e0, n0), (s1, e1, n1) in zip(seq, seq[1:]):
+        dur, gap = groups[(n1, n0 == n1)]
+        dur.append(e1 - s1)
+        gap.append(s1 - e0)
+    print("== kernel trace: median duration (ns) by what ran before the launch, and the idle gaps before it (a launch that "
+          "follows a HIP event record waits for the event's marker packet; launches that follow a kernel directly show no gap)")
+    for (name, same), (dur, gap) in sorted(groups.items()):
+        if len(dur) < 4:
+            continue
+        held = [g for g in gap if g > 1000]
+        print(f"  {name:78s} after {'itself        ' if same else 'another kernel'} launches={len(dur):4d} "
+              f"duration={statistics.median(dur):9.0f}  launches with a gap over 1 us: {len(held):4d}"
+              + (f", their median gap {statistics.median(held):7.0f}" if held else ""))
+    print()
+
+
 def load_bench(path: str):
     import json
     for line in open(path):
@@ -95,12 +120,16 @@ def bench_rows(paths, workloads: bool):
         if workloads and "workloads" in r:
             print("  per configuration (steps rotate through `sets` buffer sets so that cache-sized tensors are still timed from HBM):")
             print(f"    {'workload':12s} {'shape':>16s} {'k':>2s} {'sets':>4s} {'ms/step':>8s} | in step (median): {'compress':>13s} {'decompress':>13s} "
-                  f"{'sum(k)':>13s} | back to back: {'compress':>13s} {'decompress':>13s} {'sum(k)':>13s}")
+                  f"{'sum(k)':>13s} | back to back: {'compress':>13s} {'decompress':>13s} {'sum(k)':>13s} | batched, per tensor: {'compress':>13s} "
+                  f"{'decompress':>13s} {'sum(k)':>13s}")
             for name, e in r["workloads"].items():
                 i = list(e["in_step_median"].values())
                 b = list(e["back_to_back"].values())
+                bt = e.get("batched", {})
+                bt = [bt.get("compress"), bt.get("decompress"), next((v for k, v in bt.items() if k.startswith("decompress_sum_k")), None)]
                 print(f"    {name:12s} {str(e['shape']):>16s} {e['payloads']:2d} {e['buffer_sets']:4d} {e['ms_per_step']:8.4f} |                   "
-                      f"{cell(i[0])} {cell(i[1])} {cell(i[2])} |               {cell(b[0])} {cell(b[1])} {cell(b[2])}")
+                      f"{cell(i[0])} {cell(i[1])} {cell(i[2])} |               {cell(b[0])} {cell(b[1])} {cell(b[2])} |                      "
+                      f"{cell(bt[0])} {cell(bt[1])} {cell(bt[2])}")
         if r.get("calls_same_payload_k_times"):
             print("    one payload given k times (reads from cache): " +
                   ", ".join(f"{k} {v['ms'] * 1e3:.1f} us" for k, v in r["calls_same_payload_k_times"].items()))
@@ -114,6 +143,7 @@ def bench_rows(paths, workloads: bool):
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("--stats")
+    ap.add_argument("--trace")
     ap.add_argument("--fetch")
     ap.add_argument("--write")
     ap.add_argument("--pmc", action="append", default=[])
@@ -130,6 +160,8 @@ def main():
         for name, calls, avg, mn, mx, pct in kernel_stats(a.stats):
             print(f"  {name:78s} calls={calls:5d} avg_ns={avg:10.1f} min_ns={mn:8d} max_ns={mx:8d} pct={pct:5.2f}")
         print()
+    if a.trace:
+        trace_split(a.trace)
     if a.fetch or a.write:
         print("== HBM traffic counters: mean per dispatch in KiB as the counter reports it, and scaled by the copy kernel "
               f"(which moves {COPY_KIB:.0f} KiB each way)")
@@ -168,7 +200,7 @@ def main():
             for i in range(0, len(cells), 4):
                 print("      " + "   ".join(f"{x:38s}" for x in cells[i:i + 4]).rstrip())
         print()
-    if not (a.stats or a.fetch or a.write or a.pmc or a.bench):
+    if not (a.stats or a.trace or a.fetch or a.write or a.pmc or a.bench):
         ap.print_help()
         sys.exit(1)
 
