@@ -487,7 +487,8 @@ __global__ __launch_bounds__(64) void compress_mfma_kernel(CompressTable tab, in
 // The work of one wave: output tiles [tile_begin, tile_end) of tensor idx.  kGuarded = true is the copy that the
 // one wave owning a partial last tile runs (bounds-checked loads and stores for that tile); every other wave runs
 // the kGuarded = false copy, in which all of those checks are compiled out.
-template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kFormat, bool kGeneric, bool kGray, bool kGuarded>
+template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kFormat, bool kGeneric, bool kGray, bool kGuarded,
+          bool kAligned = false>
 __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int k, int64_t n, int64_t tile_begin, int64_t tile_end,
                                             u32x4* lds, float tau, float eps, int mode) {
     constexpr int kBlock = 128 * kRB / kSub;
@@ -519,7 +520,7 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
     int pf_i = 0;
     auto fetch = [&](int p) {
         const u32x4* src = static_cast<const u32x4*>(tab.payload(idx, k, pf_i)) + pf_tile * Layout::kTileChunks;
-        if (pf_tile != partial_tile) {
+        if (!kGuarded || pf_tile != partial_tile) {
             stage[p][0] = load16<true>(&src[lane]);
             stage[p][1] = load16<true>(&src[64 + lane]);
             if (kInterleaved) {
@@ -633,11 +634,12 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
     f32x4 sum[8];
     int64_t tile = tile_begin;
     int i = 0;
-    for (int q0 = 0; q0 < n_items; q0 += kRing) {
-#pragma unroll
-        for (int p = 0; p < kRing; ++p) {
-            const int q = q0 + p;
-            if (q >= n_items) break;
+    // One (tile, payload) item from ring slot p.  refill: fetch the item kRing places ahead into the slot;
+    // tile_may_end: whether this item can be the last payload of its tile (the epilogue is compiled in).
+    auto item = [&](int p, bool refill, bool tile_may_end) {
+            // items stay in program order: without the fence the scheduler overlaps the straight-line items of a round and
+            // the kernel no longer fits the register budget of two waves per SIMD
+            __builtin_amdgcn_sched_barrier(0);
             lds[wr_slot[0]] = stage[p][0];
             lds[wr_slot[1]] = stage[p][1];
             if (kInterleaved && lane < kExtraChunks) lds[128 + lane] = stage[p][kLoads - 1];
@@ -661,8 +663,8 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
             // block past the end of the tensor (its codes read as zeros, its scalars are not read at all).
             // Taken before the refill below, so that the slot's old scalars are dead when it is issued.
             float factor = sc.y * __builtin_amdgcn_rcpf(sc.x) * inv_root_b;
-            if (tile == partial_tile && my_block >= partial_blocks) factor = 0.0f;
-            if (q + kRing < n_items) fetch(p);      // refill this ring slot
+            if (kGuarded && tile == partial_tile && my_block >= partial_blocks) factor = 0.0f;
+            if (refill) fetch(p);
             f32x4 d[8];
             // The B operand of column tile nt: from the table, or (lean flavour) the running tile, which starts
             // every item as tile 0 and is stepped along the Gray code.  The empty asm keeps the optimiser from
@@ -723,12 +725,12 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
                     sum[nt][3] = __builtin_fmaf(d[nt][3], f3, sum[nt][3]);
                 }
             }
-            if (++i == k) {
+            if (tile_may_end && ++i == k) {
 #pragma unroll
                 for (int nt = 0; nt < 8; ++nt) {
                     if (rotate) units_butterfly<kRB>(sum[nt]);
                 }
-                const bool whole = tile != partial_tile;
+                const bool whole = !kGuarded || tile != partial_tile;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     u32x4 w;
@@ -773,13 +775,43 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
                     // empty asm hides the lane number from the optimiser, which would otherwise hoist the constants
                     // out of the loop again.
                     const CompressLane<kRB, kSub> cl(lane);
-                    cl.template tile_from_lds<kInterleaved, kFormat, kGeneric>(lds_c, tile, n_blocks - tile * kBlocksPerTile, tau, eps, mode,
+                    // (every tile of the unguarded copy is whole: a constant lets its bounds checks fold away)
+                    cl.template tile_from_lds<kInterleaved, kFormat, kGeneric>(lds_c, tile, kGuarded ? n_blocks - tile * kBlocksPerTile : INT64_MAX, tau, eps, mode,
                                                                      static_cast<u32x2*>(tab.payload_output(idx)),
                                                                      static_cast<f32x2*>(tab.scales_output(idx)));
                 }
                 i = 0;
                 ++tile;
             }
+    };
+
+    // kAligned: k is a multiple of the ring size (k = 4, 8, 12, 16 with a ring of 4).  Every round of kRing items then
+    // lies inside one tile, a tile ends only with the last slot of a round, and every round but the last refills all
+    // its slots: no condition stands between a load and its use, so the compiler can wait for exactly the slot it
+    // needs (vmcnt counts the loads issued since) instead of draining all loads in flight.
+    if (kAligned) {
+        static_assert(!kAligned || (!kGuarded && kRing > 1), "the aligned loop has no bounds checks");
+        const int rounds = n_items / kRing;
+        for (int r = 0; r + 1 < rounds; ++r) {
+#pragma unroll
+            for (int p = 0; p < kRing; ++p) {
+                if (p < kRing - 1) { item(p, true, false); ++i; }
+                else item(p, true, true);
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < kRing; ++p) {
+            if (p < kRing - 1) { item(p, false, false); ++i; }
+            else item(p, false, true);
+        }
+        return;
+    }
+    for (int q0 = 0; q0 < n_items; q0 += kRing) {
+#pragma unroll
+        for (int p = 0; p < kRing; ++p) {
+            const int q = q0 + p;
+            if (q >= n_items) break;
+            item(p, q + kRing < n_items, true);
         }
     }
 }
@@ -787,7 +819,7 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
 // kGray: the lean plain decode with one running sign tile; it is held to the register budget of three waves per
 // SIMD (168), which it needs a few registers less than it would otherwise take for.
 template <int kRB, int kSub, int kRing, bool kInterleaved, bool kRecompress, int kWaves, int kFormat, bool kGeneric, bool kGray = false>
-__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu((kGray && kSub == 1) ? 3 : 1)))
+__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu((kGray && kSub == 1) ? 3 : 2)))
 void decompress_sum_mfma_kernel(
     DecodeTable tab, int count, int k, int tiles_per_wave, float tau, float eps, int mode) {
     static_assert((kRB == 1 || kRB == 2 || kRB == 4) && (kSub == 1 || kSub == 2 || kSub == 4) && (kRB == 1 || kSub == 1),
@@ -809,8 +841,15 @@ void decompress_sum_mfma_kernel(
     if (tile_end <= tile_begin) return;      // a wave past the end (last workgroup of a tensor only)
     // The guarded copy runs in one wave per tensor; it keeps two items in flight instead of kRing so that its extra
     // bookkeeping does not raise the register count of the kernel (which every wave pays for in occupancy).
+    // The loop with exact waits (decode_wave, kAligned) is compiled where it pays and fits the register budget of two
+    // waves per SIMD: the fused form of the method in the split layout (measured on MI355X, k = 8: 5-10 % faster at every
+    // block size).  With interleaved records it spills a dozen registers and gains nothing; the plain sum is faster back to
+    // back (2-3 %) but slower inside the benchmark step, where it follows other kernels, so it keeps the generic loop.
+    constexpr bool kHasAligned = kRecompress && !kGeneric && !kInterleaved && kRing > 1;
     if (tile_end == n_tiles && (n % kTileElems) != 0)
         decode_wave<kRB, kSub, 2, kInterleaved, kRecompress, kFormat, kGeneric, kGray, true>(tab, idx, k, n, tile_begin, tile_end, lds_all[wave], tau, eps, mode);
+    else if (kHasAligned && k % kRing == 0)
+        decode_wave<kRB, kSub, kRing, kInterleaved, kRecompress, kFormat, kGeneric, kGray, false, kHasAligned>(tab, idx, k, n, tile_begin, tile_end, lds_all[wave], tau, eps, mode);
     else
         decode_wave<kRB, kSub, kRing, kInterleaved, kRecompress, kFormat, kGeneric, kGray, false>(tab, idx, k, n, tile_begin, tile_end, lds_all[wave], tau, eps, mode);
 }
