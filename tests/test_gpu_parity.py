@@ -423,7 +423,11 @@ def _payloads_for_fused(oracle, k, n, block, seed):
 
 @pytest.mark.parametrize("block,k,n", [(128, 1, 2048 * 6), (128, 8, 2048 * 9), (128, 3, 2048 * 3 + 128 * 5 + 17), (128, 2, 700),
                                        (256, 8, 2048 * 8), (256, 2, 2048 * 2 + 300), (512, 4, 2048 * 5), (64, 8, 2048 * 4 + 70),
-                                       (32, 2, 2048 * 7), (128, 16, 2048 * 4)])
+                                       (32, 2, 2048 * 7), (128, 16, 2048 * 4),
+                                       # k a multiple of the ring size (the loop without conditional refills) next to a
+                                       # partial last tile (the guarded copy) in one launch
+                                       (128, 12, 2048 * 5 + 1000), (128, 4, 2048 * 7 + 130), (256, 8, 2048 * 3 + 300),
+                                       (512, 16, 2048 * 2 + 513), (32, 8, 2048 * 3 + 40)])
 @pytest.mark.parametrize("impl", ["auto", "butterfly"])
 def test_fused_sum_compress(oracle, block, k, n, impl):
     ps, ss = _payloads_for_fused(oracle, k, n, block, seed=block + k + n)
@@ -446,7 +450,9 @@ def test_fused_sum_compress(oracle, block, k, n, impl):
     gm = np.concatenate([bits_of(mid), np.zeros(pad, dtype=np.uint16)]).reshape(-1, block)
     rm = np.concatenate([ref_mid, np.zeros(pad, dtype=np.uint16)]).reshape(-1, block)
     same = np.all(gm == rm, axis=1)
-    assert same.mean() >= 0.5
+    # a block stays identical with probability (1 - p)^B, p the flip rate of a sum of k (parity_util): the share falls
+    # with B k; the floor only guards against a comparison that compares nothing
+    assert same.mean() >= (0.5 if block * k <= 2048 else 0.05)
     gp = fp.cpu().numpy().reshape(-1, block)
     gs = fs.cpu().numpy().reshape(-1, 2)
     P.check_scales(gs[same], rs[same], f"fused B={block} k={k}")
