@@ -494,8 +494,11 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
     constexpr int kBlock = 128 * kRB / kSub;
     constexpr int kBlocksPerTile = 2048 / kBlock;
     using Layout = PayloadLayout<kBlock, kInterleaved>;
-    constexpr int kLoads = kInterleaved ? 3 : 2;                 // 16-byte loads per lane and item
-    constexpr int kExtraChunks = Layout::kTileChunks - 128;      // interleaved: chunks left for the third load
+    constexpr int kLoads = 2;                                    // 16-byte loads per lane and item
+    // Interleaved: a tile is 2048 + 8 * blocks bytes; what lies past the first 2048 (at most 512 bytes) is a third,
+    // 8-byte load of the first kExtraWords lanes.
+    constexpr int kExtraWords = kInterleaved ? 2 * (Layout::kTileChunks - 128) : 0;
+    static_assert(kExtraWords <= 64, "the third load covers at most one 8-byte word per lane");
     uint32_t* lds_c = reinterpret_cast<uint32_t*>(lds);
     const int lane = threadIdx.x & 63;
     const int g = lane >> 4;
@@ -515,7 +518,8 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
 
     // Ring fill.  (pf_tile, pf_i) walks the item list ahead of the consumer.
     u32x4 stage[kRing][kLoads];
-    f32x2 stage_sc[kRing];
+    u32x2 stage_x[kRing];       // interleaved: the third load
+    f32x2 stage_sc[kRing];      // split: this lane's block scalars
     int64_t pf_tile = tile_begin;
     int pf_i = 0;
     auto fetch = [&](int p) {
@@ -524,7 +528,7 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
             stage[p][0] = load16<true>(&src[lane]);
             stage[p][1] = load16<true>(&src[64 + lane]);
             if (kInterleaved) {
-                if (lane < kExtraChunks) stage[p][kLoads - 1] = load16<true>(&src[128 + lane]);
+                if (lane < kExtraWords) stage_x[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(src + 128) + lane);
             } else {
                 stage_sc[p] = static_cast<const f32x2*>(tab.scales(idx, k, pf_i))[pf_tile * kBlocksPerTile + my_block];
             }
@@ -542,7 +546,10 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
                 }
                 stage[p][c] = v;
             }
-            if (!kInterleaved) {
+            if (kInterleaved) {
+                stage_x[p] = u32x2{0u, 0u};
+                if (256 + lane < words) stage_x[p] = *(reinterpret_cast<const u32x2*>(src + 128) + lane);
+            } else {
                 stage_sc[p] = f32x2{1.0f, 0.0f};
                 if (my_block < partial_blocks)
                     stage_sc[p] = static_cast<const f32x2*>(tab.scales(idx, k, pf_i))[pf_tile * kBlocksPerTile + my_block];
@@ -642,7 +649,7 @@ __device__ __forceinline__ void decode_wave(const DecodeTable& tab, int idx, int
             __builtin_amdgcn_sched_barrier(0);
             lds[wr_slot[0]] = stage[p][0];
             lds[wr_slot[1]] = stage[p][1];
-            if (kInterleaved && lane < kExtraChunks) lds[128 + lane] = stage[p][kLoads - 1];
+            if (kInterleaved && lane < kExtraWords) reinterpret_cast<u32x2*>(lds + 128)[lane] = stage_x[p];
             f32x2 sc = stage_sc[p];
             wave_lds_sync();
             u32x4 a0, a1;
@@ -842,10 +849,11 @@ void decompress_sum_mfma_kernel(
     // The guarded copy runs in one wave per tensor; it keeps two items in flight instead of kRing so that its extra
     // bookkeeping does not raise the register count of the kernel (which every wave pays for in occupancy).
     // The loop with exact waits (decode_wave, kAligned) is compiled where it pays and fits the register budget of two
-    // waves per SIMD: the fused form of the method in the split layout (measured on MI355X, k = 8: 5-10 % faster at every
-    // block size).  With interleaved records it spills a dozen registers and gains nothing; the plain sum is faster back to
-    // back (2-3 %) but slower inside the benchmark step, where it follows other kernels, so it keeps the generic loop.
-    constexpr bool kHasAligned = kRecompress && !kGeneric && !kInterleaved && kRing > 1;
+    // waves per SIMD: the fused form of the method (measured on MI355X, k = 8: 5-10 % faster at every block size in the
+    // split layout, 1-8 % with interleaved records, where a few registers are spilled once per wave outside the loops).
+    // The plain sum is faster back to back (2-3 %) but slower inside the benchmark step, where it follows other
+    // kernels, so it keeps the generic loop.
+    constexpr bool kHasAligned = kRecompress && !kGeneric && kRing > 1;
     if (tile_end == n_tiles && (n % kTileElems) != 0)
         decode_wave<kRB, kSub, 2, kInterleaved, kRecompress, kFormat, kGeneric, kGray, true>(tab, idx, k, n, tile_begin, tile_end, lds_all[wave], tau, eps, mode);
     else if (kHasAligned && k % kRing == 0)
