@@ -87,6 +87,10 @@ def parse():
     ap.add_argument("--cold-trace", type=int, default=0,
                     help="print the per-step call times of this many steps from a cold start and exit")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--payloads", type=int, default=0,
+                    help="number of payloads k of the step (1..16) instead of the workload's own (beyond those the data repeats, in buffers of "
+                         "their own).  "
+                         "Implies --no-cpu-baseline and --no-workloads")
     ap.add_argument("--no-cache-fed", action="store_true",
                     help="skip the decode calls with one payload given k times (counter runs: their dispatches carry the same "
                          "kernel name and grid as the real ones)")
@@ -185,14 +189,14 @@ class Bench:
         self.taco, self.torch = taco, torch
         self.w = w = W.WORKLOADS[name]
         self.params, self.B = params, params.block
-        self.k, self.n = w.payloads, w.numel
+        self.k, self.n = (args.payloads or w.payloads), w.numel
         k, n, B = self.k, self.n, self.B
         dev = torch.device("cuda:0")
         self.interleaved = params.layout == taco.TACO_LAYOUT_INTERLEAVED
         host = np.empty((w.tokens, w.hidden), dtype=np.uint16)
         xs = []
         for i in range(k):
-            W.generate(w, i, threads=args.gen_threads, out=host)
+            W.generate(w, i % w.payloads, threads=args.gen_threads, out=host)    # --payloads beyond the workload's own repeat them
             xs.append(torch.from_numpy(host.view(np.int16)).to(dev).view(torch.bfloat16))
         del host
         if self.interleaved:
@@ -512,6 +516,10 @@ def main():
     variant = args.mode != taco.TACO_MODE_FULL or fmt != taco.TACO_FORMAT_E4M3
     on_mfma = args.impl != "butterfly" and args.mode in (6, 7)
 
+    if args.payloads:
+        if not 1 <= args.payloads <= taco.TACO_MAX_K:
+            sys.exit(f"--payloads must be between 1 and {taco.TACO_MAX_K}")
+        args.no_cpu_baseline = args.no_workloads = True
     if args.cold_trace > 0:
         cold_trace(args, taco, torch, W, params)
         return

@@ -141,23 +141,28 @@ int check_compress_item(const void* x, int64_t rows, int64_t cols, void* payload
 
 // ---- decode -------------------------------------------------------------------------------------
 
-// Launch shape of the matrix-core decode, measured on MI355X (1..16 tiles per wave, rings of 2..8 items, 1..8
-// waves per workgroup tried, all block sizes and both layouts): a ring of four (tile, payload) items in
-// flight; up to five payloads, and for the recompress form, two output tiles per wave and one wave per
-// workgroup; from six payloads on, one tile per wave and two waves per workgroup (3-10 % faster at
-// k = 8..16, 5-10 % slower at k <= 4).  The recompress form at B = 32 (its heaviest epilogue) is 6-9 %
-// faster with one tile per wave.
 struct DecodeShape {
     bool wide;              // two waves per workgroup
     int tiles_per_wave;
     int64_t tiles_per_group;
 };
 
+// Launch shape of the matrix-core decode kernels, from measurements on MI355X (bf16 [16384, 12288], every k):
+//   plain decode   k = 1: one tile per single-wave workgroup; k = 2 .. 5: two tiles; k >= 6: two waves per workgroup,
+//                  one tile each (3-10 % faster than two tiles per wave at k = 8 .. 16, 5-10 % slower at k <= 4);
+//   fused form     few payloads leave a wave little work per tile to hide the compress stage behind, so it takes
+//                  more tiles: 8 for k <= 3, 3 for k = 4 and 5, 2 from k = 6 on (block 32: 1 from k = 6 on).
+//                  More tiles per wave always lower the time of a cache-fed run and, beyond these values, raise the
+//                  HBM-fed one: the tiles in flight stop forming one dense window that advances through DRAM.
 DecodeShape decode_shape(const taco_params* p, int k, bool recompress) {
     if (!use_mfma(p)) return DecodeShape{false, 1, 1};      // butterfly family: one tile per single-wave workgroup
-    const bool wide = !recompress && k >= 6;
-    const bool single = recompress && p->block == 32;
-    return DecodeShape{wide, (wide || single) ? 1 : 2, single ? 1 : 2};
+    if (recompress) {
+        const int tiles = k <= 3 ? 8 : k <= 5 ? 3 : p->block == 32 ? 1 : 2;
+        return DecodeShape{false, tiles, tiles};
+    }
+    if (k >= 6) return DecodeShape{true, 1, 2};
+    const int tiles = k == 1 ? 1 : 2;
+    return DecodeShape{false, tiles, tiles};
 }
 
 int64_t decode_groups(int64_t n, const DecodeShape& shape) {

@@ -14,14 +14,14 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def cases(count, seed):
+def cases(count, seed, ks=(1, 1, 2, 3, 5, 8, 16), max_tiles=7):
     rng = np.random.default_rng(seed)
     out = []
     for _ in range(count):
         block = int(rng.choice([32, 64, 128, 256, 512]))
-        tiles = int(rng.integers(0, 7))
+        tiles = int(rng.integers(0, max_tiles))
         n = tiles * 2048 + int(rng.integers(0, 2048)) + (1 if tiles == 0 else 0)
-        k = int(rng.choice([1, 1, 2, 3, 5, 8, 16]))
+        k = int(rng.choice(ks))
         layout = int(rng.integers(0, 2))
         impl = int(rng.choice([taco.TACO_IMPL_AUTO, taco.TACO_IMPL_BUTTERFLY]))
         kind = int(rng.integers(0, 4))
@@ -45,7 +45,9 @@ def make_input(n, kind, rng):
     return W.float32_to_bf16_bits(x.astype(np.float32))
 
 
-@pytest.mark.parametrize("block,n,k,layout,impl,kind,seed", cases(60, 20260))
+# second set: payload counts that are multiples of the decode ring (the fused call's loop without conditional refills)
+# and more tiles, so that a wave runs several rounds and the launch mixes that loop with the guarded last tile
+@pytest.mark.parametrize("block,n,k,layout,impl,kind,seed", cases(60, 20260) + cases(40, 20261, ks=(4, 8, 12, 16), max_tiles=13))
 def test_random_case(oracle, block, n, k, layout, impl, kind, seed):
     rng = np.random.default_rng(seed)
     what = f"B={block} n={n} k={k} layout={layout} impl={impl} kind={kind}"
