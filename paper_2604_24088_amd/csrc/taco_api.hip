@@ -148,7 +148,8 @@ struct DecodeShape {
 };
 
 // Launch shape of the matrix-core decode kernels, from measurements on MI355X (bf16 [16384, 12288], every k):
-//   plain decode   k = 1: one tile per single-wave workgroup; k = 2 .. 5: two tiles; k >= 6: two waves per workgroup,
+//   plain decode   k = 1: one tile per single-wave workgroup up to block 128 (1 % faster), two tiles above (1-3 %
+//                  faster); k = 2 .. 5: two tiles; k >= 6: two waves per workgroup,
 //                  one tile each (3-10 % faster than two tiles per wave at k = 8 .. 16, 5-10 % slower at k <= 4);
 //   fused form     few payloads leave a wave little work per tile to hide the compress stage behind, so it takes
 //                  more tiles: 8 for k <= 3, 3 for k = 4 and 5, 2 from k = 6 on (block 32: 1 from k = 6 on).
@@ -161,7 +162,7 @@ DecodeShape decode_shape(const taco_params* p, int k, bool recompress) {
         return DecodeShape{false, tiles, tiles};
     }
     if (k >= 6) return DecodeShape{true, 1, 2};
-    const int tiles = k == 1 ? 1 : 2;
+    const int tiles = (k == 1 && p->block <= 128) ? 1 : 2;
     return DecodeShape{false, tiles, tiles};
 }
 
