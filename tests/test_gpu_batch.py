@@ -97,7 +97,7 @@ def test_decompress_sum_batch_equals_single_calls(oracle, block, layout, impl, k
     t = len(sizes) - 1
     ref, acc = oracle.decompress_sum([e[0] for e in encs[t]], [e[1] for e in encs[t]], sizes[t], block=block, mode=mode, fmt=fmt,
                                      want_sum=True)
-    P.check_recon(outs[t].view(torch.int16).cpu().numpy().view(np.uint16), ref, block, "batch decode", min_exact=0.9, acc=acc)
+    P.check_recon(outs[t].view(torch.int16).cpu().numpy().view(np.uint16), ref, block, "batch decode", min_exact=P.RECON_EXACT_MIN_SMALL, acc=acc)
 
 
 def test_chunks_of_one_tensor_as_a_batch():

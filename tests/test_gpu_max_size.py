@@ -89,12 +89,13 @@ def test_more_than_2_to_32_elements(oracle, block, layout):
     torch.cuda.synchronize()
     assert torch.equal(fp, up) and (il or torch.equal(fs, us))
     for j, (a, b) in enumerate(ranges):
-        want = oracle.decompress_sum([ref[0][j][0], ref[1][j][0]], [ref[0][j][1], ref[1][j][1]], b - a, block=block)
+        want, acc = oracle.decompress_sum([ref[0][j][0], ref[1][j][0]], [ref[0][j][1], ref[1][j][1]], b - a, block=block,
+                                          want_sum=True)
         small = b - a < 1000                       # the ragged tail: too few elements for a percentage
         P.check_recon(bits(out.view(-1)[a:b]), want, block, f"B{block} layout {layout} sum, elements [{a}, {b})",
-                      min_exact=0.9 if small else 0.98)
-        want1 = oracle.decompress_sum([ref[1][j][0]], [ref[1][j][1]], b - a, block=block)
+                      min_exact=P.RECON_EXACT_MIN_SMALL if small else P.RECON_EXACT_MIN_MIXED_SUM, acc=acc)
+        want1, acc1 = oracle.decompress_sum([ref[1][j][0]], [ref[1][j][1]], b - a, block=block, want_sum=True)
         P.check_recon(bits(one.view(-1)[a:b]), want1, block, f"B{block} layout {layout} decompress, elements [{a}, {b})",
-                      min_exact=0.9 if small else 0.99)
+                      min_exact=P.RECON_EXACT_MIN_SMALL if small else P.RECON_EXACT_MIN_MIXED, acc=acc1)
     assert torch.isfinite(out.view(-1)[-4096:].float()).all()
     print(f"[B{block} layout {layout}] decode parity ok", flush=True)
