@@ -2,7 +2,7 @@
 //
 // The Hadamard rotation of Algorithm 1 runs as a dense product on MFMA.  A TILE is 2048
 // consecutive elements, seen as 16 UNITS (rows) of 128 elements:  V[16, 128] = X[16, 128] H_128.
-// Both operands are exact in the input format (bf16 data or E4M3 codes, +-1 entries), products
+// Both operands are exact in the input format (bf16 data or FP8 / INT8 codes, +-1 entries), products
 // are exact and accumulation is fp32.  A block of B = 128 kRB elements is kRB consecutive units;
 // because H_B = H_kRB (x) H_128, its rotation is the 128-point product of each unit followed by
 // log2(kRB) butterfly stages ACROSS the units of the block, which live in registers of one lane.
@@ -16,7 +16,8 @@
 // zeros past the end (the zero padding of the last block, which sigma still divides by B) and
 // stores only the blocks and elements that exist, so every call is ONE kernel whatever n is.
 //
-// A 64-lane wavefront handles one or two consecutive tiles and exits: no persistent loop.  The
+// A 64-lane wavefront handles a few consecutive tiles (one to eight: the host picks the number from the call and the
+// payload count) and exits: no persistent loop.  The
 // dispatcher hands out workgroups in index order, so the tiles in flight form one dense,
 // advancing window of memory, which measured ~15 % faster on HBM than a grid-stride loop over the
 // same tiles.  Every wave works in an LDS region of its own (one or two waves per workgroup), so
