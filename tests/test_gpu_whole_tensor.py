@@ -1,7 +1,7 @@
 """GPU parity over WHOLE benchmark tensors: every element of every configuration, not a sample.
 
-For each of the five benchmark configurations (block 128, and the Qwen-style tensor again at the
-paper's optimum block 256) the GPU compresses the full tensor in the launch configuration bench.py
+For each of the five benchmark configurations (block 128; the Qwen-style tensor again at the
+paper's optimum block 256; one tensor at each of the other block sizes) the GPU compresses the full tensor in the launch configuration bench.py
 times (default parameters, kernel choice AUTO, one call per tensor) and the oracle compresses the same
 bits; every code and every {alpha, s} record is compared.  The decode side is then fed the ORACLE's
 payloads (so both sides decode identical bits): taco_decompress for one payload, taco_decompress_sum
@@ -38,7 +38,9 @@ def slabs(n: int):
 
 
 @pytest.mark.parametrize("name,B", [("tiny", 128), ("gpt_rowpar", 128), ("qwen_act", 128), ("bwd_grad", 128),
-                                    ("qwen_act", 256), ("large_k8", 128)])
+                                    ("qwen_act", 256), ("large_k8", 128),
+                                    # the other block sizes on one whole tensor each
+                                    ("gpt_rowpar", 32), ("gpt_rowpar", 64), ("gpt_rowpar", 512), ("bwd_grad", 256)])
 def test_whole_tensor_parity(oracle, name, B):
     w = W.WORKLOADS[name]
     n, k = w.numel, w.payloads
