@@ -99,13 +99,14 @@ def bench_rows(paths, workloads: bool):
         return f"{e['ms'] * 1e3:7.1f} {e['hbm_frac']:.3f}" if e else "      -     -"
 
     print("== bench.py runs: per call  us  share-of-HBM-peak;  step = ms per step and share for the whole step")
-    print(f"  {'run':44s} {'step':>13s} | in step: {'compress':>13s} {'decompress':>13s} {'sum(k)':>13s} {'sum->compress':>13s} | "
+    print(f"  {'run':48s} {'step':>13s} | in step: {'compress':>13s} {'decompress':>13s} {'sum(k)':>13s} {'sum->compress':>13s} | "
           f"back to back: {'compress':>13s} {'decompress':>13s} {'sum(k)':>13s} | yardstick: {'compress':>13s} {'decompress':>13s} {'sum(k)':>13s} "
           f"{'sum->compress':>13s}")
     for path in paths:
         r = load_bench(path)
         c = r["config"]
-        tag = (f"{c['workload'].split(':')[0]} B={c['block']} {c['layout']} {c['impl']} fmt={c['format']} mode={c['mode']}"
+        k = next((key.rsplit("_k", 1)[1] for key in r["calls"] if key.startswith("decompress_sum_k")), "?")
+        tag = (f"{c['workload'].split(':')[0]} k={k} B={c['block']} {c['layout']} {c['impl']} fmt={c['format']} mode={c['mode']}"
                + (f" chunks={c['chunks_per_call']}x{c['streams']}" if c.get("chunks_per_call", 1) > 1 else "")
                + (" batch" if c.get("batched_calls") else "") + (" graph" if c.get("hip_graph") else ""))
         calls = list(r["calls"].values())
@@ -114,7 +115,7 @@ def bench_rows(paths, workloads: bool):
         mixv = [mix.get("compress"), mix.get("decompress"),
                 next((v for k, v in mix.items() if k.startswith("decompress_sum_k")), None),
                 next((v for k, v in mix.items() if k.startswith("decompress_sum_compress")), None)]
-        print(f"  {tag:44s} {r['ms_per_step']:7.4f} {r['hbm_frac_step']:.3f} |          {cell(calls[0])} {cell(calls[1])} {cell(calls[2])} "
+        print(f"  {tag:48s} {r['ms_per_step']:7.4f} {r['hbm_frac_step']:.3f} |          {cell(calls[0])} {cell(calls[1])} {cell(calls[2])} "
               f"{cell(calls[3]) if len(calls) > 3 else cell(None)} |               {cell(b2b[0])} {cell(b2b[1])} {cell(b2b[2])} |            "
               f"{cell(mixv[0])} {cell(mixv[1])} {cell(mixv[2])} {cell(mixv[3])}")
         if workloads and "workloads" in r:

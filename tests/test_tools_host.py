@@ -92,4 +92,4 @@ def test_profile_summary_tables(tmp_path):
     path.write_text("some log line\n" + json.dumps(bench) + "\n")
     r = run(["-m", "paper_2604_24088_amd.profile_summary", "--bench", str(path)])
     assert r.returncode == 0, r.stderr
-    assert "large_k8 B=128 split auto fmt=e4m3 mode=7" in r.stdout and "100.0 0.750" in r.stdout
+    assert "large_k8 k=8 B=128 split auto fmt=e4m3 mode=7" in r.stdout and "100.0 0.750" in r.stdout
