@@ -35,9 +35,14 @@
  *     metadata placement, Section 4.4.2, in structure-of-arrays form).
  *   - A block whose rotated maximum is zero stores s_k = 0 and zero codes (sign bits
  *     of the codes are unspecified) and decodes to zeros.
- *   - Non-finite inputs are outside the contract, and so are blocks whose sum of squares
- *     leaves the range of normal fp32 numbers (|x| up to about 2^60 and down to 2^-60 are
- *     tested): the kernels work in fp32.
+ *   - Range (the kernels work in fp32).  Non-finite inputs are outside the contract, and so are
+ *     blocks whose sum of squares overflows fp32 (elements beyond about 2^58 in magnitude).
+ *     At the small end compression holds its accuracy down to blocks of bf16 subnormals
+ *     (a block whose rotated maximum is below 2^-100 is scaled up by a power of two before
+ *     Q_max / max|Z| is formed); decompression holds it down to elements of about 2^-112:
+ *     below, the block factor s / (alpha sqrt(B)) is itself a subnormal fp32 number and the
+ *     outputs are only within 2^-6 of the block's largest value
+ *     (plus one bf16 subnormal step, 2^-133).
  *   - Return value: TACO_OK (0) or a negative taco_status.  Argument errors are found on
  *     the host before anything is launched.  TACO_ERR_LAUNCH is the result of this call's own
  *     launch; an error left on the thread by earlier, unrelated work is neither reported nor

@@ -207,6 +207,12 @@ __device__ __forceinline__ void compress_group_butterfly(float (&v)[8], int lane
         s = wmax > 0.0f ? (wmax * alpha * norm) * (1.0f / qmax) : 0.0f;
         to_code = wmax > 0.0f ? qmax * __builtin_amdgcn_rcpf(wmax) : 0.0f;
     }
+    // Q_max / max|W| leaves fp32 when max|W| < 2^-118 (blocks of bf16 subnormals): take a power of two out first.
+    if (var.postscale() && wmax > 0.0f && wmax < 0x1p-100f) {
+        to_code = qmax * __builtin_amdgcn_rcpf(__builtin_ldexpf(wmax, 64));
+#pragma unroll
+        for (int r = 0; r < 8; ++r) v[r] = __builtin_ldexpf(v[r], 64);
+    }
     if (slot.blk >= n_blocks_total) return;
     float q[8];
 #pragma unroll

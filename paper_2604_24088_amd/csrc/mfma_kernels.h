@@ -360,6 +360,27 @@ struct CompressLane {
             to_code = alpha * norm;
             s = 1.0f;
         }
+        // Q_max / max|W| leaves fp32 when max|W| < 2^-118 (blocks of bf16 subnormals get there): such a block takes a
+        // power of two out of its rotated values first.  One wave-uniform test per tile, next to never true.
+        if (postscale) {
+            const bool tiny = wmax > 0.0f && wmax < 0x1p-100f;
+            if (__builtin_amdgcn_ballot_w64(tiny) != 0) {
+                const int lift = tiny ? 64 : 0;
+                to_code = wmax > 0.0f ? kQ * __builtin_amdgcn_rcpf(__builtin_ldexpf(wmax, lift)) : 0.0f;
+                const float lift_bits = __builtin_bit_cast(float, lift);
+                const int l0 = __builtin_bit_cast(int, dpp_f32<kDppQuadBcast(0)>(lift_bits));
+                const int l1 = __builtin_bit_cast(int, dpp_f32<kDppQuadBcast(kRB == 1 ? 1 : 0)>(lift_bits));
+                const int l2 = __builtin_bit_cast(int, dpp_f32<kDppQuadBcast(kRB == 1 ? 2 : kRB == 2 ? 1 : 0)>(lift_bits));
+                const int l3 = __builtin_bit_cast(int, dpp_f32<kDppQuadBcast(kRB == 1 ? 3 : kRB == 2 ? 1 : 0)>(lift_bits));
+#pragma unroll
+                for (int nt = 0; nt < 8; ++nt) {
+                    acc[nt][0] = __builtin_ldexpf(acc[nt][0], l0);
+                    acc[nt][1] = __builtin_ldexpf(acc[nt][1], l1);
+                    acc[nt][2] = __builtin_ldexpf(acc[nt][2], l2);
+                    acc[nt][3] = __builtin_ldexpf(acc[nt][3], l3);
+                }
+            }
+        }
         if (owns_scales && my_block < blocks_left) {
             if (kInterleaved)
                 records[Layout::scale_word(0, my_block)] = __builtin_bit_cast(u32x2, f32x2{alpha, s});

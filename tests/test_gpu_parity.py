@@ -579,6 +579,48 @@ def test_eps_zero_with_all_zero_blocks(oracle, impl, block):
 
 
 @pytest.mark.parametrize("impl", ["auto", "butterfly"])
+@pytest.mark.parametrize("block", [32, 128, 512])
+@pytest.mark.parametrize("exp", [-112, -120, -126, -130])
+def test_tiny_blocks(oracle, impl, block, exp):
+    """Blocks at the bottom of bf16's range, down to subnormal inputs: Q_max / max|W| no longer fits fp32 there
+    (below max|W| = 2^-118), so the kernels take a power of two out of the rotated values first.  Codes and scalars
+    are held to the same bar as everywhere else; eps dominates sigma, and the stored s stays a normal fp32 number at
+    these sizes."""
+    rng = np.random.default_rng(1000 + block - exp)
+    n = 2048 * 3 + 5 * block + 3
+    xs = W.float32_to_bf16_bits((rng.standard_normal(n) * 2.0 ** exp).astype(np.float32))
+    xs[:block] = 0                                                            # a zero block among them
+    p = taco.taco_default_params(block=block, impl=IMPLS[impl])
+    buf = torch.zeros(n + ((-n) % 8), dtype=torch.bfloat16, device=DEV)
+    buf[:n] = to_dev(xs)
+    pl, sc = taco.taco_compress(buf[:n], p)
+    torch.cuda.synchronize()
+    rp, rs, z = oracle.compress(xs, block=block, want_z=True)
+    P.check_scales(sc.cpu().numpy(), rs, f"2^{exp}")
+    # bf16 subnormals carry one to seven bits, so the rotated values are small integers times 2^-133 and their ratios
+    # to the block maximum sit on exact rounding ties far more often than data does (as for the un-rotated variants):
+    # the lower share applies there, and z makes check_codes assert that every differing code is on such a tie.
+    P.check_codes(pl.cpu().numpy(), rp, rs, block, f"2^{exp}", z=z,
+                  min_match=P.CODE_MATCH_MIN if exp > -126 else P.CODE_MATCH_MIN_UNROTATED)
+    out = taco.taco_decompress(torch.from_numpy(rp).to(DEV), torch.from_numpy(rs).to(DEV), (n,), p)
+    torch.cuda.synchronize()
+    ref, acc = oracle.decompress(rp, rs, n, block=block, want_sum=True)
+    got = bits_of(out)
+    if exp >= -112:
+        P.check_recon(got, ref, block, f"2^{exp} decompress", min_exact=P.RECON_EXACT_MIN_MIXED, acc=acc)
+    else:
+        # Stated limit of the decode side (include/taco.h): where the block factor s / (alpha sqrt(B)) is itself a
+        # subnormal fp32 number (alpha = 10^6 here, so from about 2^-115 down) it carries fewer bits, and outputs that are
+        # bf16 subnormals have an ulp of 2^-133: the outputs are finite and within 2^-6 of the block's largest value.
+        g, r = P.bf16_to_f64(got), P.bf16_to_f64(ref)
+        assert np.all(np.isfinite(g))
+        pad = (-n) % block
+        block_max = np.repeat(np.abs(np.concatenate([r, np.zeros(pad)])).reshape(-1, block).max(axis=1), block)[:n]
+        assert np.all(np.abs(g - r) <= 2.0 ** -6 * block_max + 2.0 ** -133)
+        assert np.all(g[:block] == 0.0)
+
+
+@pytest.mark.parametrize("impl", ["auto", "butterfly"])
 @pytest.mark.parametrize("block", [64, 128, 256])
 @pytest.mark.parametrize("exp", [-60, -24, 30, 60])
 def test_extreme_magnitudes(oracle, impl, block, exp):
