@@ -28,21 +28,26 @@ constexpr int kGroupElems = 512;      // elements whose transform one wave holds
 constexpr int kGroupsPerTile = 4;     // groups per wave: one tile of 2048 elements
 
 // Butterfly between lanes L and L ^ kMask (element stride 8 kMask); nothing when the block is narrower.
+// The lower lane of a pair wants a + b and the upper one a - b (a the lower lane's value).  Written as
+// own + sgn * other with sgn = +1 in the lower and -1 in the upper lane, the upper lane gets b - a, the result
+// with its sign flipped, in ONE instruction per value (a multiply-add whose operand comes through the
+// cross-lane path) instead of a move, two additions and a select.  The flipped signs need no bookkeeping
+// between stages: partner lanes differ only in the bit of the current stage, so they have been flipped
+// equally often before it; after all stages lane L carries (-1)^popcount(L & (B/8 - 1)) times the
+// transform, which fwht_group returns for the caller to fold into the factor it multiplies by anyway.
+// Products with +-1 are exact, so every value is the one the plain butterfly would give.
 template <int B, int kMask>
 __device__ __forceinline__ void cross_lane_stage(float (&v)[8], int lane) {
     if (kMask < B / 8) {
-        const bool upper = (lane & kMask) != 0;
+        const float sgn = (lane & kMask) != 0 ? -1.0f : 1.0f;
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const float other = lane_xor<kMask>(v[r]);
-            v[r] = upper ? other - v[r] : v[r] + other;
-        }
+        for (int r = 0; r < 8; ++r) v[r] = __builtin_fmaf(sgn, lane_xor<kMask>(v[r]), v[r]);
     }
 }
 
-// y = H_B x for every block of the group; v[r] holds element 8 lane + r.
+// y = H_B x for every block of the group, up to the sign that is returned: v[r] * sign is element 8 lane + r of y.
 template <int B>
-__device__ __forceinline__ void fwht_group(float (&v)[8], int lane) {
+__device__ __forceinline__ float fwht_group(float (&v)[8], int lane) {
 #pragma unroll
     for (int h = 1; h < 8; h <<= 1) {
 #pragma unroll
@@ -60,6 +65,7 @@ __device__ __forceinline__ void fwht_group(float (&v)[8], int lane) {
     cross_lane_stage<B, 8>(v, lane);
     cross_lane_stage<B, 16>(v, lane);
     cross_lane_stage<B, 32>(v, lane);
+    return (__builtin_popcount(lane & (B / 8 - 1)) & 1) ? -1.0f : 1.0f;
 }
 
 // Sum / maximum over the B / 8 lanes of the caller's block, returned in every one of them.
@@ -188,9 +194,9 @@ __device__ __forceinline__ void compress_group_butterfly(float (&v)[8], int lane
         energy = block_allreduce_sum<B>(energy);                      // sum_j G_kj^2
         alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / B) + eps);   // Eq. ash_sigma, Eq. ash_alpha
     }
-    float norm = 1.0f;
+    float norm = 1.0f, sign = 1.0f;
     if (var.rotate()) {
-        fwht_group<B>(v, lane);                                       // W = H G_k (unnormalised)
+        sign = fwht_group<B>(v, lane);                                // W = sign * v = H G_k (unnormalised)
         norm = 1.0f / __builtin_sqrtf(static_cast<float>(B));
     }
     float wmax = 0.0f;
@@ -214,6 +220,7 @@ __device__ __forceinline__ void compress_group_butterfly(float (&v)[8], int lane
         for (int r = 0; r < 8; ++r) v[r] = __builtin_ldexpf(v[r], 64);
     }
     if (slot.blk >= n_blocks_total) return;
+    to_code *= sign;
     float q[8];
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
@@ -310,8 +317,8 @@ __device__ __forceinline__ void decode_sum_group_butterfly(const DecodeTable& ta
             }
         }
     }
-    if (var.rotate()) fwht_group<B>(v, lane);
-    const float post = (k == 1) ? single : 1.0f;
+    const float sign = var.rotate() ? fwht_group<B>(v, lane) : 1.0f;
+    const float post = (k == 1) ? single * sign : sign;
 #pragma unroll
     for (int r = 0; r < 8; ++r) v[r] *= post;
 }
