@@ -35,8 +35,12 @@
  *     metadata placement, Section 4.4.2, in structure-of-arrays form).
  *   - A block whose rotated maximum is zero stores s_k = 0 and zero codes (sign bits
  *     of the codes are unspecified) and decodes to zeros.
- *   - Range (the kernels work in fp32).  Non-finite inputs are outside the contract, and so are
- *     blocks whose sum of squares overflows fp32 (elements beyond about 2^58 in magnitude).
+ *   - Range (the kernels work in fp32).  Non-finite inputs are outside the contract.  Where a
+ *     block's sum of squares overflows fp32 (elements beyond about 2^58 in magnitude) the largest
+ *     finite number is taken for it: the stored alpha_k, s_k are then not tau / sigma_k and its
+ *     companion, but the codes and the ratio s_k / alpha_k, which is all decompression uses, are
+ *     unaffected (the ablation modes without the post-rotation scale excepted: their codes depend
+ *     on alpha_k).
  *     At the small end compression holds its accuracy down to blocks of bf16 subnormals
  *     (a block whose rotated maximum is below 2^-100 is scaled up by a power of two before
  *     Q_max / max|Z| is formed); decompression holds it down to elements of about 2^-112:

@@ -192,7 +192,9 @@ __device__ __forceinline__ void compress_group_butterfly(float (&v)[8], int lane
 #pragma unroll
         for (int r = 0; r < 8; ++r) energy = __builtin_fmaf(v[r], v[r], energy);
         energy = block_allreduce_sum<B>(energy);                      // sum_j G_kj^2
-        alpha = tau * __builtin_amdgcn_rsqf(energy * (1.0f / B) + eps);   // Eq. ash_sigma, Eq. ash_alpha
+        // Eq. ash_sigma, Eq. ash_alpha; an overflowing sum of squares is taken as the largest finite number (the codes do not
+        // depend on alpha and the reconstruction only on s / alpha, so both stay right where alpha itself no longer is)
+        alpha = tau * __builtin_amdgcn_rsqf(__builtin_fminf(energy * (1.0f / B), 0x1.fffffep+127f) + eps);
     }
     float norm = 1.0f, sign = 1.0f;
     if (var.rotate()) {

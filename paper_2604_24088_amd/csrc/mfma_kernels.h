@@ -347,7 +347,10 @@ struct CompressLane {
             if (kSub == 2) energy += __shfl_xor(energy, 16, 64);
             energy = __shfl(energy, energy_src, 64);
         }
-        const float alpha = rescale ? tau * __builtin_amdgcn_rsqf(energy * (1.0f / kBlock) + eps) : 1.0f;   // Eq. ash_sigma, ash_alpha
+        // Eq. ash_sigma, ash_alpha.  A sum of squares that overflows fp32 (elements beyond about 2^58) is taken as the largest
+        // finite number: alpha then differs from tau / sigma, but the codes do not depend on alpha and the reconstruction
+        // only on s / alpha = max|W| / (Q_max sqrt(B)), so both stay right; without the clamp alpha would be 0 and decode NaN.
+        const float alpha = rescale ? tau * __builtin_amdgcn_rsqf(__builtin_fminf(energy * (1.0f / kBlock), 0x1.fffffep+127f) + eps) : 1.0f;
         const float norm = rotate ? inv_sqrt_block<kBlock>() : 1.0f;
         // With the post-rotation scale: Z / s = W * Q_max / max|W| in exact arithmetic (Eq. post_scale,
         // Eq. quantization), s = max|Z| / Q_max; an all-zero block stores s = 0 whatever alpha is (with

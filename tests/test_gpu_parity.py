@@ -580,6 +580,40 @@ def test_eps_zero_with_all_zero_blocks(oracle, impl, block):
 
 @pytest.mark.parametrize("impl", ["auto", "butterfly"])
 @pytest.mark.parametrize("block", [32, 128, 512])
+@pytest.mark.parametrize("exp", [64, 90, 110])
+def test_huge_blocks(oracle, impl, block, exp):
+    """Elements so large that the block's sum of squares overflows fp32: the kernels take the largest finite number for it,
+    so the stored alpha (and with it s) is no longer the oracle's, but the codes, which do not depend on alpha, and
+    s / alpha = max|W| / (Q_max sqrt(B)), which is all the reconstruction depends on, still are."""
+    rng = np.random.default_rng(2000 + block + exp)
+    n = 2048 * 2 + 3 * block + 5
+    xs = W.float32_to_bf16_bits((rng.standard_normal(n) * 2.0 ** exp).astype(np.float32))
+    p = taco.taco_default_params(block=block, impl=IMPLS[impl])
+    buf = torch.zeros(n + ((-n) % 8), dtype=torch.bfloat16, device=DEV)
+    buf[:n] = to_dev(xs)
+    pl, sc = taco.taco_compress(buf[:n], p)
+    out = taco.taco_decompress(pl, sc, (n,), p)
+    torch.cuda.synchronize()
+    rp, rs, z = oracle.compress(xs, block=block, want_z=True)
+    gs = sc.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(gs)) and np.all(gs > 0.0)
+    P.check_codes(pl.cpu().numpy(), rp, rs, block, f"2^{exp}", z=z)
+    ratio_g, ratio_r = gs[:, 1] / gs[:, 0], rs[:, 1].astype(np.float64) / rs[:, 0].astype(np.float64)
+    assert np.max(np.abs(ratio_g - ratio_r) / ratio_r) <= 4.0 * P.SCALE_RTOL
+    # decode of the GPU's own payload against the oracle's decode of the oracle's: the same values in every block whose
+    # codes all agree (the inverse rotation spreads one differing code over its whole block)
+    g = P.bf16_to_f64(bits_of(out))
+    r = P.bf16_to_f64(oracle.decompress(rp, rs, n, block=block))
+    assert np.all(np.isfinite(g))
+    same_block = np.all((pl.cpu().numpy() == rp).reshape(-1, block), axis=1)          # every code of the block agrees
+    same = np.repeat(same_block, block)[:n]
+    tol = np.maximum(P.bf16_ulp(r), P.RECON_RTOL * np.abs(r).max())
+    assert np.all(np.abs(g - r)[same] <= tol[same])
+    assert same_block.mean() >= 0.9
+
+
+@pytest.mark.parametrize("impl", ["auto", "butterfly"])
+@pytest.mark.parametrize("block", [32, 128, 512])
 @pytest.mark.parametrize("exp", [-112, -120, -126, -130])
 def test_tiny_blocks(oracle, impl, block, exp):
     """Blocks at the bottom of bf16's range, down to subnormal inputs: Q_max / max|W| no longer fits fp32 there
