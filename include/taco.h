@@ -204,6 +204,19 @@ int taco_compress_batch(const taco_compress_item* items, int32_t count, const ta
 int taco_decompress_sum_batch(const taco_decode_item* items, int32_t count, int32_t k, const taco_params* p,
                               void* stream);
 
+/* The fused decompress_sum -> compress of taco_decompress_sum_compress for several tensors (the chunks of one
+ * exchange, or the shards one rank reduces for its peers) in ONE kernel; same k for all items. */
+typedef struct taco_recompress_item {
+    const void* const* payloads; /* in   HOST array of k device pointers                    */
+    const void* const* scales;   /* in   HOST array of k device pointers (or NULL when interleaved) */
+    int64_t rows, cols;
+    void* payload_out;           /* out  device, taco_payload_bytes(n) (+ taco_scales_bytes(n) when interleaved) */
+    void* scales_out;            /* out  device, taco_scales_bytes(n); ignored when interleaved */
+} taco_recompress_item;
+
+int taco_decompress_sum_compress_batch(const taco_recompress_item* items, int32_t count, int32_t k,
+                                       const taco_params* p, void* stream);
+
 /* Text for a taco_status value (static storage, never NULL). */
 const char* taco_strerror(int status);
 

@@ -238,6 +238,57 @@ int decode_single(const void* const* payloads, const void* const* scales, int32_
     return launch_decode(tab, 1, k, workgroups, p, recompress, static_cast<hipStream_t>(stream));
 }
 
+// One tensor of a batched decode: its k sources and either the bf16 output or the re-compressed outputs.
+struct BatchItem {
+    const void* const* payloads;
+    const void* const* scales;
+    int64_t rows, cols;
+    void* out_bf16;
+    void* payload_out;
+    void* scales_out;
+};
+
+template <typename Get>
+int decode_batch(int32_t count, int32_t k, const taco_params* p, bool recompress, void* stream, Get&& get) {
+    if (k < 1 || k > TACO_MAX_K) return TACO_ERR_K;
+    if (count < 1 || count > TACO_MAX_BATCH || static_cast<int64_t>(count) * k > TACO_MAX_BATCH_PAYLOADS) return TACO_ERR_BATCH;
+    if (int rc = check_params(p)) return rc;
+    if (recompress && !params_ok_for_compress(p)) return TACO_ERR_PARAM;
+    const bool il = p->layout == TACO_LAYOUT_INTERLEAVED;
+    const DecodeShape shape = decode_shape(p, k, recompress);
+    RangeSet ranges;
+    taco::DecodeTable tab{};
+    int64_t workgroups = 0;
+    for (int t = 0; t < count; ++t) {
+        const BatchItem item = get(t);
+        int64_t n = 0;
+        if (recompress ? (!item.payload_out || (!il && !item.scales_out)) : !item.out_bf16) return TACO_ERR_NULL;
+        if (int rc = check_shape(item.rows, item.cols, &n)) return rc;
+        if (int rc = check_sources(item.payloads, item.scales, k, n, p, &ranges, [&](int i, const void* pl, const void* sc) {
+                tab.src_payload[t * k + i] = pl;
+                tab.src_scales[t * k + i] = sc;
+            }))
+            return rc;
+        if (recompress) {
+            if (!aligned16(item.payload_out) || (!il && !aligned16(item.scales_out))) return TACO_ERR_ALIGN;
+            ranges.add_out(item.payload_out, payload_arg_bytes(n, p));
+            if (!il) ranges.add_out(item.scales_out, scales_arg_bytes(n, p));
+            tab.payload_out[t] = item.payload_out;
+            tab.scales_out[t] = il ? nullptr : item.scales_out;
+        } else {
+            if (!aligned16(item.out_bf16)) return TACO_ERR_ALIGN;
+            ranges.add_out(item.out_bf16, 2u * static_cast<uint64_t>(n));
+            tab.out[t] = item.out_bf16;
+        }
+        tab.n_elems[t] = n;
+        tab.first[t] = workgroups;
+        workgroups += decode_groups(n, shape);
+    }
+    tab.first[count] = workgroups;
+    if (ranges.clash()) return TACO_ERR_OVERLAP;
+    return launch_decode(tab, count, k, workgroups, p, recompress, static_cast<hipStream_t>(stream));
+}
+
 }  // namespace
 
 extern "C" {
@@ -324,32 +375,18 @@ int taco_decompress(const void* payload, const void* scales, int64_t rows, int64
 int taco_decompress_sum_batch(const taco_decode_item* items, int32_t count, int32_t k, const taco_params* p,
                               void* stream) {
     if (!items) return TACO_ERR_NULL;
-    if (k < 1 || k > TACO_MAX_K) return TACO_ERR_K;
-    if (count < 1 || count > TACO_MAX_BATCH || static_cast<int64_t>(count) * k > TACO_MAX_BATCH_PAYLOADS) return TACO_ERR_BATCH;
-    if (int rc = check_params(p)) return rc;
-    const DecodeShape shape = decode_shape(p, k, false);
-    RangeSet ranges;
-    taco::DecodeTable tab{};
-    int64_t workgroups = 0;
-    for (int t = 0; t < count; ++t) {
-        int64_t n = 0;
-        if (!items[t].out_bf16) return TACO_ERR_NULL;
-        if (int rc = check_shape(items[t].rows, items[t].cols, &n)) return rc;
-        if (int rc = check_sources(items[t].payloads, items[t].scales, k, n, p, &ranges, [&](int i, const void* pl, const void* sc) {
-                tab.src_payload[t * k + i] = pl;
-                tab.src_scales[t * k + i] = sc;
-            }))
-            return rc;
-        if (!aligned16(items[t].out_bf16)) return TACO_ERR_ALIGN;
-        ranges.add_out(items[t].out_bf16, 2u * static_cast<uint64_t>(n));
-        tab.out[t] = items[t].out_bf16;
-        tab.n_elems[t] = n;
-        tab.first[t] = workgroups;
-        workgroups += decode_groups(n, shape);
-    }
-    tab.first[count] = workgroups;
-    if (ranges.clash()) return TACO_ERR_OVERLAP;
-    return launch_decode(tab, count, k, workgroups, p, false, static_cast<hipStream_t>(stream));
+    return decode_batch(count, k, p, false, stream, [&](int t) {
+        return BatchItem{items[t].payloads, items[t].scales, items[t].rows, items[t].cols, items[t].out_bf16, nullptr, nullptr};
+    });
+}
+
+int taco_decompress_sum_compress_batch(const taco_recompress_item* items, int32_t count, int32_t k, const taco_params* p,
+                                       void* stream) {
+    if (!items) return TACO_ERR_NULL;
+    return decode_batch(count, k, p, true, stream, [&](int t) {
+        return BatchItem{items[t].payloads, items[t].scales, items[t].rows, items[t].cols, nullptr, items[t].payload_out,
+                         items[t].scales_out};
+    });
 }
 
 int taco_debug_cvt_e4m3(const void* in_f32, int64_t n, void* out_codes, void* stream) {

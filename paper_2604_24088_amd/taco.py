@@ -27,7 +27,7 @@ TACO_LAYOUT_SPLIT, TACO_LAYOUT_INTERLEAVED = 0, 1
 # every symbol include/taco.h declares, then those of include/taco_debug.h
 EXPORTS = ("taco_default_params", "taco_payload_bytes", "taco_scales_bytes", "taco_compress", "taco_decompress",
            "taco_decompress_sum", "taco_decompress_sum_compress", "taco_compress_batch", "taco_decompress_sum_batch",
-           "taco_strerror", "taco_version", "taco_build_id")
+           "taco_decompress_sum_compress_batch", "taco_strerror", "taco_version", "taco_build_id")
 DEBUG_EXPORTS = ("taco_debug_cvt_e4m3", "taco_debug_copy", "taco_debug_traffic")
 
 
@@ -45,6 +45,12 @@ class taco_compress_item(ctypes.Structure):
 class taco_decode_item(ctypes.Structure):
     _fields_ = [("payloads", ctypes.POINTER(ctypes.c_void_p)), ("scales", ctypes.POINTER(ctypes.c_void_p)),
                 ("rows", ctypes.c_int64), ("cols", ctypes.c_int64), ("out_bf16", ctypes.c_void_p)]
+
+
+class taco_recompress_item(ctypes.Structure):
+    _fields_ = [("payloads", ctypes.POINTER(ctypes.c_void_p)), ("scales", ctypes.POINTER(ctypes.c_void_p)),
+                ("rows", ctypes.c_int64), ("cols", ctypes.c_int64), ("payload_out", ctypes.c_void_p),
+                ("scales_out", ctypes.c_void_p)]
 
 
 class TacoError(RuntimeError):
@@ -91,6 +97,9 @@ def lib() -> ctypes.CDLL:
         L.taco_decompress_sum_batch.restype = c.c_int
         L.taco_decompress_sum_batch.argtypes = [c.POINTER(taco_decode_item), c.c_int32, c.c_int32, c.POINTER(taco_params),
                                                 c.c_void_p]
+        L.taco_decompress_sum_compress_batch.restype = c.c_int
+        L.taco_decompress_sum_compress_batch.argtypes = [c.POINTER(taco_recompress_item), c.c_int32, c.c_int32,
+                                                         c.POINTER(taco_params), c.c_void_p]
         L.taco_build_id.restype = c.c_char_p
         L.taco_build_id.argtypes = []
         L.taco_debug_cvt_e4m3.restype = c.c_int
@@ -363,6 +372,40 @@ def taco_decompress_sum_batch(payloads: Sequence[Sequence[torch.Tensor]], scales
     st = lib().taco_decompress_sum_batch(items, count, k, ctypes.byref(p), _stream_handle(stream))
     _check(st, "taco_decompress_sum_batch")
     return outs
+
+
+def taco_decompress_sum_compress_batch(payloads: Sequence[Sequence[torch.Tensor]], scales, shapes,
+                                       params: Optional[taco_params] = None, payloads_out=None, scales_out=None, stream=None):
+    """taco_decompress_sum_compress of up to TACO_MAX_BATCH tensors in ONE kernel (same k for every tensor).
+    Returns (payloads_out, scales_out) lists."""
+    p = params or taco_default_params()
+    count = len(payloads)
+    _require(1 <= count <= TACO_MAX_BATCH, f"{count} tensors: between 1 and {TACO_MAX_BATCH}")
+    k = len(payloads[0])
+    _require(1 <= k <= TACO_MAX_K and count * k <= TACO_MAX_BATCH_PAYLOADS,
+             f"k = {k}: between 1 and {TACO_MAX_K}, and at most {TACO_MAX_BATCH_PAYLOADS} payloads in all")
+    scales = [list(s) if s is not None else [None] * k for s in (scales if scales is not None else [None] * count)]
+    payloads_out = list(payloads_out) if payloads_out is not None else [None] * count
+    scales_out = list(scales_out) if scales_out is not None else [None] * count
+    _require(len(scales) == count and len(shapes) == count and len(payloads_out) == count and len(scales_out) == count,
+             "one scales list, shape and output pair per tensor")
+    items = (taco_recompress_item * count)()
+    keep = []
+    dev = payloads[0][0].device
+    for t in range(count):
+        _require(len(payloads[t]) == k and len(scales[t]) == k, "every tensor needs the same number of payloads")
+        rows, cols = _rows_cols(tuple(shapes[t]))
+        _check_payload_args(rows * cols, p, payloads[t], scales[t], dev)
+        payloads_out[t], scales_out[t] = _alloc_outputs(rows * cols, p, dev, payloads_out[t], scales_out[t])
+        _check_payload_args(rows * cols, p, [payloads_out[t]], [scales_out[t]], dev)
+        parr, sarr = _pointer_array(payloads[t], k), _pointer_array(scales[t], k)
+        keep.append((parr, sarr))
+        items[t] = taco_recompress_item(ctypes.cast(parr, ctypes.POINTER(ctypes.c_void_p)),
+                                        ctypes.cast(sarr, ctypes.POINTER(ctypes.c_void_p)), rows, cols,
+                                        payloads_out[t].data_ptr(), _ptr_or_null(scales_out[t]))
+    st = lib().taco_decompress_sum_compress_batch(items, count, k, ctypes.byref(p), _stream_handle(stream))
+    _check(st, "taco_decompress_sum_compress_batch")
+    return payloads_out, scales_out
 
 
 def taco_debug_cvt_e4m3(values: torch.Tensor, stream=None) -> torch.Tensor:

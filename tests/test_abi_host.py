@@ -178,6 +178,36 @@ def test_decompress_sum_batch_rejects_bad_arguments():
     assert L.taco_decompress_sum_batch(items([good, (cast(pl), cast(sc), 4, 512, B1 + 16)]), 2, 2, ctypes.byref(p), None) == -12
 
 
+def test_fused_batch_rejects_bad_arguments():
+    L = taco.lib()
+    p = _params()
+    pl = (ctypes.c_void_p * 2)(B0, B1)
+    sc = (ctypes.c_void_p * 2)(B2, B2 + 0x1000)
+    cast = lambda a: ctypes.cast(a, ctypes.POINTER(ctypes.c_void_p))
+
+    def items(entries):
+        arr = (taco.taco_recompress_item * len(entries))()
+        for i, e in enumerate(entries):
+            arr[i] = taco.taco_recompress_item(*e)
+        return arr
+
+    call = L.taco_decompress_sum_compress_batch
+    good = (cast(pl), cast(sc), 4, 512, B2 + 0x100000, B2 + 0x180000)
+    assert call(None, 1, 2, ctypes.byref(p), None) == -1
+    assert call(items([good]), 0, 2, ctypes.byref(p), None) == -13
+    assert call(items([good] * 33), 33, 2, ctypes.byref(p), None) == -13
+    assert call(items([good]), 1, 17, ctypes.byref(p), None) == -5
+    assert call(items([good]), 1, 2, ctypes.byref(_params(tau=0.0)), None) == -9            # the compress half needs tau > 0
+    assert call(items([good, (cast(pl), cast(sc), 4, 512, 0, B2 + 0x190000)]), 2, 2, ctypes.byref(p), None) == -1
+    assert call(items([good, (cast(pl), cast(sc), 4, 512, B2 + 0x110000, None)]), 2, 2, ctypes.byref(p), None) == -1
+    assert call(items([good, (cast(pl), cast(sc), 4, 512, B2 + 0x110000, None)]), 2, 2, ctypes.byref(_params(layout=1)), None) != -1
+    assert call(items([good, (cast(pl), cast(sc), 0, 512, B2 + 0x110000, B2 + 0x190000)]), 2, 2, ctypes.byref(p), None) == -2
+    assert call(items([good, (cast(pl), cast(sc), 4, 512, B2 + 0x110008, B2 + 0x190000)]), 2, 2, ctypes.byref(p), None) == -4
+    # the second tensor's payload over the first tensor's payload, and its scales over a source
+    assert call(items([good, (cast(pl), cast(sc), 4, 512, B2 + 0x100000 + 2032, B2 + 0x190000)]), 2, 2, ctypes.byref(p), None) == -12
+    assert call(items([good, (cast(pl), cast(sc), 4, 512, B2 + 0x110000, B0 + 16)]), 2, 2, ctypes.byref(p), None) == -12
+
+
 @pytest.mark.parametrize("k,status", [(0, -5), (17, -5), (-1, -5)])
 def test_decompress_sum_rejects_bad_k(k, status):
     L = taco.lib()

@@ -100,6 +100,34 @@ def test_decompress_sum_batch_equals_single_calls(oracle, block, layout, impl, k
     P.check_recon(outs[t].view(torch.int16).cpu().numpy().view(np.uint16), ref, block, "batch decode", min_exact=P.RECON_EXACT_MIN_SMALL, acc=acc)
 
 
+@pytest.mark.parametrize("block,layout,impl,k,mode,fmt", [
+    (128, 0, taco.TACO_IMPL_AUTO, 8, 7, 0), (128, 1, taco.TACO_IMPL_AUTO, 4, 7, 0), (256, 0, taco.TACO_IMPL_AUTO, 2, 7, 0),
+    (32, 0, taco.TACO_IMPL_AUTO, 8, 7, 0), (512, 1, taco.TACO_IMPL_AUTO, 3, 7, 0), (64, 0, taco.TACO_IMPL_AUTO, 5, 7, 2),
+    (128, 0, taco.TACO_IMPL_BUTTERFLY, 2, 7, 0), (128, 0, taco.TACO_IMPL_AUTO, 1, 6, 1)])
+def test_fused_batch_equals_single_calls(oracle, block, layout, impl, k, mode, fmt):
+    """taco_decompress_sum_compress_batch: every tensor's output is bit for bit that of the single fused call (which the
+    parity tests hold against the oracle and against the two separate calls)."""
+    p = taco.taco_default_params(block=block, layout=layout, impl=impl, mode=mode, fmt=fmt)
+    sizes = SIZES[:taco.TACO_MAX_BATCH_PAYLOADS // k][:6]
+    payloads, scales, shapes = [], [], []
+    for t, n in enumerate(sizes):
+        enc = [oracle.compress(make(n, 2000 * t + i, 0.02 * (i + 1)), block=block, mode=mode, fmt=fmt) for i in range(k)]
+        if layout:
+            payloads.append([torch.from_numpy(P.interleave(e[0], e[1], block)).to(DEV) for e in enc])
+            scales.append(None)
+        else:
+            payloads.append([torch.from_numpy(e[0]).to(DEV) for e in enc])
+            scales.append([torch.from_numpy(e[1]).to(DEV) for e in enc])
+        shapes.append((n,))
+    bp, bs = taco.taco_decompress_sum_compress_batch(payloads, scales, shapes, p)
+    torch.cuda.synchronize()
+    for t, n in enumerate(sizes):
+        sp, ss = taco.taco_decompress_sum_compress(payloads[t], scales[t], (n,), p)
+        torch.cuda.synchronize()
+        assert torch.equal(bp[t], sp), (t, n)
+        assert layout or torch.equal(bs[t], ss), (t, n)
+
+
 def test_chunks_of_one_tensor_as_a_batch():
     """Row chunks of a tensor (the overlap granularity of Section 4.4.2) as the items of one batched call: the same
     bits as the whole-tensor call, written into the same buffers."""

@@ -44,6 +44,20 @@ def test_two_shot_allreduce_on_one_gpu(oracle, block, layout):
         scs = [None if il else e[1][s * sb:(s + 1) * sb] for e in enc]
         taco.taco_decompress_sum_compress(pls, scs, (shard,), p, gathered_p[s * sb * rec:(s + 1) * sb * rec],
                                           None if il else gathered_s[s * sb:(s + 1) * sb])
+    # the same eight shard reductions as ONE launch (what one GPU standing in for all ranks can batch; on a rank of its
+    # own the batch would be the chunks of its shard): bit for bit the same gathered buffer
+    batched_p = torch.empty_like(gathered_p)
+    batched_s = None if il else torch.empty_like(gathered_s)
+    per = taco.TACO_MAX_BATCH_PAYLOADS // RANKS
+    for s0 in range(0, RANKS, per):
+        part = range(s0, min(s0 + per, RANKS))
+        taco.taco_decompress_sum_compress_batch(
+            [[e[0][s * sb * rec:(s + 1) * sb * rec] for e in enc] for s in part],
+            [None if il else [e[1][s * sb:(s + 1) * sb] for e in enc] for s in part], [(shard,)] * len(part), p,
+            [batched_p[s * sb * rec:(s + 1) * sb * rec] for s in part],
+            [None if il else batched_s[s * sb:(s + 1) * sb] for s in part])
+    torch.cuda.synchronize()
+    assert torch.equal(batched_p, gathered_p) and (il or torch.equal(batched_s, gathered_s))
     # shot 2, receive side: decompress the gathered tensor
     y = taco.taco_decompress(gathered_p, gathered_s, (rows, w.hidden), p)
     torch.cuda.synchronize()
