@@ -10,12 +10,13 @@ last-level cache.  Inputs are resident in HBM before the timed region.
 Prints ONE JSON line.  `value` counts bf16-equivalent bytes: 2N per compressed tensor, 2N per
 decompressed tensor, k*2N for decompress_sum (k tensors decoded); `value_out_basis` counts only bf16
 bytes that really cross HBM; `hbm_frac_step` prices the ALGORITHMIC bytes of the whole step.
-The timed region brackets only the k compress launches of a step with HIP events (the roofline's launch
-duration comes from them); `calls` gives the MEDIAN of each call's duration over the same number of steps
-run once more with events between all calls, on the launch stream.  A launch that follows an event record
-waits about 6 us for the event's marker packet (the kernel trace shows the gap, and kernel durations equal
-to the back-to-back ones), so the in-step times of the two decode calls contain one such gap each, the
-compress time an eighth of one; `ms_per_step_with_events_between_calls` is the step with them.
+The timed region records two HIP events per step: one at its start and one after the compress group, after
+decompress or after decompress_sum, in turn over the steps.  `calls` gives the compress launch time from
+the first kind of step (the roofline's launch duration is its average) and the two decode calls as
+differences of the medians of those intervals: no event sits between the kernels they cover.  A launch that
+follows an event record waits about 6 us for the event's marker packet (the kernel trace shows the gap,
+and kernel durations equal to the back-to-back ones); `calls_with_events_between_calls` and
+`ms_per_step_with_events_between_calls` are the same steps run once more with events around every call.
 `calls_back_to_back` times 16 launches of one call in a row, which is what a kernel
 costs when the host's launch time is not in the way.  `workloads` carries the same two measurements for
 every one of the five benchmark configurations (steps rotate through enough buffer sets to defeat the
@@ -303,15 +304,18 @@ class Bench:
         _, payloads, scales, _, outk = self.cur
         self.decode(payloads, scales, outk)
 
-    def step(self, ev=None, split=True):
-        """ev: four events; all are recorded around the three parts when `split`, else only the two around the compress group."""
+    def step(self, ev=None, split="all"):
+        """ev: four events.  split = "all": recorded around each of the three parts.  split = 0, 1 or 2: only ev[0] at the
+        start of the step and ev[1] after part `split` (compress group, decompress, decompress_sum)."""
         self.cur = self.sets[self.step_no % self.n_sets]
         self.step_no += 1
         for j, part in enumerate(self.parts):
-            if ev and (split or j < 2):
+            if ev and (split == "all" or j == 0):
                 ev[j].record(self.stream)
             part()
-        if ev and split:
+            if ev and split == j:
+                ev[1].record(self.stream)
+        if ev and split == "all":
             ev[3].record(self.stream)
 
     # ---- measurements -------------------------------------------------------------------------
@@ -332,22 +336,35 @@ class Bench:
                 self.step()
             torch.cuda.synchronize()
 
-    def timed_steps(self, steps, warmup, split=True):
-        """Wall time of `steps` steps and the HIP-event times per call.  With split = False only the compress group of a step
-        is bracketed by events (per[1], per[2] come back empty): a launch that follows an event record waits about 6 us for the
-        event's marker packet, which a caller who records no events between its calls does not pay."""
-        torch = self.torch
+    def timed_steps(self, steps, warmup, split="rotate"):
+        """Wall time of `steps` steps and the HIP-event times of their calls, [compress per launch, decompress, decompress_sum],
+        one list each.
+
+        A launch that follows an event record waits about 6 us for the event's marker packet (the kernel trace shows the idle
+        gap), so events BETWEEN the calls of a step stretch the step and the calls behind them.  split = "rotate" therefore
+        records two events per step only: one at its start and one after the compress group, after decompress or after
+        decompress_sum, in turn over the steps; the times of the two decode calls are the differences of the medians of those
+        intervals (first the compress group alone, then with decompress, then with both), with no marker between the kernels
+        they cover.  split = "all" records events around every call of every step (the times then contain the gaps)."""
+        torch, statistics_median = self.torch, statistics.median
         for _ in range(warmup):
             self.step()
+        if steps < 6:
+            split = "all"
         events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for s in range(steps):
-            self.step(events[s], split)
+            self.step(events[s], split if split == "all" else s % 3)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-        per = [[e[j].elapsed_time(e[j + 1]) for e in events] for j in range(3 if split else 1)]
-        per[0] = [v / self.k for v in per[0]]            # per compress launch
+        if split == "all":
+            per = [[e[j].elapsed_time(e[j + 1]) for e in events] for j in range(3)]
+            per[0] = [v / self.k for v in per[0]]        # per compress launch
+            return wall, per
+        upto = [[e[0].elapsed_time(e[1]) for s, e in enumerate(events) if s % 3 == j] for j in range(3)]
+        m = [statistics_median(v) for v in upto]
+        per = [[v / self.k for v in upto[0]], [m[1] - m[0]], [m[2] - m[1]]]
         return wall, per
 
     def back_to_back(self, fn, alg_bytes):
@@ -467,8 +484,7 @@ def call_entry(ms, alg_bytes, bf16_bytes):
 def workload_entry(b, steps, warmup, settle_ms):
     """In-step medians and back-to-back times of one workload (k compress + 1 decompress + 1 decompress_sum(k))."""
     b.settle(settle_ms)
-    wall, _ = b.timed_steps(steps, warmup, split=False)
-    _, per = b.timed_steps(steps, 0)
+    wall, per = b.timed_steps(steps, warmup)
     by, k, n = b.bytes_of(), b.k, b.n
     med = [statistics.median(v) for v in per]
     moved = k * by["compress"] + by["decompress"] + by["sum"]
@@ -485,7 +501,7 @@ def cold_trace(args, taco, torch, W, params):
     """Per-step call times from a cold start: nothing is launched before the first traced step."""
     b = Bench(args, args.workload, params, taco, torch, W, rotate=args.rotate)
     torch.cuda.synchronize()
-    _, per = b.timed_steps(args.cold_trace, 0)
+    _, per = b.timed_steps(args.cold_trace, 0, split="all")
     print(json.dumps({"cold_trace_us": {"workload": b.w.name, "block": b.B,
                                         "compress": [round(v * 1e3, 1) for v in per[0]],
                                         "decompress": [round(v * 1e3, 1) for v in per[1]],
@@ -528,8 +544,8 @@ def main():
               graph=args.graph, batch=args.batch)
     w, k, n = b.w, b.k, b.n
     b.settle(args.settle_ms)
-    wall, per_timed = b.timed_steps(args.steps, args.warmup, split=False)       # THE timed region
-    wall_split, per = b.timed_steps(args.steps, 0)                              # the same steps again with events between all calls
+    wall, per = b.timed_steps(args.steps, args.warmup)                          # THE timed region (two events per step)
+    wall_split, per_marked = b.timed_steps(args.steps, 0, split="all")           # the same steps again with events between all calls
 
     # ---- yardstick outside the timed region: plain copy of 1 GiB (reads 1 GiB, writes 1 GiB)
     xs = b.sets[0][0]
@@ -553,7 +569,8 @@ def main():
     same = b.same_payload_calls() if k > 1 and not args.no_cache_fed else {}
 
     ms_step = wall * 1e3 / args.steps
-    t_comp_avg = sum(per_timed[0]) / len(per_timed[0])   # ms per compress launch, average over the timed region
+    t_comp_avg = sum(per[0]) / len(per[0])               # ms per compress launch, average over the timed region
+    med_marked = [statistics.median(v) for v in per_marked]
     med = [statistics.median(v) for v in per]
     by = b.bytes_of()
     equiv = (k + 1 + k) * 2.0 * n                        # bf16-equivalent bytes per step
@@ -594,6 +611,9 @@ def main():
                   "decompress": call_entry(med[1], by["decompress"], 2.0 * n),
                   f"decompress_sum_k{k}": call_entry(med[2], by["sum"], k * 2.0 * n),
                   f"decompress_sum_compress_k{k} (not in the step)": call_entry(t_fused, by["fused"], k * 2.0 * n)},
+        "calls_with_events_between_calls": {"compress": call_entry(med_marked[0], by["compress"], 2.0 * n),
+                                            "decompress": call_entry(med_marked[1], by["decompress"], 2.0 * n),
+                                            f"decompress_sum_k{k}": call_entry(med_marked[2], by["sum"], k * 2.0 * n)},
         "roofline": {"kernel": (f"compress_mfma_kernel<{max(B // 128, 1)},{max(128 // B, 1)},{'true' if il else 'false'},"
                                 f"{ {'e4m3': 0, 'e5m2': 1, 'int8': 2}[args.format] },{'false' if (args.mode & 6) == 6 else 'true'}>")
                      if on_mfma else f"compress_butterfly_kernel<{B}>",
