@@ -451,7 +451,7 @@ const char* taco_strerror(int status) {
     }
 }
 
-const char* taco_version(void) { return "0.4"; }
+const char* taco_version(void) { return "0.5"; }
 
 const char* taco_build_id(void) {
     // the marker in front lets a build script find the digest in the binary without loading it
