@@ -11,7 +11,10 @@
                    plain copy kernel of known size (taco_debug_copy of 393216 KiB in bench.py), i.e. HBM bytes per launch
   --pmc DIR     output directory of any other   rocprofv3 --pmc <counters> ...   run: mean of every counter per kernel
   --elements / --block / --k   when given, the algorithmic bytes of compress, decompress, decompress_sum(k) and the fused
-                call on a tensor of N elements are printed beside the traffic, with the ratio
+                call on a tensor of N elements are printed beside the traffic, with the ratio; the stats section adds the
+                compress kernel's algorithmic bytes over its average duration as a share of the 8000 GB/s HBM peak, the
+                counter sections add, per kernel, the chip's busy cycles, the matrix cores' busy share and the vector
+                instructions per tile of 2048 elements with their issue share
   --trace DIR   the same directory as --stats (it holds the kernel trace): per kernel, the median duration and the median idle gap
                 before it, apart for launches that follow another kernel (as in a bench step) and launches that follow the same
                 kernel (back-to-back runs); the gap is what HIP-event times between calls contain beside the kernel itself
@@ -158,8 +161,16 @@ def main():
         bench_rows(a.bench, a.workloads)
     if a.stats:
         print("== kernel stats (rocprofv3 --kernel-trace --stats): calls, average / min / max duration in ns, share of GPU time")
-        for name, calls, avg, mn, mx, pct in kernel_stats(a.stats):
+        rows = kernel_stats(a.stats)
+        for name, calls, avg, mn, mx, pct in rows:
             print(f"  {name:78s} calls={calls:5d} avg_ns={avg:10.1f} min_ns={mn:8d} max_ns={mx:8d} pct={pct:5.2f}")
+        if a.elements:
+            per = 1.0 + 8.0 / a.block
+            for name, calls, avg, mn, mx, pct in rows:
+                if name.startswith("compress_"):
+                    alg = (2.0 + per) * a.elements
+                    print(f"  roofline check, {name}: {alg:.0f} algorithmic bytes / {avg / 1e3:.2f} us average = {alg / avg:.0f} GB/s = "
+                          f"{alg / avg / 8000.0:.3f} of 8000 GB/s")
         print()
     if a.trace:
         trace_split(a.trace)
@@ -200,6 +211,18 @@ def main():
             cells = [f"{c} {tab[(kname, grid, c)][1]:.0f}" for c in names if (kname, grid, c) in tab]
             for i in range(0, len(cells), 4):
                 print("      " + "   ".join(f"{x:38s}" for x in cells[i:i + 4]).rstrip())
+            get = lambda c: tab.get((kname, grid, c), (0, 0.0))[1]
+            busy = get("SQ_BUSY_CYCLES") / 32.0                 # the counter sums over the 32 shader engines
+            if busy > 0 and get("SQ_VALU_MFMA_BUSY_CYCLES") > 0:
+                mfma = get("SQ_VALU_MFMA_BUSY_CYCLES") / 1024.0  # per SIMD (256 compute units x 4)
+                line = (f"      derived: busy cycles of the chip {busy / 1e3:.0f} k; matrix cores busy per SIMD {mfma / 1e3:.0f} k = "
+                        f"{mfma / busy:.3f} of them")
+                if a.elements and get("SQ_INSTS_VALU") > 0:
+                    tiles = a.elements / 2048.0
+                    valu = get("SQ_INSTS_VALU")
+                    line += (f"; vector instructions per tile of 2048 elements {valu / tiles:.0f}, at four issue cycles each "
+                             f"{valu / 1024.0 * 4 / 1e3:.0f} k cycles per SIMD = {valu / 1024.0 * 4 / busy:.2f}")
+                print(line)
         print()
     if not (a.stats or a.trace or a.fetch or a.write or a.pmc or a.bench):
         ap.print_help()
